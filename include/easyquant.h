@@ -1,0 +1,164 @@
+/*
+ * easyquant.h -- C ABI of the MI355X (gfx950) EasyQuant quantization library.
+ *
+ * EasyQuant (arXiv 2403.02775) quantizes one weight matrix at a time without any
+ * data (Algorithm 1):
+ *   1. find the (n sigma) outliers of the weight and keep them verbatim (Eq. 3);
+ *   2. for the remaining "normal" values, optimise the quantization range of every
+ *      output channel (or group) with Adam, using the gradient of the
+ *      reconstruction error ||Q[x] - x||^2 with respect to the range (Eq. 2, Sec. 4.2);
+ *   3. quantize the normal values at that range (Eq. 1);
+ *   4. dequantize as  Mask * W + (1 - Mask) * Q[W]  (Eq. 4).
+ * "We store the index and value for all outliers together with the quantized
+ * normal values" (Sec. 5, Implementation) is the output format below.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - Matrices are row-major, ROW = OUTPUT CHANNEL (out_features x in_features), so a
+ *    row is what the paper calls a channel sharing one range (Sec. 5, Setup).  A
+ *    "unit" is one row (group_size = 0) or group_size consecutive elements of a row.
+ *  - Every pointer marked DEVICE is GPU memory owned by the caller; the library
+ *    never allocates, frees or retains device memory.  Every pointer marked HOST is
+ *    read before the call returns.
+ *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream) and return without waiting for it.
+ *  - Return value: EQ_OK or a negative EQ_E_* code for problems visible on the host
+ *    (nothing is enqueued then).  Conditions only the GPU can see are reported in
+ *    the per-matrix DEVICE status word (EQ_S_* bits), valid once the stream is idle.
+ *  - Thread-safe for calls that use distinct outputs and workspaces.
+ */
+#ifndef EASYQUANT_H_
+#define EASYQUANT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported symbol (the library is built with hidden visibility by default) */
+#define EQ_API __attribute__((visibility("default")))
+
+/* element type of W: the paper keeps outliers "in full precision (fp32/fp16/bf16)" (Fig. 1);
+ * this library takes the two 16-bit formats. */
+enum { EQ_F16 = 0, EQ_BF16 = 1 };
+/* EQ_SYMMETRIC is the paper's setting (Sec. 5, Setup).  EQ_ASYMMETRIC is an extension:
+ * an integer zero-point fixed from min/max at initialisation, only the range optimised. */
+enum { EQ_SYMMETRIC = 0, EQ_ASYMMETRIC = 1 };
+/* scope of mean / sigma in Eq. 3: one row (default), one unit, or the whole matrix (Eq. 3 as printed). */
+enum { EQ_STAT_ROW = 0, EQ_STAT_GROUP = 1, EQ_STAT_MATRIX = 2 };
+/* which iterate of the optimisation is returned: the best of the trajectory (step 0
+ * included, so never worse than min/max scaling), or the last one ("we choose the
+ * quantization ranges from step 100 / 500", Sec. 5, Setup). */
+enum { EQ_SELECT_BEST = 0, EQ_SELECT_LAST = 1 };
+
+/* return codes */
+enum {
+  EQ_OK = 0,
+  EQ_E_NULL = -1,         /* a required pointer is NULL */
+  EQ_E_SHAPE = -2,        /* rows/cols/ld/group_size inconsistent (see eq_quantize_matrix) */
+  EQ_E_PARAM = -3,        /* bits, mode, dtype, scope, select or a hyper-parameter out of range */
+  EQ_E_ALIGN = -4,        /* W or W_out not 16-byte aligned, codes not 4-byte aligned */
+  EQ_E_WORKSPACE = -5,    /* workspace NULL, misaligned (256 B) or smaller than eq_workspace_bytes() */
+  EQ_E_UNSUPPORTED = -6,  /* a row too long for on-chip staging (cols > EQ_MAX_COLS) */
+  EQ_E_HIP = -7           /* a HIP runtime call failed (launch, copy); eq_last_hip_error() has the code */
+};
+/* bits of the DEVICE status word */
+enum {
+  EQ_S_OUTLIER_OVERFLOW = 1, /* more outliers than out_capacity: out_row_ptr holds the true
+                                counts (so the caller can re-size and call again); out_col /
+                                out_val are incomplete */
+  EQ_S_NONFINITE = 2         /* W holds an Inf or NaN: every output of that matrix is unspecified */
+};
+
+#define EQ_MAX_COLS 65536
+
+typedef struct eq_params {
+  int32_t dtype;       /* EQ_F16 | EQ_BF16 */
+  int32_t bits;        /* 2..8 (the paper evaluates 4) */
+  int32_t group_size;  /* 0 = one range per row (the paper's per-channel setting); else a
+                          multiple of 32 that divides cols (finer grouping, Sec. 5.1) */
+  int32_t mode;        /* EQ_SYMMETRIC | EQ_ASYMMETRIC */
+  int32_t stat_scope;  /* EQ_STAT_* */
+  float   n_sigma;     /* threshold n of Eq. 3; 2.5..3 in the paper; +inf disables outliers */
+  int32_t iters;       /* Adam steps T on the range (100 / 500 in the paper); 0 = outlier-aware RTN */
+  float   lr;          /* Adam step size on the range (1e-3 / 1e-4 in the paper) */
+  float   beta1, beta2, eps; /* Adam moments and epsilon (paper silent: 0.9, 0.999, 1e-8) */
+  int32_t select;      /* EQ_SELECT_* */
+} eq_params;
+
+/* Quantized form of one rows x cols matrix.  All pointers DEVICE, caller-owned.
+ * units_per_row = 1 (group_size 0) or cols / group_size. */
+typedef struct eq_qmatrix {
+  uint32_t* codes;        /* rows * eq_code_words_per_row(cols, bits) words.  Per row, a
+                             little-endian bit stream: the unsigned code of column j sits in
+                             bits [bits*j, bits*j+bits) of the row's stream (4-bit: even
+                             column in the low nibble); rows are padded to whole words.
+                             unsigned code = signed level of Eq. 1 + zero_point; an outlier's
+                             slot holds zero_point (level 0). */
+  float*    scales;       /* rows * units_per_row: s of Eq. 1 (range / D), binary32 */
+  uint8_t*  zero_points;  /* rows * units_per_row: 2^(bits-1)-1 in symmetric mode */
+  uint32_t* out_row_ptr;  /* rows + 1: exclusive prefix sum of outliers per row (CSR) */
+  uint32_t* out_col;      /* out_capacity: column of each outlier, ascending within a row */
+  uint16_t* out_val;      /* out_capacity: the outlier's raw 16-bit pattern (lossless) */
+  int64_t   out_capacity; /* entries available in out_col / out_val */
+  int32_t*  status;       /* one word, EQ_S_* bits; written by the call (0 = fine) */
+} eq_qmatrix;
+
+/* Algorithm 1, "Quantize", for one matrix.
+ *   W      DEVICE, rows x cols elements of p->dtype, row stride ld elements (ld >= cols,
+ *          ld % 8 == 0, W 16-byte aligned).  Read only.
+ *   rows   >= 0, cols >= 0 with cols % 8 == 0 (cols % 32 == 0 when group_size != 0) and
+ *          cols <= EQ_MAX_COLS.  rows == 0 or cols == 0 enqueues nothing but still
+ *          clears status / out_row_ptr.
+ *   p      HOST.   out  HOST struct of DEVICE pointers (all non-NULL; out_col / out_val
+ *          may be NULL when out_capacity == 0).
+ *   workspace  DEVICE scratch, 256-byte aligned, at least eq_workspace_bytes() bytes;
+ *          contents are undefined afterwards; must not be shared by calls that overlap.
+ * The outlier list comes out sorted by (row, column) whatever the execution order.
+ * Same inputs give bit-identical outputs on every run. */
+EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,
+                       const eq_params* p, const eq_qmatrix* out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The same for n independent matrices in ONE pass over the GPU ("each weight can be
+ * quantized in parallel", Sec. 5, Implementation): W, rows, cols, ld, outs are HOST
+ * arrays of length n; all matrices share p.  n == 0 is a no-op. */
+EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols,
+                      const int64_t* ld, const eq_params* p, const eq_qmatrix* outs,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Algorithm 1, "Dequantize" (Eq. 4): W_out[i][j] = round_to_dtype(scale * (code - zero_point))
+ * for normal values, the stored raw pattern for outliers.  W_out DEVICE, rows x cols of
+ * p->dtype with row stride ld_out (>= cols, % 8 == 0, 16-byte aligned).  Only dtype, bits
+ * and group_size of p are read.  q->status is not touched. */
+EQ_API int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p,
+                  void* W_out, int64_t ld_out, void* hip_stream);
+
+/* Bytes of workspace eq_quantize_batch needs for these shapes (HOST arrays of length n);
+ * eq_quantize_matrix is the n == 1 case.  0 on invalid arguments. */
+EQ_API size_t eq_workspace_bytes(int32_t n, const int64_t* rows, const int64_t* cols,
+                          const int64_t* out_capacity, const eq_params* p);
+
+/* Words per row of the packed code stream: ceil(cols * bits / 32). */
+EQ_API int64_t eq_code_words_per_row(int64_t cols, int32_t bits);
+
+/* An out_capacity that can never overflow: by Chebyshev's inequality at most 1/n^2 of a
+ * statistic scope lies n sigma from its mean (Eq. 3), so rows*cols/n^2 rounded up per row
+ * (rows*cols when n <= 1).  Typical weights need 0.3-1 % (Tables 8-9). */
+EQ_API int64_t eq_outlier_capacity_bound(int64_t rows, int64_t cols, float n_sigma);
+
+/* Fills *p with the paper's BLOOM setting: 4 bits, per-channel, symmetric, n = 3,
+ * Adam lr 1e-3 for 100 steps (Sec. 5, Setup), fp16, row statistics, best iterate. */
+EQ_API void eq_default_params(eq_params* p);
+
+/* Static description of a return code. */
+EQ_API const char* eq_strerror(int code);
+/* hipError_t of the most recent EQ_E_HIP on this thread (0 if none). */
+EQ_API int eq_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EASYQUANT_H_ */

@@ -1,0 +1,203 @@
+"""ctypes binding of libeasyquant.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+EQ_F16, EQ_BF16 = 0, 1
+EQ_SYMMETRIC, EQ_ASYMMETRIC = 0, 1
+EQ_STAT_ROW, EQ_STAT_GROUP, EQ_STAT_MATRIX = 0, 1, 2
+EQ_SELECT_BEST, EQ_SELECT_LAST = 0, 1
+EQ_S_OUTLIER_OVERFLOW, EQ_S_NONFINITE = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libeasyquant.so")
+
+
+class EasyQuantError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {eq_strerror(code)} ({code})")
+        self.code = code
+
+
+class _CParams(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("bits", C.c_int32), ("group_size", C.c_int32), ("mode", C.c_int32),
+                ("stat_scope", C.c_int32), ("n_sigma", C.c_float), ("iters", C.c_int32), ("lr", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("select", C.c_int32)]
+
+
+class _CQMatrix(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("scales", C.c_void_p), ("zero_points", C.c_void_p),
+                ("out_row_ptr", C.c_void_p), ("out_col", C.c_void_p), ("out_val", C.c_void_p),
+                ("out_capacity", C.c_int64), ("status", C.c_void_p)]
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: build it with `python -m paper_2403_02775_amd.build` "
+                              "(hipcc, gfx950); this package has no CPU fallback")
+        L = C.CDLL(path)
+        L.eq_quantize_matrix.restype = C.c_int
+        L.eq_quantize_matrix.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.POINTER(_CParams),
+                                         C.POINTER(_CQMatrix), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.eq_quantize_batch.restype = C.c_int
+        L.eq_quantize_batch.argtypes = [C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                        C.POINTER(C.c_int64), C.POINTER(_CParams), C.POINTER(_CQMatrix), C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
+        L.eq_dequantize.restype = C.c_int
+        L.eq_dequantize.argtypes = [C.POINTER(_CQMatrix), C.c_int64, C.c_int64, C.POINTER(_CParams), C.c_void_p,
+                                    C.c_int64, C.c_void_p]
+        L.eq_workspace_bytes.restype = C.c_size_t
+        L.eq_workspace_bytes.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                         C.POINTER(_CParams)]
+        L.eq_code_words_per_row.restype = C.c_int64
+        L.eq_code_words_per_row.argtypes = [C.c_int64, C.c_int32]
+        L.eq_outlier_capacity_bound.restype = C.c_int64
+        L.eq_outlier_capacity_bound.argtypes = [C.c_int64, C.c_int64, C.c_float]
+        L.eq_default_params.restype = None
+        L.eq_default_params.argtypes = [C.POINTER(_CParams)]
+        L.eq_strerror.restype = C.c_char_p
+        L.eq_strerror.argtypes = [C.c_int]
+        L.eq_last_hip_error.restype = C.c_int
+        L.eq_last_hip_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+@dataclass
+class Params:
+    """Mirror of `eq_params` (defaults = eq_default_params: the paper's BLOOM setting)."""
+    dtype: int = EQ_F16
+    bits: int = 4
+    group_size: int = 0
+    mode: int = EQ_SYMMETRIC
+    stat_scope: int = EQ_STAT_ROW
+    n_sigma: float = 3.0
+    iters: int = 100
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    select: int = EQ_SELECT_BEST
+
+    def c(self) -> _CParams:
+        return _CParams(self.dtype, self.bits, self.group_size, self.mode, self.stat_scope, self.n_sigma, self.iters,
+                        self.lr, self.beta1, self.beta2, self.eps, self.select)
+
+
+@dataclass
+class QMatrix:
+    """Mirror of `eq_qmatrix`: device tensors owned by the caller."""
+    codes: torch.Tensor        # int32  [rows, words_per_row]
+    scales: torch.Tensor       # float32 [rows, units_per_row]
+    zero_points: torch.Tensor  # uint8  [rows, units_per_row]
+    out_row_ptr: torch.Tensor  # int32  [rows + 1]   (bit pattern of uint32)
+    out_col: torch.Tensor      # int32  [capacity]
+    out_val: torch.Tensor      # int16  [capacity]   (raw 16-bit patterns)
+    status: torch.Tensor       # int32  [1]
+
+    @property
+    def capacity(self) -> int:
+        return int(self.out_col.numel())
+
+    def c(self) -> _CQMatrix:
+        cap = self.capacity
+        return _CQMatrix(self.codes.data_ptr(), self.scales.data_ptr(), self.zero_points.data_ptr(),
+                         self.out_row_ptr.data_ptr(), self.out_col.data_ptr() if cap else None,
+                         self.out_val.data_ptr() if cap else None, cap, self.status.data_ptr())
+
+
+def eq_strerror(code: int) -> str:
+    return lib().eq_strerror(int(code)).decode()
+
+
+def eq_code_words_per_row(cols: int, bits: int) -> int:
+    return int(lib().eq_code_words_per_row(cols, bits))
+
+
+def eq_outlier_capacity_bound(rows: int, cols: int, n_sigma: float) -> int:
+    return int(lib().eq_outlier_capacity_bound(rows, cols, n_sigma))
+
+
+def eq_workspace_bytes(rows: Sequence[int], cols: Sequence[int], capacities: Sequence[int], p: Params) -> int:
+    n = len(rows)
+    A = C.c_int64 * max(n, 1)
+    cp = p.c()
+    return int(lib().eq_workspace_bytes(n, A(*rows), A(*cols), A(*capacities), C.byref(cp)))
+
+
+def alloc_outputs(rows: int, cols: int, p: Params, capacity: int, device) -> QMatrix:
+    """Allocates the output tensors of one matrix (device memory comes from PyTorch)."""
+    upr = 1 if p.group_size == 0 else cols // p.group_size
+    wpr = (cols * p.bits + 31) // 32
+    return QMatrix(
+        codes=torch.empty((rows, wpr), dtype=torch.int32, device=device),
+        scales=torch.empty((rows, upr), dtype=torch.float32, device=device),
+        zero_points=torch.empty((rows, upr), dtype=torch.uint8, device=device),
+        out_row_ptr=torch.empty(rows + 1, dtype=torch.int32, device=device),
+        out_col=torch.empty(capacity, dtype=torch.int32, device=device),
+        out_val=torch.empty(capacity, dtype=torch.int16, device=device),
+        status=torch.empty(1, dtype=torch.int32, device=device),
+    )
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check_w(W: torch.Tensor, p: Params):
+    want = torch.float16 if p.dtype == EQ_F16 else torch.bfloat16
+    if W.dtype != want or W.dim() != 2 or W.stride(1) != 1 or not W.is_cuda:
+        raise ValueError("W must be a 2-D CUDA tensor of the dtype named in the parameters, unit stride along columns")
+
+
+def eq_quantize_matrix(W: torch.Tensor, p: Params, out: QMatrix, workspace: torch.Tensor, stream=None) -> None:
+    _check_w(W, p)
+    rows, cols = W.shape
+    cp, cq = p.c(), out.c()
+    rc = lib().eq_quantize_matrix(W.data_ptr(), rows, cols, W.stride(0) if rows > 1 else max(cols, W.stride(0)),
+                                  C.byref(cp), C.byref(cq), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                  _stream_ptr(stream))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_quantize_matrix")
+
+
+def eq_quantize_batch(Ws: List[torch.Tensor], p: Params, outs: List[QMatrix], workspace: torch.Tensor, stream=None) -> None:
+    n = len(Ws)
+    for W in Ws:
+        _check_w(W, p)
+    PA, IA, QA = C.c_void_p * max(n, 1), C.c_int64 * max(n, 1), _CQMatrix * max(n, 1)
+    rows = [int(W.shape[0]) for W in Ws]
+    cols = [int(W.shape[1]) for W in Ws]
+    lds = [int(W.stride(0)) if W.shape[0] > 1 else max(int(W.shape[1]), int(W.stride(0))) for W in Ws]
+    cp = p.c()
+    rc = lib().eq_quantize_batch(n, PA(*[W.data_ptr() for W in Ws]), IA(*rows), IA(*cols), IA(*lds), C.byref(cp),
+                                 QA(*[o.c() for o in outs]), workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_quantize_batch")
+
+
+def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tensor, stream=None) -> None:
+    _check_w(W_out, p)
+    cp, cq = p.c(), q.c()
+    rc = lib().eq_dequantize(C.byref(cq), rows, cols, C.byref(cp), W_out.data_ptr(),
+                             W_out.stride(0) if rows > 1 else max(cols, W_out.stride(0)), _stream_ptr(stream))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_dequantize")

@@ -1,0 +1,289 @@
+// Host side of the C ABI declared in include/easyquant.h: argument checks, workspace
+// carving, descriptor upload and kernel launches.  Every step of the quantization path
+// runs in the kernels; nothing here touches weight data.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "easyquant.h"
+#include "eq_common.h"
+#include "eq_generic.h"
+#include "eq_post.h"
+#include "eq_rowstage.h"
+
+namespace {
+
+using namespace eq;
+
+thread_local int g_last_hip_error = 0;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr int kMatrixStatParts = 1024;   // workgroups of the whole-matrix statistics pre-pass
+
+bool params_ok(const eq_params* p) {
+  if (p->dtype != EQ_F16 && p->dtype != EQ_BF16) return false;
+  if (p->bits < 2 || p->bits > 8) return false;
+  if (p->mode != EQ_SYMMETRIC && p->mode != EQ_ASYMMETRIC) return false;
+  if (p->stat_scope < EQ_STAT_ROW || p->stat_scope > EQ_STAT_MATRIX) return false;
+  if (p->select != EQ_SELECT_BEST && p->select != EQ_SELECT_LAST) return false;
+  if (p->iters < 0 || p->group_size < 0) return false;
+  if (!(p->n_sigma >= 0.0f)) return false;                 // NaN or negative
+  if (!(p->lr >= 0.0f) || !std::isfinite(p->lr)) return false;
+  if (!(p->beta1 >= 0.0f && p->beta1 < 1.0f) || !(p->beta2 >= 0.0f && p->beta2 < 1.0f)) return false;
+  if (!(p->eps >= 0.0f) || !std::isfinite(p->eps)) return false;
+  return true;
+}
+
+int shape_check(int64_t rows, int64_t cols, int64_t ld, const eq_params* p) {
+  if (rows < 0 || cols < 0 || rows > 0x7FFFFFFF) return EQ_E_SHAPE;
+  if (cols % 8) return EQ_E_SHAPE;
+  if (cols > EQ_MAX_COLS) return EQ_E_UNSUPPORTED;
+  if (ld < cols || ld % 8) return EQ_E_SHAPE;
+  if (p->group_size) {
+    if (p->group_size % 32 || cols % p->group_size) return EQ_E_SHAPE;
+  }
+  return EQ_OK;
+}
+
+KParams make_kparams(const eq_params* p) {
+  KParams k;
+  std::memset(&k, 0, sizeof(k));
+  k.dtype = p->dtype; k.bits = p->bits; k.mode = p->mode; k.scope = p->stat_scope;
+  k.select = p->select; k.iters = p->iters;
+  k.L = (1 << p->bits) - 1;
+  k.zsym = (1 << (p->bits - 1)) - 1;
+  k.D = p->mode == EQ_SYMMETRIC ? (float)k.zsym : (float)k.L;
+  k.n = (double)p->n_sigma;
+  k.lr = (double)p->lr; k.b1 = (double)p->beta1; k.b2 = (double)p->beta2; k.eps = (double)p->eps;
+  return k;
+}
+
+// Byte offsets of everything that lives in the workspace.
+struct Plan {
+  size_t descs = 0;                     // MatDesc[n]
+  std::vector<size_t> cursor, row_count, row_stage, st_col, st_val, mat_stats, mat_partial;
+  size_t total = 0;
+};
+
+int64_t clamp_capacity(int64_t c) { return c < 0 ? 0 : (c > 0xFFFFFFFEll ? 0xFFFFFFFEll : c); }
+
+Plan make_plan(int32_t n, const int64_t* rows, const int64_t* /*cols*/, const int64_t* cap, const eq_params* p) {
+  Plan pl;
+  size_t off = 0;
+  pl.descs = off;
+  off = align_up(off + sizeof(MatDesc) * (size_t)n, 256);
+  for (int32_t i = 0; i < n; ++i) {
+    const size_t r = (size_t)rows[i];
+    const size_t c = (size_t)clamp_capacity(cap[i]);
+    pl.cursor.push_back(off);      off = align_up(off + 8, 256);
+    pl.row_count.push_back(off);   off = align_up(off + 4 * r, 256);
+    pl.row_stage.push_back(off);   off = align_up(off + 4 * r, 256);
+    pl.st_col.push_back(off);      off = align_up(off + 4 * c, 256);
+    pl.st_val.push_back(off);      off = align_up(off + 2 * c, 256);
+    if (p->stat_scope == EQ_STAT_MATRIX) {
+      pl.mat_stats.push_back(off);   off = align_up(off + 16, 256);
+      pl.mat_partial.push_back(off); off = align_up(off + 8 * (size_t)kMatrixStatParts, 256);
+    } else {
+      pl.mat_stats.push_back(0);
+      pl.mat_partial.push_back(0);
+    }
+  }
+  pl.total = off;
+  return pl;
+}
+
+#define EQ_HIP(call)                                  \
+  do {                                                \
+    hipError_t e_ = (call);                           \
+    if (e_ != hipSuccess) {                           \
+      g_last_hip_error = (int)e_;                     \
+      return EQ_E_HIP;                                \
+    }                                                 \
+  } while (0)
+
+template <int DT>
+int launch_all(int32_t n, const MatDesc* dmats, const std::vector<MatDesc>& h, const KParams& kp, hipStream_t st) {
+  int32_t max_rows = 0, max_cols = 0;
+  for (const MatDesc& m : h) {
+    if (m.cols == 0) continue;
+    max_rows = std::max(max_rows, m.rows);
+    max_cols = std::max(max_cols, m.cols);
+  }
+  hipLaunchKernelGGL(reset_state, dim3((n + 255) / 256), dim3(256), 0, st, dmats, n);
+  EQ_HIP(hipGetLastError());
+  if (max_rows > 0) {
+    if (kp.scope == EQ_STAT_MATRIX) {
+      for (int pass = 0; pass < 2; ++pass) {
+        hipLaunchKernelGGL(matrix_partial_sums<DT>, dim3(kMatrixStatParts, n), dim3(kThreads), 0, st, dmats, pass);
+        EQ_HIP(hipGetLastError());
+        hipLaunchKernelGGL(matrix_finish_sums, dim3(n), dim3(kThreads), 0, st, dmats, pass, kMatrixStatParts);
+        EQ_HIP(hipGetLastError());
+      }
+    }
+    const size_t lds = 256 + (size_t)max_cols * 2 + (size_t)max_cols / 8;
+    static thread_local size_t lds_set[2] = {0, 0};
+    if (lds > 65536 && lds > lds_set[DT]) {
+      EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_rows_generic<DT>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      lds_set[DT] = lds;
+    }
+    hipLaunchKernelGGL(quantize_rows_generic<DT>, dim3(max_rows, n), dim3(kThreads), lds, st, dmats, kp);
+    EQ_HIP(hipGetLastError());
+  }
+  hipLaunchKernelGGL(scan_row_counts, dim3(n), dim3(kThreads), 0, st, dmats);
+  EQ_HIP(hipGetLastError());
+  if (max_rows > 0) {
+    hipLaunchKernelGGL(gather_outliers, dim3((max_rows + kWaves - 1) / kWaves, n), dim3(kThreads), 0, st, dmats);
+    EQ_HIP(hipGetLastError());
+  }
+  return EQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void eq_default_params(eq_params* p) {
+  if (!p) return;
+  p->dtype = EQ_F16; p->bits = 4; p->group_size = 0; p->mode = EQ_SYMMETRIC; p->stat_scope = EQ_STAT_ROW;
+  p->n_sigma = 3.0f; p->iters = 100; p->lr = 1e-3f; p->beta1 = 0.9f; p->beta2 = 0.999f; p->eps = 1e-8f;
+  p->select = EQ_SELECT_BEST;
+}
+
+const char* eq_strerror(int code) {
+  switch (code) {
+    case EQ_OK: return "ok";
+    case EQ_E_NULL: return "a required pointer is NULL";
+    case EQ_E_SHAPE: return "inconsistent rows / cols / ld / group_size";
+    case EQ_E_PARAM: return "parameter out of range";
+    case EQ_E_ALIGN: return "pointer not sufficiently aligned";
+    case EQ_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case EQ_E_UNSUPPORTED: return "row too long for on-chip staging";
+    case EQ_E_HIP: return "HIP runtime call failed";
+    default: return "unknown error code";
+  }
+}
+
+int eq_last_hip_error(void) { return g_last_hip_error; }
+
+int64_t eq_code_words_per_row(int64_t cols, int32_t bits) {
+  if (cols < 0 || bits < 1 || bits > 32) return 0;
+  return (cols * bits + 31) / 32;
+}
+
+int64_t eq_outlier_capacity_bound(int64_t rows, int64_t cols, float n_sigma) {
+  if (rows <= 0 || cols <= 0) return 0;
+  if (!(n_sigma > 1.0f)) return rows * cols;
+  const double per_row = std::floor((double)cols / ((double)n_sigma * (double)n_sigma)) + 1.0;
+  const double v = std::fmin(per_row, (double)cols) * (double)rows;
+  return (int64_t)v;
+}
+
+size_t eq_workspace_bytes(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
+                          const eq_params* p) {
+  if (n < 0 || !p || (n > 0 && (!rows || !cols || !out_capacity))) return 0;
+  if (!params_ok(p)) return 0;
+  for (int32_t i = 0; i < n; ++i)
+    if (rows[i] < 0 || cols[i] < 0 || rows[i] > 0x7FFFFFFF) return 0;
+  return make_plan(n, rows, cols, out_capacity, p).total + 256;
+}
+
+int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols, const int64_t* ld,
+                      const eq_params* p, const eq_qmatrix* outs, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  if (n < 0 || n > 65535) return EQ_E_SHAPE;
+  if (n == 0) return EQ_OK;
+  if (!W || !rows || !cols || !ld || !p || !outs) return EQ_E_NULL;
+  if (!params_ok(p)) return EQ_E_PARAM;
+  std::vector<int64_t> caps((size_t)n);
+  for (int32_t i = 0; i < n; ++i) {
+    const int rc = shape_check(rows[i], cols[i], ld[i], p);
+    if (rc != EQ_OK) return rc;
+    const eq_qmatrix& o = outs[i];
+    if (!o.out_row_ptr || !o.status) return EQ_E_NULL;
+    if (o.out_capacity < 0) return EQ_E_SHAPE;
+    const bool empty = rows[i] == 0 || cols[i] == 0;
+    if (!empty && (!W[i] || !o.codes || !o.scales || !o.zero_points)) return EQ_E_NULL;
+    if (o.out_capacity > 0 && (!o.out_col || !o.out_val)) return EQ_E_NULL;
+    if (((uintptr_t)W[i] & 15) || ((uintptr_t)o.codes & 3) || ((uintptr_t)o.scales & 3) ||
+        ((uintptr_t)o.out_row_ptr & 3) || ((uintptr_t)o.out_col & 3) || ((uintptr_t)o.out_val & 1) ||
+        ((uintptr_t)o.status & 3))
+      return EQ_E_ALIGN;
+    caps[(size_t)i] = o.out_capacity;
+  }
+  const Plan pl = make_plan(n, rows, cols, caps.data(), p);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return EQ_E_WORKSPACE;
+
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  std::vector<MatDesc> h((size_t)n);
+  for (int32_t i = 0; i < n; ++i) {
+    MatDesc& m = h[(size_t)i];
+    std::memset(&m, 0, sizeof(m));
+    const eq_qmatrix& o = outs[i];
+    m.W = static_cast<const uint16_t*>(W[i]);
+    m.codes = o.codes; m.scales = o.scales; m.zps = o.zero_points;
+    m.out_row_ptr = o.out_row_ptr; m.out_col = o.out_col; m.out_val = o.out_val; m.status = o.status;
+    m.cursor = reinterpret_cast<unsigned long long*>(ws + pl.cursor[(size_t)i]);
+    m.row_count = reinterpret_cast<uint32_t*>(ws + pl.row_count[(size_t)i]);
+    m.row_stage = reinterpret_cast<uint32_t*>(ws + pl.row_stage[(size_t)i]);
+    m.st_col = reinterpret_cast<uint32_t*>(ws + pl.st_col[(size_t)i]);
+    m.st_val = reinterpret_cast<uint16_t*>(ws + pl.st_val[(size_t)i]);
+    if (p->stat_scope == EQ_STAT_MATRIX) {
+      m.mat_stats = reinterpret_cast<double*>(ws + pl.mat_stats[(size_t)i]);
+      m.mat_partial = reinterpret_cast<double*>(ws + pl.mat_partial[(size_t)i]);
+    }
+    m.ld = ld[i];
+    m.capacity = clamp_capacity(o.out_capacity);
+    m.rows = (int32_t)rows[i];
+    m.cols = (int32_t)cols[i];
+    m.G = p->group_size ? p->group_size : (int32_t)cols[i];
+    m.upr = m.G ? m.cols / m.G : 0;
+    m.words_per_row = (int32_t)eq_code_words_per_row(cols[i], p->bits);
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  MatDesc* dmats = reinterpret_cast<MatDesc*>(ws + pl.descs);
+  // pageable source: the runtime stages the bytes before returning, so `h` may die with this frame
+  EQ_HIP(hipMemcpyAsync(dmats, h.data(), sizeof(MatDesc) * (size_t)n, hipMemcpyHostToDevice, st));
+  const KParams kp = make_kparams(p);
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, h, kp, st) : launch_all<EQ_BF16>(n, dmats, h, kp, st);
+}
+
+int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,
+                       const eq_qmatrix* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!out) return EQ_E_NULL;
+  return eq_quantize_batch(1, &W, &rows, &cols, &ld, p, out, workspace, workspace_bytes, hip_stream);
+}
+
+int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p, void* W_out, int64_t ld_out,
+                  void* hip_stream) {
+  if (!q || !p) return EQ_E_NULL;
+  if (p->dtype != EQ_F16 && p->dtype != EQ_BF16) return EQ_E_PARAM;
+  if (p->bits < 2 || p->bits > 8 || p->group_size < 0) return EQ_E_PARAM;
+  if (rows < 0 || cols < 0 || rows > 0x7FFFFFFF || cols % 8 || ld_out < cols || ld_out % 8) return EQ_E_SHAPE;
+  if (cols > EQ_MAX_COLS) return EQ_E_UNSUPPORTED;
+  if (p->group_size && (p->group_size % 32 || cols % p->group_size)) return EQ_E_SHAPE;
+  if (rows == 0 || cols == 0) return EQ_OK;
+  if (!W_out || !q->codes || !q->scales || !q->zero_points || !q->out_row_ptr) return EQ_E_NULL;
+  if (((uintptr_t)W_out & 15) || ((uintptr_t)q->codes & 3)) return EQ_E_ALIGN;
+  DeqDesc d;
+  d.codes = q->codes; d.scales = q->scales; d.zps = q->zero_points;
+  d.out_row_ptr = q->out_row_ptr; d.out_col = q->out_col; d.out_val = q->out_val;
+  d.W = static_cast<uint16_t*>(W_out);
+  d.ld = ld_out; d.rows = (int32_t)rows; d.cols = (int32_t)cols;
+  d.G = p->group_size ? p->group_size : (int32_t)cols;
+  d.upr = d.cols / d.G;
+  d.words_per_row = (int32_t)eq_code_words_per_row(cols, p->bits);
+  d.bits = p->bits;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (p->dtype == EQ_F16)
+    hipLaunchKernelGGL(dequantize_rows<EQ_F16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
+  else
+    hipLaunchKernelGGL(dequantize_rows<EQ_BF16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
+  EQ_HIP(hipGetLastError());
+  return EQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,159 @@
+// Small kernels around the main pass: state reset, the CSR finish of the outlier list,
+// whole-matrix statistics, and the dequantizer of Eq. 4.
+#pragma once
+
+#include "eq_common.h"
+
+namespace eq {
+
+// Reset of the per-matrix cursor and status word (a kernel rather than a memset, so the
+// whole call can be recorded into a HIP graph).
+__global__ void reset_state(const MatDesc* __restrict__ mats, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  *mats[i].cursor = 0ull;
+  *mats[i].status = 0;
+  if (mats[i].rows == 0 || mats[i].cols == 0) {
+    for (int r = 0; r <= mats[i].rows; ++r) mats[i].out_row_ptr[r] = 0u;
+  }
+}
+
+// out_row_ptr = exclusive prefix sum of the per-row outlier counts.  One workgroup per matrix.
+__global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __restrict__ mats) {
+  __shared__ uint32_t wtot[kWaves];
+  const MatDesc md = mats[blockIdx.x];
+  if (md.cols == 0) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  uint32_t running = 0;
+  for (int32_t r0 = 0; r0 < md.rows; r0 += kThreads) {
+    const int32_t r = r0 + (int32_t)threadIdx.x;
+    const uint32_t c = r < md.rows ? md.row_count[r] : 0u;
+    uint32_t inc = c;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const uint32_t t = __shfl_up(inc, o);
+      if (lane >= (uint32_t)o) inc += t;
+    }
+    if (lane == kWave - 1) wtot[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t t = wtot[w];
+      if ((uint32_t)w < wave) before += t;
+      total += t;
+    }
+    if (r < md.rows) md.out_row_ptr[r] = running + before + (inc - c);
+    running += total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) md.out_row_ptr[md.rows] = running;
+}
+
+// Moves each row's run of outliers from the staging area (arrival order of the rows) to its
+// CSR position.  One wavefront per row; blockIdx.y = matrix.
+__global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats) {
+  const MatDesc md = mats[blockIdx.y];
+  const int64_t row = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (row >= md.rows || md.cols == 0) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t cnt = md.row_count[row];
+  const uint32_t src = md.row_stage[row];
+  const uint32_t dst = md.out_row_ptr[row];
+  if (src == 0xFFFFFFFFu || (unsigned long long)dst + cnt > (unsigned long long)md.capacity) return;
+  for (uint32_t i = lane; i < cnt; i += kWave) {
+    md.out_col[dst + i] = md.st_col[src + i];
+    md.out_val[dst + i] = md.st_val[src + i];
+  }
+}
+
+// ---- whole-matrix statistics (Eq. 3 as printed: mean and sigma of W) ---------------------
+// Pass 1: per-workgroup partial sums of x; pass 2: of (x - mean)^2; a one-workgroup finish
+// after each.  Partials are combined in a fixed order, so the result does not depend on timing.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void matrix_partial_sums(const MatDesc* __restrict__ mats, int pass) {
+  __shared__ double red[kWaves];
+  const MatDesc md = mats[blockIdx.y];
+  if (md.rows == 0 || md.cols == 0) return;
+  const double mu = pass ? md.mat_stats[0] : 0.0;
+  const uint32_t nchunks = (uint32_t)md.cols >> 3;
+  double s = 0.0;
+  for (int64_t row = blockIdx.x; row < md.rows; row += gridDim.x) {
+    const uint4* src = reinterpret_cast<const uint4*>(md.W + row * md.ld);
+    for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) {
+      const uint4 v = src[ch];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const double d = (double)widen16<DT>((w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu) - mu;
+        s += pass ? d * d : d;
+      }
+    }
+  }
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) md.mat_partial[blockIdx.x] = s;
+}
+
+__global__ __launch_bounds__(kThreads) void matrix_finish_sums(const MatDesc* __restrict__ mats, int pass, int nparts) {
+  __shared__ double red[kWaves];
+  const MatDesc md = mats[blockIdx.x];
+  if (md.rows == 0 || md.cols == 0) return;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nparts; i += kThreads) s += md.mat_partial[i];
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) {
+    const double cnt = (double)md.rows * (double)md.cols;
+    md.mat_stats[pass] = pass ? sqrt(s / cnt) : s / cnt;
+  }
+}
+
+// ---- Eq. 4 ---------------------------------------------------------------------------
+// One workgroup per row: dense reconstruction scale * (code - zero_point) rounded to the
+// 16-bit type, then the row's outliers written over it.
+struct DeqDesc {
+  const uint32_t* codes;
+  const float* scales;
+  const uint8_t* zps;
+  const uint32_t* out_row_ptr;
+  const uint32_t* out_col;
+  const uint16_t* out_val;
+  uint16_t* W;
+  int64_t ld;
+  int32_t rows, cols, upr, G, words_per_row, bits;
+};
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
+  const int64_t row = blockIdx.x;
+  const uint32_t* wrow = d.codes + row * (int64_t)d.words_per_row;
+  uint16_t* orow = d.W + row * d.ld;
+  const uint32_t mask = (1u << d.bits) - 1u;
+  for (uint32_t g32 = threadIdx.x; g32 * 32u < (uint32_t)d.cols; g32 += kThreads) {
+    const uint32_t* wp = wrow + g32 * (uint32_t)d.bits;
+    unsigned long long acc = 0;
+    int nb = 0, wi = 0;
+    const uint32_t e_end = min(32u, (uint32_t)d.cols - g32 * 32u);
+    for (uint32_t e = 0; e < e_end; ++e) {
+      if (nb < d.bits) {
+        acc |= (unsigned long long)wp[wi++] << nb;
+        nb += 32;
+      }
+      const uint32_t u = (uint32_t)acc & mask;
+      acc >>= d.bits;
+      nb -= d.bits;
+      const uint32_t col = g32 * 32u + e;
+      const int64_t unit = row * (int64_t)d.upr + col / (uint32_t)d.G;
+      const float s = d.scales[unit];
+      const int z = (int)d.zps[unit];
+      orow[col] = (uint16_t)narrow16<DT>(s * (float)((int)u - z));
+    }
+  }
+  __syncthreads();
+  const uint32_t b = d.out_row_ptr[row], e = d.out_row_ptr[row + 1];
+  for (uint32_t i = b + threadIdx.x; i < e; i += kThreads) {
+    const uint32_t col = d.out_col[i];
+    if (col < (uint32_t)d.cols) orow[col] = d.out_val[i];
+  }
+}
+
+}  // namespace eq

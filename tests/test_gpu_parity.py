@@ -1,0 +1,162 @@
+"""Parity of the HIP path (called through the C ABI) with the CPU oracle on identical
+seeded inputs, element by element.  The bar is stated in tests/parity.py."""
+import numpy as np
+import pytest
+import torch
+
+import eq_inputs
+import paper_2403_02775_amd as eqg
+from oracle import easyquant_oracle as eqo
+from parity import compare, compare_sse, gpu_dequantize, raw_of, run_gpu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _check(W, p, what, batch=True, deq=True):
+    print(f"[case] {what} shape={tuple(W.shape)} bits={p.bits} G={p.group_size} mode={p.mode} T={p.iters}", flush=True)
+    raw = raw_of(W)
+    outs, got = run_gpu([W], p, batch=batch)
+    want = eqo.quantize_matrix(raw, p)
+    res = compare(raw, got[0], want, p, what)
+    if deq:
+        rows, cols = raw.shape
+        dg = gpu_dequantize(outs[0], rows, cols, p, W.device)
+        # the GPU dequantizer on the GPU's own outputs equals Eq. 4 evaluated by the oracle on them
+        assert (dg == eqo.dequantize(got[0], rows, cols, p)).all(), what
+        compare_sse(raw, dg, eqo.dequantize(want, rows, cols, p), p, res["rows_ok"], what)
+    return res
+
+
+def test_config1_per_channel_symmetric_and_asymmetric():
+    (_, W), = eq_inputs.gen_config_small("c1", DEV)
+    for mode in (eqo.ASYMMETRIC, eqo.SYMMETRIC):
+        p = eqo.Params(bits=4, group_size=0, mode=mode, iters=100)
+        res = _check(W, p, f"c1 mode={mode}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+
+
+@pytest.mark.parametrize("bits,G,mode", [(4, 128, eqo.SYMMETRIC), (3, 128, eqo.SYMMETRIC), (4, 128, eqo.ASYMMETRIC),
+                                         (2, 64, eqo.SYMMETRIC), (8, 32, eqo.ASYMMETRIC), (4, 256, eqo.SYMMETRIC),
+                                         (3, 0, eqo.ASYMMETRIC)])
+def test_small_matrices_across_bits_groups_modes(bits, G, mode):
+    # 72 rows x 1280 cols: several workgroups, ten 128-groups per row, rows not a multiple of anything
+    W = eq_inputs.gen_matrix(72, 1280, eq_inputs.RECIPES["c2"], seed=100 + bits, device=DEV)
+    p = eqo.Params(bits=bits, group_size=G, mode=mode, iters=60)
+    res = _check(W, p, "small")
+    assert res["excused_elems"] == 0
+
+
+def test_bf16_and_student_t_inputs():
+    W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
+    p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
+    _check(W, p, "bf16 t4")
+    W = eq_inputs.gen_matrix(40, 2048, eq_inputs.RECIPES["c3"], seed=4, device=DEV)
+    _check(W, eqo.Params(bits=3, group_size=128, iters=50), "f16 t4 3-bit")
+
+
+@pytest.mark.parametrize("scope", [eqo.STAT_GROUP, eqo.STAT_MATRIX])
+def test_statistic_scopes(scope):
+    W = eq_inputs.gen_matrix(64, 1024, eq_inputs.RECIPES["c5"], seed=5, device=DEV)
+    p = eqo.Params(bits=4, group_size=128, stat_scope=scope, iters=20)
+    _check(W, p, f"scope={scope}")
+
+
+def test_last_iterate_and_llama_learning_rate():
+    W = eq_inputs.gen_matrix(32, 1024, eq_inputs.RECIPES["c5"], seed=6, device=DEV)
+    _check(W, eqo.Params(bits=4, group_size=128, iters=100, select=eqo.SELECT_LAST), "select=last")
+    _check(W, eqo.Params(bits=4, group_size=128, iters=500, lr=1e-4), "T=500 lr=1e-4")
+    _check(W, eqo.Params(bits=4, group_size=128, iters=0), "T=0")
+    _check(W, eqo.Params(bits=4, group_size=128, iters=1), "T=1")
+    _check(W, eqo.Params(bits=4, group_size=128, iters=30, n_sigma=float("inf")), "no outliers")
+    _check(W, eqo.Params(bits=4, group_size=128, iters=30, n_sigma=1.0), "n=1 (many outliers)")
+
+
+def test_row_stride_and_single_matrix_entry_point():
+    big = eq_inputs.gen_matrix(24, 1536, eq_inputs.RECIPES["c2"], seed=7, device=DEV)
+    W = big[:, :1024]                                   # ld = 1536 > cols
+    assert W.stride(0) == 1536
+    p = eqo.Params(bits=4, group_size=128, iters=25)
+    _check(W, p, "strided", batch=False)
+
+
+def test_edge_cases_empty_constant_and_zero_rows():
+    p = eqo.Params(bits=4, group_size=32, iters=10)
+    W = torch.zeros((3, 64), dtype=torch.float16, device=DEV)
+    W[1, :32] = 0.5                                      # one constant group
+    W[2, 5] = -1.0                                       # a lone spike: it is the row's only outlier
+    _check(W, p, "degenerate units")
+    # no rows / no columns: nothing is launched on data, row_ptr and status are still written
+    for shape in ((0, 64), (4, 0)):
+        We = torch.zeros(shape, dtype=torch.float16, device=DEV)
+        outs, got = run_gpu([We], p)
+        assert got[0]["status"] == 0 and (got[0]["out_row_ptr"] == 0).all()
+
+
+def test_batch_of_mixed_shapes_matches_single_calls_and_is_deterministic():
+    rec = eq_inputs.RECIPES["c5"]
+    Ws = [eq_inputs.gen_matrix(r, c, rec, seed=50 + i, device=DEV) for i, (r, c) in
+          enumerate([(16, 1024), (40, 256), (8, 2816), (0, 128), (24, 1024)])]
+    p = eqo.Params(bits=4, group_size=128, iters=20)
+    _, got_a = run_gpu(Ws, p)
+    _, got_b = run_gpu(Ws, p)
+    for W, a, b in zip(Ws, got_a, got_b):
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k                      # byte-identical reruns
+        if W.shape[0]:
+            compare(raw_of(W), a, eqo.quantize_matrix(raw_of(W), p), p, "batch")
+            _, single = run_gpu([W], p, batch=False)
+            for k in a:
+                assert np.array_equal(a[k], single[0][k]), k
+
+
+def test_outlier_overflow_and_nonfinite_are_reported():
+    W = eq_inputs.gen_matrix(32, 1024, eq_inputs.RECIPES["c5"], seed=8, device=DEV)
+    p = eqo.Params(bits=4, group_size=128, iters=5)
+    want = eqo.quantize_matrix(raw_of(W), p)
+    true_total = int(want["out_row_ptr"][-1])
+    outs, got = run_gpu([W], p, capacities=[true_total // 2])
+    assert got[0]["status"] & eqg.EQ_S_OUTLIER_OVERFLOW
+    assert (got[0]["out_row_ptr"] == want["out_row_ptr"]).all()          # true counts, so the caller can re-size
+    outs, got = run_gpu([W], p, capacities=[true_total])                  # exactly enough
+    compare(raw_of(W), got[0], want, p, "exact capacity")
+    outs, got = run_gpu([W], p, capacities=[0])
+    assert got[0]["status"] & eqg.EQ_S_OUTLIER_OVERFLOW
+    Wb = W.clone()
+    Wb[3, 17] = float("inf")
+    outs, got = run_gpu([Wb], p)
+    assert got[0]["status"] & eqg.EQ_S_NONFINITE
+
+
+def test_argument_validation_on_device_pointers():
+    W = torch.zeros((8, 256), dtype=torch.float16, device=DEV)
+    gp = eqg.Params(group_size=128)
+    out = eqg.alloc_outputs(8, 256, gp, 64, DEV)
+    ws = torch.empty(eqg.eq_workspace_bytes([8], [256], [64], gp), dtype=torch.uint8, device=DEV)
+    with pytest.raises(eqg.EasyQuantError) as e:
+        eqg.eq_quantize_matrix(W, gp, out, ws[:128])
+    assert e.value.code == -5
+    with pytest.raises(eqg.EasyQuantError) as e:
+        eqg.eq_quantize_matrix(W, gp, out, ws[1:])
+    assert e.value.code == -5
+    with pytest.raises(eqg.EasyQuantError) as e:
+        eqg.eq_quantize_matrix(W.view(-1)[4:4 + 7 * 256].view(7, 256), gp, out, ws)
+    assert e.value.code == -4
+
+
+def test_config2_llama7b_attention_projection():
+    (_, W), = eq_inputs.gen_config_small("c2", DEV)
+    p = eqo.Params(bits=4, group_size=128, iters=100)
+    raw = raw_of(W)
+    outs, got = run_gpu([W], p)
+    # the oracle works through the matrix in row blocks (rows are independent under row statistics)
+    parts = [eqo.quantize_matrix(raw[r:r + 512], p) for r in range(0, 4096, 512)]
+    want = {k: np.concatenate([q[k] for q in parts]) for k in ("codes", "scales", "zero_points", "out_col", "out_val", "mask", "u")}
+    cnt = np.concatenate([np.diff(q["out_row_ptr"].astype(np.int64)) for q in parts])
+    want["out_row_ptr"] = np.concatenate([[0], np.cumsum(cnt)]).astype(np.uint32)
+    res = compare(raw, got[0], want, p, "c2")
+    assert res["excused_elems"] == 0
+    dg = gpu_dequantize(outs[0], 4096, 4096, p, W.device)
+    compare_sse(raw, dg, eqo.dequantize(want, 4096, 4096, p), p, res["rows_ok"], "c2")
+    frac = got[0]["out_row_ptr"][-1] / raw.size
+    assert 0.004 < frac < 0.008
