@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the EasyQuant quantization hot path on one MI355X.
+
+One "step" = one eq_quantize_batch call over a whole synthetic LLaMA-shaped weight set that
+is already resident in HBM (outlier isolation, all range-optimisation iterations, packed
+codes, scales, zero-points and the sorted outlier list for every matrix).
+
+Prints ONE JSON line: metric = GB/s of 16-bit weights quantized (and seconds per model), a
+`roofline` object for the dominant kernel and a `cpu_baseline` object (the CPU oracle timed
+on a bounded sample of the same workload on this machine's host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12                               # B/s, MI355X HBM3E
+ALU_PEAK = 256 * 4 * 16 * 2.4e9                 # lane-operations/s: 256 CUs x 4 SIMD x 16 lanes x 2.4 GHz
+
+WORKLOADS = {
+    # name: (model shapes, recipe key, 16-bit type, bits, note)
+    "llama65b_f16_w4g128": ("llama65b", "c5", "f16", 4),
+    "llama7b_bf16_w4g128": ("llama7b", "c4", "bf16", 4),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_workload(name, layers, device):
+    import torch
+    import eq_inputs
+    which, rkey, dt, bits = WORKLOADS[name]
+    recipe = eq_inputs.with_dtype(eq_inputs.RECIPES[rkey], dt)
+    Ws, names = [], []
+    t0 = time.time()
+    for layer, nm, W in eq_inputs.iter_model(which, recipe, device, base_seed=0, layers=layers):
+        Ws.append(W)
+        names.append((layer, nm))
+        if nm == "down":
+            torch.cuda.synchronize()
+            log(f"[gen] layer {layer} done, {sum(w.numel() for w in Ws) * 2 / 1e9:.1f} GB resident, {time.time() - t0:.0f}s")
+    return Ws, names, bits, dt
+
+
+def algorithmic_bytes(Ws, bits, n_outliers):
+    """HBM bytes the path must move: read W once; write codes, scale + zero-point, outliers (col + value) and row_ptr."""
+    elems = sum(w.numel() for w in Ws)
+    units = elems // 128
+    rows = sum(w.shape[0] for w in Ws)
+    return elems * 2 + elems * bits // 8 + units * 5 + n_outliers * 6 + (rows + len(Ws)) * 4
+
+
+def cpu_baseline(Ws, gp_kwargs, sample_rows):
+    """The oracle, as it stands, on the first `sample_rows` rows of the first matrix."""
+    import numpy as np
+    from oracle import easyquant_oracle as eqo
+    W = Ws[0][:sample_rows]
+    raw = W.cpu().contiguous().view(__import__("torch").int16).numpy().view(np.uint16)
+    p = eqo.Params(**gp_kwargs)
+    t0 = time.perf_counter()
+    eqo.quantize_matrix(raw, p)
+    dt = time.perf_counter() - t0
+    return raw.size * 2 / dt / 1e9, dt, raw.shape
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama65b_f16_w4g128", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=-1, help="limit the number of layers (debugging; changes the workload)")
+    ap.add_argument("--iters", type=int, default=100, help="Adam steps T on the range")
+    ap.add_argument("--lr", type=float, default=1e-3)
+    ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
+    ap.add_argument("--cpu-rows", type=int, default=384, help="rows of the first matrix given to the CPU oracle (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (the path needs no communication; see DESIGN.md); run with --gpus 1")
+
+    import torch
+    import paper_2403_02775_amd as eqg
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    Ws, names, bits, dt = build_workload(args.workload, args.layers, dev)
+    gp = eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=128, mode=eqg.EQ_SYMMETRIC,
+                    stat_scope=eqg.EQ_STAT_ROW, n_sigma=3.0, iters=args.iters, lr=args.lr, select=eqg.EQ_SELECT_BEST)
+    caps = [int(w.numel() * args.capacity_frac) for w in Ws]
+    outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, dev) for w, c in zip(Ws, caps)]
+    ws_bytes = eqg.eq_workspace_bytes([w.shape[0] for w in Ws], [w.shape[1] for w in Ws], caps, gp)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    log(f"[mem] inputs {sum(w.numel() for w in Ws) * 2 / 1e9:.1f} GB, workspace {ws_bytes / 1e9:.1f} GB, "
+        f"allocated {torch.cuda.memory_allocated() / 1e9:.1f} GB")
+
+    def step():
+        eqg.eq_quantize_batch(Ws, gp, outs, ws)
+
+    for i in range(args.warmup):
+        step()
+        torch.cuda.synchronize()
+        log(f"[warmup] {i + 1}/{args.warmup}")
+    eqg.eq_profile_enable(True)
+    eqg.eq_profile_read()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    kern_ms, launches = eqg.eq_profile_read()
+    eqg.eq_profile_enable(False)
+
+    status = [int(o.status.item()) for o in outs]
+    assert not any(status), f"device status words: {sorted(set(status))}"
+    n_out = sum(int(o.out_row_ptr[-1].item()) & 0xFFFFFFFF for o in outs)
+    elems = sum(w.numel() for w in Ws)
+    ms_per_step = gpu_ms / args.steps
+    weight_gbs = elems * 2 / (ms_per_step * 1e-3) / 1e9
+    passes = args.iters + 2                       # T+1 evaluations (best-iterate selection) + the emitting one
+    lane_ops = elems * (5 * passes + 12)          # useful lane-operations: 5 per element and pass, 12 fixed
+    kern_s = kern_ms * 1e-3 / args.steps          # main kernels per step (one launch per row-length class)
+    alg_bytes = algorithmic_bytes(Ws, bits, n_out)
+    alu_frac = lane_ops / kern_s / ALU_PEAK
+    hbm_frac = alg_bytes / kern_s / HBM_PEAK
+    if alu_frac >= hbm_frac:
+        roof = {"bound": "alu", "achieved": lane_ops / kern_s / 1e12, "peak": ALU_PEAK / 1e12, "unit": "Tlaneop/s",
+                "frac": alu_frac, "traffic": None}
+    else:
+        roof = {"bound": "hbm", "achieved": alg_bytes / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": hbm_frac, "traffic": None}
+    roof.update({"kernel": "quantize_units128", "launches_per_step": launches / args.steps,
+                 "kernel_ms_per_step": kern_ms / args.steps, "avg_launch_ms": kern_ms / max(launches, 1),
+                 "algorithmic_bytes": alg_bytes, "hbm_frac": hbm_frac, "alu_frac": alu_frac,
+                 "lane_ops_per_element": 5 * passes + 12})
+
+    out = {
+        "metric": "fp16 weight GB/s quantized (fraction of HBM peak); s per 65B-shaped model",
+        "value": weight_gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if True else None, "data": "synthetic",
+        "config": {"workload": args.workload + ("" if args.layers < 0 else f"[first {args.layers} layers]"),
+                   "matrices": len(Ws), "elements": elems, "bits": bits, "group_size": 128, "mode": "symmetric",
+                   "n_sigma": 3.0, "iters": args.iters, "lr": args.lr, "select": "best", "weights_dtype": dt,
+                   "parallelism": "1 GPU, one batch call"},
+        "seconds_per_model": ms_per_step * 1e-3,
+        "weight_hbm_frac": weight_gbs * 1e9 / HBM_PEAK,
+        "outlier_fraction": n_out / elems,
+        "wall_s_per_step": wall / args.steps,
+        "roofline": roof,
+    }
+    if args.cpu_rows > 0:
+        kw = dict(dtype=gp.dtype, bits=bits, group_size=128, mode=0, stat_scope=0, n_sigma=3.0, iters=args.iters,
+                  lr=args.lr, select=0)
+        gbs, secs, shape = cpu_baseline(Ws, kw, args.cpu_rows)
+        out["cpu_baseline"] = {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {shape[0]} rows x {shape[1]} cols of layer 0 q_proj ({secs:.1f} s, NumPy, "
+                                         f"single thread; host has {os.cpu_count()} logical CPUs)",
+                               "seconds_per_model_extrapolated": elems * 2 / (gbs * 1e9)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -153,6 +153,14 @@ EQ_API int64_t eq_outlier_capacity_bound(int64_t rows, int64_t cols, float n_sig
  * Adam lr 1e-3 for 100 steps (Sec. 5, Setup), fp16, row statistics, best iterate. */
 EQ_API void eq_default_params(eq_params* p);
 
+/* Instrumentation for benchmarks.  While enabled, every launch of a main quantization kernel
+ * (the kernels that run Algorithm 1's "Quantize"; not the small reset / prefix-sum / gather
+ * kernels around them) is bracketed by HIP events on the call's stream.
+ * eq_profile_read waits for those events, returns the summed kernel time in milliseconds and
+ * the number of launches since the last read, and forgets them.  Not thread-safe. */
+EQ_API int eq_profile_enable(int on);
+EQ_API int eq_profile_read(double* kernel_ms, int32_t* launches);
+
 /* Static description of a return code. */
 EQ_API const char* eq_strerror(int code);
 /* hipError_t of the most recent EQ_E_HIP on this thread (0 if none). */

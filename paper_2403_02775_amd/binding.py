@@ -74,6 +74,10 @@ def lib() -> C.CDLL:
         L.eq_strerror.argtypes = [C.c_int]
         L.eq_last_hip_error.restype = C.c_int
         L.eq_last_hip_error.argtypes = []
+        L.eq_profile_enable.restype = C.c_int
+        L.eq_profile_enable.argtypes = [C.c_int]
+        L.eq_profile_read.restype = C.c_int
+        L.eq_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -125,6 +129,19 @@ def eq_strerror(code: int) -> str:
     return lib().eq_strerror(int(code)).decode()
 
 
+def eq_profile_enable(on: bool) -> None:
+    lib().eq_profile_enable(1 if on else 0)
+
+
+def eq_profile_read():
+    """(summed main-kernel milliseconds, number of launches) since the last read."""
+    ms, n = C.c_double(0.0), C.c_int32(0)
+    rc = lib().eq_profile_read(C.byref(ms), C.byref(n))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_profile_read")
+    return ms.value, n.value
+
+
 def eq_code_words_per_row(cols: int, bits: int) -> int:
     return int(lib().eq_code_words_per_row(cols, bits))
 
@@ -161,6 +178,12 @@ def _stream_ptr(stream) -> Optional[int]:
     return C.c_void_p(stream.cuda_stream)
 
 
+def _ld(W: torch.Tensor) -> int:
+    """Row stride in elements (a matrix with at most one row, or no columns, has no meaningful stride)."""
+    rows, cols = W.shape
+    return int(cols) if rows <= 1 or cols == 0 else int(W.stride(0))
+
+
 def _check_w(W: torch.Tensor, p: Params):
     want = torch.float16 if p.dtype == EQ_F16 else torch.bfloat16
     if W.dtype != want or W.dim() != 2 or W.stride(1) != 1 or not W.is_cuda:
@@ -171,7 +194,7 @@ def eq_quantize_matrix(W: torch.Tensor, p: Params, out: QMatrix, workspace: torc
     _check_w(W, p)
     rows, cols = W.shape
     cp, cq = p.c(), out.c()
-    rc = lib().eq_quantize_matrix(W.data_ptr(), rows, cols, W.stride(0) if rows > 1 else max(cols, W.stride(0)),
+    rc = lib().eq_quantize_matrix(W.data_ptr(), rows, cols, _ld(W),
                                   C.byref(cp), C.byref(cq), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                   _stream_ptr(stream))
     if rc != 0:
@@ -185,7 +208,7 @@ def eq_quantize_batch(Ws: List[torch.Tensor], p: Params, outs: List[QMatrix], wo
     PA, IA, QA = C.c_void_p * max(n, 1), C.c_int64 * max(n, 1), _CQMatrix * max(n, 1)
     rows = [int(W.shape[0]) for W in Ws]
     cols = [int(W.shape[1]) for W in Ws]
-    lds = [int(W.stride(0)) if W.shape[0] > 1 else max(int(W.shape[1]), int(W.stride(0))) for W in Ws]
+    lds = [_ld(W) for W in Ws]
     cp = p.c()
     rc = lib().eq_quantize_batch(n, PA(*[W.data_ptr() for W in Ws]), IA(*rows), IA(*cols), IA(*lds), C.byref(cp),
                                  QA(*[o.c() for o in outs]), workspace.data_ptr(),
@@ -198,6 +221,6 @@ def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tens
     _check_w(W_out, p)
     cp, cq = p.c(), q.c()
     rc = lib().eq_dequantize(C.byref(cq), rows, cols, C.byref(cp), W_out.data_ptr(),
-                             W_out.stride(0) if rows > 1 else max(cols, W_out.stride(0)), _stream_ptr(stream))
+                             _ld(W_out), _stream_ptr(stream))
     if rc != 0:
         raise EasyQuantError(rc, "eq_dequantize")

@@ -4,11 +4,15 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <algorithm>
+#include <cstdlib>
 #include <cstring>
+#include <numeric>
 #include <vector>
 
 #include "easyquant.h"
 #include "eq_common.h"
+#include "eq_fused128.h"
 #include "eq_generic.h"
 #include "eq_post.h"
 #include "eq_rowstage.h"
@@ -18,6 +22,25 @@ namespace {
 using namespace eq;
 
 thread_local int g_last_hip_error = 0;
+
+// ---- optional event bracketing of the main kernels (eq_profile_*) ----
+bool g_profile = false;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
+
+struct ScopedKernelTimer {
+  hipStream_t st;
+  hipEvent_t a = nullptr, b = nullptr;
+  explicit ScopedKernelTimer(hipStream_t s) : st(s) {
+    if (!g_profile) return;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+    (void)hipEventRecord(a, st);
+  }
+  ~ScopedKernelTimer() {
+    if (!a) return;
+    (void)hipEventRecord(b, st);
+    g_events.emplace_back(a, b);
+  }
+};
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -61,20 +84,87 @@ KParams make_kparams(const eq_params* p) {
   return k;
 }
 
-// Byte offsets of everything that lives in the workspace.
+// One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
+struct LaneClass {
+  int32_t cols = 0, upr = 0;
+  uint32_t pool_slots = 0;
+  size_t lds_bytes = 0;
+  size_t first_item = 0, n_items = 0;
+};
+
+// Byte offsets of everything that lives in the workspace, and the launch plan.
 struct Plan {
   size_t descs = 0;                     // MatDesc[n]
+  size_t items = 0;                     // WorkItem[]
   std::vector<size_t> cursor, row_count, row_stage, st_col, st_val, mat_stats, mat_partial;
+  std::vector<int32_t> path;            // per matrix: 0 = general kernel, 1 = unit-per-lane kernel
+  std::vector<LaneClass> classes;
+  std::vector<WorkItem> work;
+  bool any_general = false;
   size_t total = 0;
 };
 
 int64_t clamp_capacity(int64_t c) { return c < 0 ? 0 : (c > 0xFFFFFFFEll ? 0xFFFFFFFEll : c); }
 
-Plan make_plan(int32_t n, const int64_t* rows, const int64_t* /*cols*/, const int64_t* cap, const eq_params* p) {
+// The unit-per-lane kernel serves group_size 128 with row or matrix statistics and rows that
+// fit its LDS pool; everything else goes to the general kernel.
+bool lane_kernel_ok(int64_t rows, int64_t cols, const eq_params* p) {
+  return p->group_size == kG && p->stat_scope != EQ_STAT_GROUP && rows > 0 && cols > 0 && cols <= 32768;
+}
+
+Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* cap, const eq_params* p) {
   Plan pl;
+  pl.path.assign((size_t)n, 0);
+  // ---- launch plan ----
+  std::vector<int32_t> order;
+  for (int32_t i = 0; i < n; ++i) {
+    if (lane_kernel_ok(rows[i], cols[i], p)) {
+      pl.path[(size_t)i] = 1;
+      order.push_back(i);
+    } else if (rows[i] > 0 && cols[i] > 0) {
+      pl.any_general = true;
+    }
+  }
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return cols[a] < cols[b]; });
+  for (size_t k = 0; k < order.size();) {
+    size_t e = k;
+    int64_t total_units = 0;
+    const int64_t c = cols[order[k]];
+    const int64_t upr = c / kG;
+    while (e < order.size() && cols[order[e]] == c) total_units += rows[order[e++]] * upr;
+    LaneClass lc;
+    lc.cols = (int32_t)c;
+    lc.upr = (int32_t)upr;
+    const int64_t g = std::gcd(upr, (int64_t)kThreads);
+    lc.pool_slots = (uint32_t)(upr >= kThreads && upr % kThreads == 0 ? upr : kThreads - g + upr);
+    lc.lds_bytes = 256 + (size_t)lc.pool_slots * kSlotBytes + (size_t)c / 8;
+    // rows per work item: enough units to amortise the partly filled last round of an item,
+    // few enough that the grid has several items per compute unit; a multiple of the period
+    // after which rows fill whole rounds when that fits
+    int64_t target = std::min<int64_t>(16384, std::max<int64_t>(kThreads, total_units / 4096));
+    if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {   // tuning / test override
+      const long v = std::atol(ov);
+      if (v > 0) target = v;
+    }
+    const int64_t period = kThreads / g;
+    int64_t rpi = std::max<int64_t>(1, target / upr);
+    if (rpi >= period) rpi -= rpi % period;
+    lc.first_item = pl.work.size();
+    for (size_t j = k; j < e; ++j) {
+      const int32_t m = order[j];
+      for (int64_t r = 0; r < rows[m]; r += rpi)
+        pl.work.push_back(WorkItem{m, (int32_t)r, (int32_t)std::min<int64_t>(rpi, rows[m] - r), 0});
+    }
+    lc.n_items = pl.work.size() - lc.first_item;
+    pl.classes.push_back(lc);
+    k = e;
+  }
+  // ---- workspace layout ----
   size_t off = 0;
   pl.descs = off;
   off = align_up(off + sizeof(MatDesc) * (size_t)n, 256);
+  pl.items = off;
+  off = align_up(off + sizeof(WorkItem) * pl.work.size(), 256);
   for (int32_t i = 0; i < n; ++i) {
     const size_t r = (size_t)rows[i];
     const size_t c = (size_t)clamp_capacity(cap[i]);
@@ -105,32 +195,53 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* /*cols*/, const in
   } while (0)
 
 template <int DT>
-int launch_all(int32_t n, const MatDesc* dmats, const std::vector<MatDesc>& h, const KParams& kp, hipStream_t st) {
-  int32_t max_rows = 0, max_cols = 0;
+int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const std::vector<MatDesc>& h, const Plan& pl,
+               const KParams& kp, hipStream_t st) {
+  int32_t max_rows = 0, gen_rows = 0, gen_cols = 0;
   for (const MatDesc& m : h) {
-    if (m.cols == 0) continue;
+    if (m.cols == 0 || m.rows == 0) continue;
     max_rows = std::max(max_rows, m.rows);
-    max_cols = std::max(max_cols, m.cols);
+    if (m.path == 0) {
+      gen_rows = std::max(gen_rows, m.rows);
+      gen_cols = std::max(gen_cols, m.cols);
+    }
   }
   hipLaunchKernelGGL(reset_state, dim3((n + 255) / 256), dim3(256), 0, st, dmats, n);
   EQ_HIP(hipGetLastError());
-  if (max_rows > 0) {
-    if (kp.scope == EQ_STAT_MATRIX) {
-      for (int pass = 0; pass < 2; ++pass) {
-        hipLaunchKernelGGL(matrix_partial_sums<DT>, dim3(kMatrixStatParts, n), dim3(kThreads), 0, st, dmats, pass);
-        EQ_HIP(hipGetLastError());
-        hipLaunchKernelGGL(matrix_finish_sums, dim3(n), dim3(kThreads), 0, st, dmats, pass, kMatrixStatParts);
-        EQ_HIP(hipGetLastError());
-      }
+  if (max_rows > 0 && kp.scope == EQ_STAT_MATRIX) {
+    for (int pass = 0; pass < 2; ++pass) {
+      hipLaunchKernelGGL(matrix_partial_sums<DT>, dim3(kMatrixStatParts, n), dim3(kThreads), 0, st, dmats, pass);
+      EQ_HIP(hipGetLastError());
+      hipLaunchKernelGGL(matrix_finish_sums, dim3(n), dim3(kThreads), 0, st, dmats, pass, kMatrixStatParts);
+      EQ_HIP(hipGetLastError());
     }
-    const size_t lds = 256 + (size_t)max_cols * 2 + (size_t)max_cols / 8;
-    static thread_local size_t lds_set[2] = {0, 0};
-    if (lds > 65536 && lds > lds_set[DT]) {
+  }
+  static thread_local size_t lds_set[2][2] = {{0, 0}, {0, 0}};   // [kernel][dtype]: largest LDS size enabled so far
+  for (const LaneClass& lc : pl.classes) {
+    if (lc.n_items == 0) continue;
+    if (lc.lds_bytes > 65536 && lc.lds_bytes > lds_set[1][DT]) {
+      EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_units128<DT>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
+      lds_set[1][DT] = lc.lds_bytes;
+    }
+    {
+      ScopedKernelTimer tm(st);
+      hipLaunchKernelGGL(quantize_units128<DT>, dim3((unsigned)lc.n_items), dim3(kThreads), lc.lds_bytes, st, dmats,
+                         ditems + lc.first_item, kp, lc.pool_slots);
+    }
+    EQ_HIP(hipGetLastError());
+  }
+  if (gen_rows > 0) {
+    const size_t lds = 256 + (size_t)gen_cols * 2 + (size_t)gen_cols / 8;
+    if (lds > 65536 && lds > lds_set[0][DT]) {
       EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_rows_generic<DT>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      lds_set[DT] = lds;
+      lds_set[0][DT] = lds;
     }
-    hipLaunchKernelGGL(quantize_rows_generic<DT>, dim3(max_rows, n), dim3(kThreads), lds, st, dmats, kp);
+    {
+      ScopedKernelTimer tm(st);
+      hipLaunchKernelGGL(quantize_rows_generic<DT>, dim3(gen_rows, n), dim3(kThreads), lds, st, dmats, kp);
+    }
     EQ_HIP(hipGetLastError());
   }
   hipLaunchKernelGGL(scan_row_counts, dim3(n), dim3(kThreads), 0, st, dmats);
@@ -168,6 +279,31 @@ const char* eq_strerror(int code) {
 }
 
 int eq_last_hip_error(void) { return g_last_hip_error; }
+
+int eq_profile_enable(int on) {
+  g_profile = on != 0;
+  return EQ_OK;
+}
+
+int eq_profile_read(double* kernel_ms, int32_t* launches) {
+  double total = 0.0;
+  int32_t cnt = 0;
+  int rc = EQ_OK;
+  for (auto& ev : g_events) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(ev.second);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; rc = EQ_E_HIP; }
+    total += ms;
+    ++cnt;
+    (void)hipEventDestroy(ev.first);
+    (void)hipEventDestroy(ev.second);
+  }
+  g_events.clear();
+  if (kernel_ms) *kernel_ms = total;
+  if (launches) *launches = cnt;
+  return rc;
+}
 
 int64_t eq_code_words_per_row(int64_t cols, int32_t bits) {
   if (cols < 0 || bits < 1 || bits > 32) return 0;
@@ -242,13 +378,19 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
     m.G = p->group_size ? p->group_size : (int32_t)cols[i];
     m.upr = m.G ? m.cols / m.G : 0;
     m.words_per_row = (int32_t)eq_code_words_per_row(cols[i], p->bits);
+    m.path = pl.path[(size_t)i];
+    if (m.path == 1 && ((uintptr_t)o.codes & 15)) return EQ_E_ALIGN;   // 128-bit code stores
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   MatDesc* dmats = reinterpret_cast<MatDesc*>(ws + pl.descs);
   // pageable source: the runtime stages the bytes before returning, so `h` may die with this frame
   EQ_HIP(hipMemcpyAsync(dmats, h.data(), sizeof(MatDesc) * (size_t)n, hipMemcpyHostToDevice, st));
+  WorkItem* ditems = reinterpret_cast<WorkItem*>(ws + pl.items);
+  if (!pl.work.empty())
+    EQ_HIP(hipMemcpyAsync(ditems, pl.work.data(), sizeof(WorkItem) * pl.work.size(), hipMemcpyHostToDevice, st));
   const KParams kp = make_kparams(p);
-  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, h, kp, st) : launch_all<EQ_BF16>(n, dmats, h, kp, st);
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, h, pl, kp, st)
+                            : launch_all<EQ_BF16>(n, dmats, ditems, h, pl, kp, st);
 }
 
 int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,

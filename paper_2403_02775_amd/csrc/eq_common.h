@@ -44,7 +44,7 @@ struct MatDesc {
   int32_t upr;                  // units per row
   int32_t G;                    // elements per unit
   int32_t words_per_row;
-  int32_t pad_;
+  int32_t path;                 // 0: general kernel, 1: unit-per-lane kernel
 };
 
 // Hyper-parameters in the form the kernels use them.

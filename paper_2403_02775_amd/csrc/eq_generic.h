@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_generic(const MatDesc*
   extern __shared__ __align__(16) unsigned char smem[];
   const MatDesc md = mats[blockIdx.y];
   const int64_t row = blockIdx.x;
-  if (row >= md.rows) return;
+  if (row >= md.rows || md.path != 0 || md.cols == 0) return;
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
   StageScratch* sc = reinterpret_cast<StageScratch*>(smem);
   unsigned char* lds_row = smem + 256;

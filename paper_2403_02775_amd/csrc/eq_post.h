@@ -145,7 +145,11 @@ __global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
       const int64_t unit = row * (int64_t)d.upr + col / (uint32_t)d.G;
       const float s = d.scales[unit];
       const int z = (int)d.zps[unit];
-      orow[col] = (uint16_t)narrow16<DT>(s * (float)((int)u - z));
+      float prod = s * (float)((int)u - z);
+      // Eq. 4 is evaluated as a binary32 product that is then rounded to the 16-bit type.  The
+      // empty asm keeps the compiler from fusing both into one rounding (v_fma_mixlo_f16).
+      asm volatile("" : "+v"(prod));
+      orow[col] = (uint16_t)narrow16<DT>(prod);
     }
   }
   __syncthreads();

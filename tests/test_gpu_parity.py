@@ -47,6 +47,19 @@ def test_small_matrices_across_bits_groups_modes(bits, G, mode):
     assert res["excused_elems"] == 0
 
 
+@pytest.mark.parametrize("rows,cols,units_per_item", [(130, 1280, 1000), (9, 22016, 0), (24, 11008, 1500),
+                                                      (3, 32768, 0), (70, 8192, 2048), (64, 4096, 0)])
+def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_item, monkeypatch):
+    # group 128: rows whose unit count does not divide the 256-unit rounds leave units behind
+    # that are carried to the next fill; the override makes work items span several rounds
+    if units_per_item:
+        monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", str(units_per_item))
+    W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows + cols, device=DEV)
+    for bits in (4, 3):
+        res = _check(W, eqo.Params(bits=bits, group_size=128, iters=12), f"lane kernel {rows}x{cols}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+
+
 def test_bf16_and_student_t_inputs():
     W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
