@@ -82,7 +82,7 @@ def main():
     ap.add_argument("--iters", type=int, default=100, help="Adam steps T on the range")
     ap.add_argument("--lr", type=float, default=1e-3)
     ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
-    ap.add_argument("--cpu-rows", type=int, default=384, help="rows of the first matrix given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the first matrix given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path needs no communication; see DESIGN.md); run with --gpus 1")

@@ -17,7 +17,10 @@ vectorised over units with NumPy (every unit sees the same scalar sequence of
 operations; nothing is blocked, fused or reordered).  The iteration is chaotic
 at the last bit, therefore the arithmetic is pinned as well:
 
-* element-wise work in IEEE binary32, one rounding per operation;
+* the scale s = r / D and its reciprocal are binary32 (one rounding each); the level
+  of an element is the EXACT product x * (1/s) rounded ONCE to the nearest integer,
+  ties to even, as Eq. 1 rounds a real number (the product of a 16-bit value and a
+  binary32 value is exact in binary64, so no intermediate rounding takes part);
 * the two sums of Eq. 2, ``A = sum c_i^2`` and ``B = sum x_i c_i``, are EXACT
   (integers, and a binary64 accumulation of exact binary32 products that is
   checked to be exact; ``math.fsum`` otherwise);
@@ -238,8 +241,8 @@ class UnitView:
         D = self.D
         s32 = (r32 / D).astype(_f32)
         inv32 = (_f32(1.0) / s32).astype(_f32)
-        t = (self.xt * inv32[:, None]).astype(_f32)
-        tc = np.minimum(np.maximum(t, self.c_lo[:, None]), self.c_hi[:, None])
+        t = self.xt.astype(_f64) * inv32.astype(_f64)[:, None]       # exact (<= 11 + 24 significant bits)
+        tc = np.minimum(np.maximum(t, self.c_lo.astype(_f64)[:, None]), self.c_hi.astype(_f64)[:, None])
         c = np.rint(tc).astype(_f32)
         ci = c.astype(np.int64)
         A = (ci * ci).sum(axis=1)
