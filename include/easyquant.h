@@ -161,6 +161,13 @@ EQ_API void eq_default_params(eq_params* p);
 EQ_API int eq_profile_enable(int on);
 EQ_API int eq_profile_read(double* kernel_ms, int32_t* launches);
 
+/* Diagnostics (host only, no GPU): the library divides by values whose correctly rounded
+ * reciprocal it knows (Adam's bias corrections, the level count D) with a short multiply-add
+ * sequence instead of a hardware division.  These run that same sequence on the host so that
+ * a test can confirm it returns the IEEE quotient a / b bit for bit. */
+EQ_API double eq_diag_div_f64(double a, double b);
+EQ_API float eq_diag_div_f32(float a, float b);
+
 /* Static description of a return code. */
 EQ_API const char* eq_strerror(int code);
 /* hipError_t of the most recent EQ_E_HIP on this thread (0 if none). */

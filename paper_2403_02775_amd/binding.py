@@ -74,6 +74,10 @@ def lib() -> C.CDLL:
         L.eq_strerror.argtypes = [C.c_int]
         L.eq_last_hip_error.restype = C.c_int
         L.eq_last_hip_error.argtypes = []
+        L.eq_diag_div_f64.restype = C.c_double
+        L.eq_diag_div_f64.argtypes = [C.c_double, C.c_double]
+        L.eq_diag_div_f32.restype = C.c_float
+        L.eq_diag_div_f32.argtypes = [C.c_float, C.c_float]
         L.eq_profile_enable.restype = C.c_int
         L.eq_profile_enable.argtypes = [C.c_int]
         L.eq_profile_read.restype = C.c_int

@@ -81,6 +81,9 @@ KParams make_kparams(const eq_params* p) {
   k.D = p->mode == EQ_SYMMETRIC ? (float)k.zsym : (float)k.L;
   k.n = (double)p->n_sigma;
   k.lr = (double)p->lr; k.b1 = (double)p->beta1; k.b2 = (double)p->beta2; k.eps = (double)p->eps;
+  k.rD64 = 1.0 / (double)k.D;
+  k.rD32 = 1.0f / k.D;
+  k.adam_tab = nullptr;
   return k;
 }
 
@@ -92,10 +95,29 @@ struct LaneClass {
   size_t first_item = 0, n_items = 0;
 };
 
+// Bias corrections of Adam for steps 1..T and their correctly rounded reciprocals, in the
+// order the kernels read them (Adam::step).  The running products are formed exactly as the
+// recurrence defines them: p <- p * beta in binary64.
+std::vector<double> make_adam_table(const eq_params* p) {
+  std::vector<double> tab((size_t)std::max(p->iters, 1) * 4, 1.0);
+  const double b1 = (double)p->beta1, b2 = (double)p->beta2;
+  double p1 = 1.0, p2 = 1.0;
+  for (int t = 0; t < p->iters; ++t) {
+    p1 = p1 * b1;
+    p2 = p2 * b2;
+    tab[4 * (size_t)t + 0] = 1.0 - p1;
+    tab[4 * (size_t)t + 1] = 1.0 / (1.0 - p1);
+    tab[4 * (size_t)t + 2] = 1.0 - p2;
+    tab[4 * (size_t)t + 3] = 1.0 / (1.0 - p2);
+  }
+  return tab;
+}
+
 // Byte offsets of everything that lives in the workspace, and the launch plan.
 struct Plan {
   size_t descs = 0;                     // MatDesc[n]
   size_t items = 0;                     // WorkItem[]
+  size_t adam = 0;                      // double[4 * max(T, 1)]
   std::vector<size_t> cursor, row_count, row_stage, st_col, st_val, mat_stats, mat_partial;
   std::vector<int32_t> path;            // per matrix: 0 = general kernel, 1 = unit-per-lane kernel
   std::vector<LaneClass> classes;
@@ -165,6 +187,8 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
   off = align_up(off + sizeof(MatDesc) * (size_t)n, 256);
   pl.items = off;
   off = align_up(off + sizeof(WorkItem) * pl.work.size(), 256);
+  pl.adam = off;
+  off = align_up(off + sizeof(double) * 4 * (size_t)std::max(p->iters, 1), 256);
   for (int32_t i = 0; i < n; ++i) {
     const size_t r = (size_t)rows[i];
     const size_t c = (size_t)clamp_capacity(cap[i]);
@@ -280,6 +304,9 @@ const char* eq_strerror(int code) {
 
 int eq_last_hip_error(void) { return g_last_hip_error; }
 
+double eq_diag_div_f64(double a, double b) { return div_known_rcp(a, b, 1.0 / b); }
+float eq_diag_div_f32(float a, float b) { return div_known_rcp(a, b, 1.0f / b); }
+
 int eq_profile_enable(int on) {
   g_profile = on != 0;
   return EQ_OK;
@@ -388,7 +415,11 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   WorkItem* ditems = reinterpret_cast<WorkItem*>(ws + pl.items);
   if (!pl.work.empty())
     EQ_HIP(hipMemcpyAsync(ditems, pl.work.data(), sizeof(WorkItem) * pl.work.size(), hipMemcpyHostToDevice, st));
-  const KParams kp = make_kparams(p);
+  KParams kp = make_kparams(p);
+  const std::vector<double> tab = make_adam_table(p);
+  double* dtab = reinterpret_cast<double*>(ws + pl.adam);
+  EQ_HIP(hipMemcpyAsync(dtab, tab.data(), sizeof(double) * tab.size(), hipMemcpyHostToDevice, st));
+  kp.adam_tab = dtab;
   return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, h, pl, kp, st)
                             : launch_all<EQ_BF16>(n, dmats, ditems, h, pl, kp, st);
 }

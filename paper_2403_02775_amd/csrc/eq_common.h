@@ -1,8 +1,10 @@
 // Shared device-side definitions of the EasyQuant HIP path (gfx950 only).
 //
 // Arithmetic contract of the whole path (what makes results reproducible bit for bit):
-//   * element work in binary32, one rounding per operation (compiled with
-//     -ffp-contract=off: no fused multiply-add is formed from separate operations);
+//   * scale s = r / D and 1 / s in binary32; the level of an element is the exact product
+//     x * (1 / s) rounded once to the nearest integer, ties to even (Eq. 1), then clamped
+//     (compiled with -ffp-contract=off: no fused multiply-add is formed from separate
+//     operations; the fused multiply-adds below are written out on purpose);
 //   * the two sums of the gradient (Eq. 2), A = sum c^2 and B = sum x c, are exact;
 //   * the scalar recurrence (loss, gradient, Adam on the range; Sec. 4.2) in binary64,
 //     the range rounded to binary32 after every step.
@@ -56,6 +58,10 @@ struct KParams {
   float pad_;
   double n;         // threshold of Eq. 3
   double lr, b1, b2, eps;
+  double rD64;      // RN(1 / D) in binary64
+  float rD32;       // RN(1 / D) in binary32
+  float pad2_;
+  const double* adam_tab;   // device: per step t (0-based) {1 - b1^(t+1), RN(1 / that), 1 - b2^(t+1), RN(1 / that)}
 };
 
 // 128-bit streaming load: the data is used once, so it is marked non-temporal.
@@ -125,32 +131,80 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* red) {
   return t;
 }
 
+// ---- Eq. 1: levels -----------------------------------------------------------------------
+// 1.5 * 2^23: fma(x, inv, kMagic) is the exact x * inv plus kMagic rounded once to binary32;
+// in [2^23, 2^24) the spacing is 1, so the result is kMagic + rint(x * inv) (ties to even;
+// kMagic is even) whenever |x * inv| < 2^22.  The range floor r >= r0 / 1024 keeps
+// |x * inv| <= 1024 D < 2^18.  Clamping after the rounding equals clamping before it
+// because the bounds are integers.
+constexpr float kMagic = 12582912.0f;
+__device__ __forceinline__ float level_of(float x, float inv, float clo, float chi) {
+  return fminf(fmaxf(__builtin_fmaf(x, inv, kMagic) - kMagic, clo), chi);
+}
+
+// ---- division by a value whose correctly rounded reciprocal is known -----------------------
+// q0 = a * rb; two residual corrections with fused multiply-adds.  With rb = RN(1 / b) the
+// last step returns the correctly rounded a / b (Markstein's theorem), i.e. the same bits as
+// an IEEE division, at 5 operations instead of ~30.
+// (binary64: the operands here are sums and products of binary32-range quantities, far from
+// the ends of the binary64 range, so no guard is needed; a zero numerator returns zero.)
+__host__ __device__ __forceinline__ double div_known_rcp(double a, double b, double rb) {
+  const double q0 = a * rb;
+  const double r0 = fma(-b, q0, a);
+  const double q1 = fma(r0, rb, q0);
+  const double r1 = fma(-b, q1, a);
+  return fma(r1, rb, q1);
+}
+// binary32: a range close to the subnormals (or to overflow) takes the ordinary division.
+__host__ __device__ __forceinline__ float div_known_rcp(float a, float b, float rb) {
+  const float aa = fabsf(a);
+  if (!(aa > 1e-30f && aa < 1e30f)) return a / b;
+  const float q0 = a * rb;
+  const float r0 = fmaf(-b, q0, a);
+  const float q1 = fmaf(r0, rb, q0);
+  const float r1 = fmaf(-b, q1, a);
+  return fmaf(r1, rb, q1);
+}
+
 // ---- the scalar recurrence --------------------------------------------------------------
 // Loss (minus the constant sum x^2) and its derivative with respect to the range at scale
 // s = r / D, from the exact sums A and B:  loss = s^2 A - 2 s B + sum x^2;
 // d loss / d s = 2 (s A - B) is Eq. 2 with Q[x_i] = s c_i; d s / d r = 1 / D.
-__device__ __forceinline__ void loss_and_grad(float s32, double A, double B, float D, double& J, double& g) {
+__device__ __forceinline__ void loss_and_grad(const KParams& kp, float s32, double A, double B, double& J, double& g) {
   const double s = (double)s32;
   const double e = s * A - B;
   J = s * (e - B);
-  g = (2.0 * e) / (double)D;
+  g = div_known_rcp(2.0 * e, (double)kp.D, kp.rD64);
 }
 
 // Adam (bias-corrected) on the range of one unit; moments in binary64.
+// The bias corrections 1 - beta^t are the same for every unit, so the host tabulates them
+// together with their correctly rounded reciprocals (kp.adam_tab) and the two divisions by
+// them cost 5 operations each.
 struct Adam {
-  double m, v, p1, p2;
-  __device__ __forceinline__ void init() { m = 0.0; v = 0.0; p1 = 1.0; p2 = 1.0; }
-  __device__ __forceinline__ float step(const KParams& kp, float r32, double g, double floor_r) {
+  double m, v;
+  __device__ __forceinline__ void init() { m = 0.0; v = 0.0; }
+  // bc = {1 - b1^t, RN(1 / .), 1 - b2^t, RN(1 / .)} of this step, loaded by the caller ahead of
+  // the evaluation so that the memory latency is hidden behind it
+  __device__ __forceinline__ float step(const KParams& kp, const double (&bc)[4], float r32, double g, double floor_r) {
     m = kp.b1 * m + (1.0 - kp.b1) * g;
     v = kp.b2 * v + (1.0 - kp.b2) * (g * g);
-    p1 = p1 * kp.b1;
-    p2 = p2 * kp.b2;
-    const double mh = m / (1.0 - p1);
-    const double vh = v / (1.0 - p2);
+    const double mh = div_known_rcp(m, bc[0], bc[1]);
+    const double vh = div_known_rcp(v, bc[2], bc[3]);
     const double r64 = (double)r32 - kp.lr * (mh / (sqrt(vh) + kp.eps));
     return (float)fmax(r64, floor_r);
   }
 };
+__device__ __forceinline__ void load_bias_corrections(const KParams& kp, int t, double (&bc)[4]) {
+  const double2* p = reinterpret_cast<const double2*>(kp.adam_tab + 4 * t);
+  const double2 a = p[0], b = p[1];
+  bc[0] = a.x; bc[1] = a.y; bc[2] = b.x; bc[3] = b.y;
+}
+// scale and reciprocal scale of a range (binary32, correctly rounded)
+__device__ __forceinline__ void scale_of(const KParams& kp, float r32, float& s32, float& inv) {
+  s32 = div_known_rcp(r32, kp.D, kp.rD32);
+  inv = 1.0f / s32;
+}
 
 // Initial range and zero-point of a unit from the min / max of its normal values (outliers
 // already replaced by 0).  Returns false for a unit that is not optimised (all zero).

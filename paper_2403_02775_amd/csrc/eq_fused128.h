@@ -2,10 +2,12 @@
 //
 // A workgroup walks a range of rows.  Rows are staged into an LDS pool (eq_rowstage.h: one
 // coalesced HBM read, statistics, outlier compaction); whenever the pool holds 256 units
-// every lane takes one, pulls its 128 values into registers and runs ALL range-optimisation
-// iterations there (Sec. 4.2 / Algorithm 1, second step) with no memory traffic at all:
-// no cross-lane reduction, and the scalar Adam step is paid once per 128 elements.  Units
-// left over (< 256) are carried to the next fill, so lanes idle only at the end of a range.
+// every lane takes one and runs ALL range-optimisation iterations on it (Sec. 4.2 /
+// Algorithm 1, second step) without touching HBM: the unit's fixed-point planes live in
+// registers, its 16-bit values are re-read from the lane's own LDS slot in each iteration
+// (conflict-free 128-bit reads, ~3 % of the instruction stream), there is no cross-lane
+// reduction, and the scalar Adam step is paid once per 128 elements.  Units left over
+// (< 256) are carried to the next fill, so lanes idle only at the end of a range.
 //
 // Exact sums without binary64 in the inner loop: x is held as a block fixed-point integer
 // xi = x * 2^q (|xi| < 2^30, q from the unit's largest magnitude), split into two signed
@@ -27,7 +29,6 @@ constexpr int kPairs = kG / 2;
 constexpr int kSlotBytes = 272;       // 256 B of data + 16 B of padding (bank spread)
 constexpr int kSlotChunks = 17;
 constexpr int kCodeOff = 128;         // packed codes are assembled in the upper half of the slot
-constexpr float kMagic = 12582912.0f; // 1.5 * 2^23: (t + kMagic) rounds t to an integer, ties to even
 
 struct WorkItem {
   int32_t mat, row0, nrows, pad_;
@@ -35,46 +36,79 @@ struct WorkItem {
 
 typedef short short2_t __attribute__((ext_vector_type(2)));
 
-// Bit patterns of (clamp(x * inv) + kMagic) for the two elements of a packed pair.  The low
-// 16 bits of each pattern are the signed level c in two's complement.
+// Bit patterns of kMagic + level for the two elements of a packed pair (see level_of): the low
+// 16 bits of each pattern are the signed level c in two's complement.  mlo / mhi are the
+// level bounds plus kMagic.  For fp16 the widening folds into the multiply-add (v_fma_mix_f32).
 template <int DT>
-__device__ __forceinline__ void pair_levels(uint32_t w, float inv, float clo, float chi, uint32_t& f0, uint32_t& f1) {
-  float t0, t1;
+__device__ __forceinline__ void pair_levels(uint32_t w, float inv, float mlo, float mhi, uint32_t& f0, uint32_t& f1) {
+  float x0, x1;
   if (DT == EQ_F16) {
-    // fma(x, inv, 0) == x * inv (one rounding); written as fma so that the half -> float
-    // widening folds into the instruction (v_fma_mix_f32)
-    t0 = __builtin_fmaf(__half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu))), inv, 0.0f);
-    t1 = __builtin_fmaf(__half2float(__ushort_as_half((unsigned short)(w >> 16))), inv, 0.0f);
+    x0 = __half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu)));
+    x1 = __half2float(__ushort_as_half((unsigned short)(w >> 16)));
   } else {
-    t0 = __uint_as_float(w << 16) * inv;
-    t1 = __uint_as_float(w & 0xFFFF0000u) * inv;
+    x0 = __uint_as_float(w << 16);
+    x1 = __uint_as_float(w & 0xFFFF0000u);
   }
-  f0 = __float_as_uint(__builtin_amdgcn_fmed3f(t0, clo, chi) + kMagic);
-  f1 = __float_as_uint(__builtin_amdgcn_fmed3f(t1, clo, chi) + kMagic);
+  f0 = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, kMagic), mlo, mhi));
+  f1 = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, kMagic), mlo, mhi));
 }
 
-// One evaluation of Eq. 1 / Eq. 2 for the unit held in registers.
+// Levels of the 8 elements of one 16-byte chunk as four packed int16 pairs.  Written stage by
+// stage (8 multiply-adds, 8 clamps, 4 packs) so that neighbouring instructions are independent:
+// a dependent instruction cannot issue back to back, and only two wavefronts share a SIMD.
 template <int DT>
-__device__ __forceinline__ void eval_regs(const uint32_t (&xr)[kPairs], const uint32_t (&H)[kPairs],
-                                          const uint32_t (&Lo)[kPairs], float inv, float clo, float chi, int q,
-                                          double& A, double& B) {
-  int a = 0, bh = 0, bl = 0;
+__device__ __forceinline__ void chunk_levels(const uint4 v, float inv, float mlo, float mhi, short2_t (&c)[4]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  float t[8];
 #pragma unroll
-  for (int k = 0; k < kPairs; ++k) {
-    uint32_t f0, f1;
-    // The packed pair is passed through an empty asm so that the optimiser treats it as new
-    // in every evaluation: otherwise it hoists the 128 widenings out of the iteration loop
-    // and the unit no longer fits the register file.
-    uint32_t w = xr[k];
-    asm volatile("" : "+v"(w));
-    pair_levels<DT>(w, inv, clo, chi, f0, f1);
-    const short2_t c = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm(f1, f0, 0x05040100u));
-    a = __builtin_amdgcn_sdot2(c, c, a, false);
-    bh = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, H[k]), c, bh, false);
-    bl = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[k]), c, bl, false);
+  for (int j = 0; j < 4; ++j) {
+    float x0, x1;
+    if (DT == EQ_F16) {
+      x0 = __half2float(__ushort_as_half((unsigned short)(w[j] & 0xFFFFu)));
+      x1 = __half2float(__ushort_as_half((unsigned short)(w[j] >> 16)));
+    } else {
+      x0 = __uint_as_float(w[j] << 16);
+      x1 = __uint_as_float(w[j] & 0xFFFF0000u);
+    }
+    t[2 * j] = __builtin_fmaf(x0, inv, kMagic);
+    t[2 * j + 1] = __builtin_fmaf(x1, inv, kMagic);
   }
-  A = (double)a;
-  B = ldexp((double)bh * 65536.0 + (double)bl, -q);     // exact: |.| < 2^47
+  __builtin_amdgcn_sched_barrier(0);       // keep the stages apart: the scheduler would re-serialise them
+#pragma unroll
+  for (int j = 0; j < 8; ++j) t[j] = __builtin_amdgcn_fmed3f(t[j], mlo, mhi);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    c[j] = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm(__float_as_uint(t[2 * j + 1]), __float_as_uint(t[2 * j]), 0x05040100u));
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// One evaluation of Eq. 1 / Eq. 2 for the lane's unit: values from its LDS slot (read one
+// chunk ahead of use), planes from registers.  The compiler barrier keeps the reads inside
+// the iteration loop (hoisted, they would pin 64 more registers).
+template <int DT>
+__device__ __forceinline__ void eval_regs(const unsigned char* slot, const uint32_t (&H)[kPairs],
+                                          const uint32_t (&Lo)[kPairs], float inv, float mlo, float mhi, int q,
+                                          double& A, double& B) {
+  asm volatile("" ::: "memory");
+  int a[4] = {0, 0, 0, 0}, bh[4] = {0, 0, 0, 0}, bl[4] = {0, 0, 0, 0};   // four chains each
+  uint4 nxt = *reinterpret_cast<const uint4*>(slot);
+#pragma unroll
+  for (int ch = 0; ch < 16; ++ch) {
+    const uint4 cur = nxt;
+    if (ch + 1 < 16) nxt = *reinterpret_cast<const uint4*>(slot + (ch + 1) * 16);
+    short2_t c[4];
+    chunk_levels<DT>(cur, inv, mlo, mhi, c);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] = __builtin_amdgcn_sdot2(c[j], c[j], a[j], false);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bh[j] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, H[4 * ch + j]), c[j], bh[j], false);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bl[j] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[4 * ch + j]), c[j], bl[j], false);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  A = (double)((a[0] + a[1]) + (a[2] + a[3]));
+  B = ldexp((double)((bh[0] + bh[1]) + (bh[2] + bh[3])) * 65536.0 + (double)((bl[0] + bl[1]) + (bl[2] + bl[3])), -q);  // exact: |.| < 2^47
 }
 
 // The same from the LDS slot with a binary64 accumulation (units the fixed-point form cannot hold).
@@ -88,7 +122,7 @@ __device__ __forceinline__ void eval_slot(const unsigned char* slot, float inv, 
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const float xv = widen16<DT>((w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
-      const float c = rintf(fminf(fmaxf(xv * inv, clo), chi));
+      const float c = level_of(xv, inv, clo, chi);
       const int ci = (int)c;
       a += ci * ci;
       b += (double)(xv * c);
@@ -107,24 +141,26 @@ __device__ __forceinline__ float optimise_range(const KParams& kp, float r0, Eva
   Adam ad;
   ad.init();
   for (int t = 0; t < kp.iters; ++t) {
-    const float s32 = r32 / kp.D;
-    const float inv = 1.0f / s32;
+    double bc[4];
+    load_bias_corrections(kp, t, bc);      // issued before the evaluation, consumed after it
+    float s32, inv;
+    scale_of(kp, r32, s32, inv);
     double A, B, J, g;
     ev(inv, A, B);
-    loss_and_grad(s32, A, B, kp.D, J, g);
+    loss_and_grad(kp, s32, A, B, J, g);
     if (J < J_best) {
       J_best = J;
       r_sel = r32;
     }
-    r32 = ad.step(kp, r32, g, floor_r);
+    r32 = ad.step(kp, bc, r32, g, floor_r);
   }
   if (kp.select == EQ_SELECT_LAST) return r32;
   if (kp.iters > 0) {
-    const float s32 = r32 / kp.D;
-    const float inv = 1.0f / s32;
+    float s32, inv;
+    scale_of(kp, r32, s32, inv);
     double A, B, J, g;
     ev(inv, A, B);
-    loss_and_grad(s32, A, B, kp.D, J, g);
+    loss_and_grad(kp, s32, A, B, J, g);
     if (J < J_best) r_sel = r32;
   }
   return r_sel;
@@ -165,44 +201,49 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
       const bool valid = slot_i < take;
       unsigned char* slot = pool + (size_t)(valid ? slot_i : base) * kSlotBytes;
 
-      // ---- the unit's values: LDS -> registers ----
-      uint32_t xr[kPairs];
+      // ---- range of the unit, and its block fixed-point planes ----
+      // xi = x * 2^q with |xi| < 2^30, split into signed 16-bit planes xi = 65536 H + L
+      float vmin = 0.0f, vmax = 0.0f;
 #pragma unroll
       for (int ch = 0; ch < 16; ++ch) {
         const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-        xr[4 * ch + 0] = v.x; xr[4 * ch + 1] = v.y; xr[4 * ch + 2] = v.z; xr[4 * ch + 3] = v.w;
-      }
-      float vmin = 0.0f, vmax = 0.0f;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-      for (int k = 0; k < kPairs; ++k) {
-        const float x0 = widen16<DT>(xr[k] & 0xFFFFu), x1 = widen16<DT>(xr[k] >> 16);
-        vmin = fminf(vmin, fminf(x0, x1));
-        vmax = fmaxf(vmax, fmaxf(x0, x1));
+        for (int j = 0; j < 4; ++j) {
+          const float x0 = widen16<DT>(w[j] & 0xFFFFu), x1 = widen16<DT>(w[j] >> 16);
+          vmin = fminf(vmin, fminf(x0, x1));
+          vmax = fmaxf(vmax, fmaxf(x0, x1));
+        }
       }
       float r0;
       int z;
       const bool active = init_unit(kp, vmin, vmax, r0, z);
       const float clo = (float)(-z), chi = (float)(kp.L - z);
+      const float mlo = clo + kMagic, mhi = chi + kMagic;     // exact: small integers next to 1.5 * 2^23
       const float r_start = active ? r0 : kp.D;              // an all-zero unit keeps s = 1
-
-      // ---- block fixed point: xi = x * 2^q, |xi| < 2^30, split into 16-bit planes ----
       int E = 0;
       (void)frexpf(fmaxf(-vmin, vmax), &E);                  // max |x| < 2^E
       const int q = 30 - E;
       uint32_t H[kPairs], Lo[kPairs];
       bool exact = true;
 #pragma unroll
-      for (int k = 0; k < kPairs; ++k) {
-        const float y0 = ldexpf(widen16<DT>(xr[k] & 0xFFFFu), q);
-        const float y1 = ldexpf(widen16<DT>(xr[k] >> 16), q);
-        const int i0 = (int)y0, i1 = (int)y1;
-        exact = exact && ((float)i0 == y0) && ((float)i1 == y1);
-        Lo[k] = __builtin_amdgcn_perm((uint32_t)i1, (uint32_t)i0, 0x05040100u);
-        H[k] = __builtin_amdgcn_perm((uint32_t)(i1 + 0x8000), (uint32_t)(i0 + 0x8000), 0x07060302u);
+      for (int ch = 0; ch < 16; ++ch) {
+        const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int k = 4 * ch + j;
+          const float y0 = ldexpf(widen16<DT>(w[j] & 0xFFFFu), q);
+          const float y1 = ldexpf(widen16<DT>(w[j] >> 16), q);
+          const int i0 = (int)y0, i1 = (int)y1;
+          exact = exact && ((float)i0 == y0) && ((float)i1 == y1);
+          Lo[k] = __builtin_amdgcn_perm((uint32_t)i1, (uint32_t)i0, 0x05040100u);
+          H[k] = __builtin_amdgcn_perm((uint32_t)(i1 + 0x8000), (uint32_t)(i0 + 0x8000), 0x07060302u);
+        }
       }
 
       float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
-        eval_regs<DT>(xr, H, Lo, inv, clo, chi, q, A, B);
+        eval_regs<DT>(slot, H, Lo, inv, mlo, mhi, q, A, B);
       });
       if (!exact) {
         r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
@@ -211,39 +252,44 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
       }
 
       // ---- emit (Algorithm 1, third step) ----
-      const float s32 = r_sel / kp.D;
-      const float inv = 1.0f / s32;
+      float s32, inv;
+      scale_of(kp, r_sel, s32, inv);
       __syncthreads();              // every lane has finished reading slots that are not its own
       if (valid) {
         if (kp.bits == 4) {
-          uint32_t* dst = reinterpret_cast<uint32_t*>(slot + kCodeOff);
+          // all 16 words first (they overwrite the upper half of the values), then one store burst
+          uint32_t o[16];
 #pragma unroll
-          for (int wd = 0; wd < 16; wd += 4) {
-            uint32_t o[4];
+          for (int ch = 0; ch < 16; ++ch) {
+            const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            uint32_t word = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              uint32_t word = 0;
-#pragma unroll
-              for (int k = 0; k < 4; ++k) {
-                uint32_t f0, f1;
-                pair_levels<DT>(xr[(wd + j) * 4 + k], inv, clo, chi, f0, f1);
-                word |= ((f0 + (uint32_t)z) & 0xFu) << (8 * k);
-                word |= ((f1 + (uint32_t)z) & 0xFu) << (8 * k + 4);
-              }
-              o[j] = word;
+              uint32_t f0, f1;
+              pair_levels<DT>(w[j], inv, mlo, mhi, f0, f1);
+              word |= ((f0 + (uint32_t)z) & 0xFu) << (8 * j);
+              word |= ((f1 + (uint32_t)z) & 0xFu) << (8 * j + 4);
             }
-            *reinterpret_cast<uint4*>(dst + wd) = make_uint4(o[0], o[1], o[2], o[3]);
+            o[ch] = word;
           }
-        } else {
-          // unsigned codes as bytes in the lower half of the slot, then a bit-stream pack
-          uint32_t* bytes = reinterpret_cast<uint32_t*>(slot);
+          uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);
 #pragma unroll
-          for (int k = 0; k < kPairs; k += 2) {
-            uint32_t f0, f1, f2, f3;
-            pair_levels<DT>(xr[k], inv, clo, chi, f0, f1);
-            pair_levels<DT>(xr[k + 1], inv, clo, chi, f2, f3);
-            bytes[k >> 1] = ((f0 + (uint32_t)z) & 0xFFu) | (((f1 + (uint32_t)z) & 0xFFu) << 8) |
-                            (((f2 + (uint32_t)z) & 0xFFu) << 16) | (((f3 + (uint32_t)z) & 0xFFu) << 24);
+          for (int wd = 0; wd < 4; ++wd) dst[wd] = make_uint4(o[4 * wd], o[4 * wd + 1], o[4 * wd + 2], o[4 * wd + 3]);
+        } else {
+          // unsigned codes as bytes over the front of the slot (chunk ch yields bytes 8 ch .. 8 ch + 7,
+          // never ahead of the values still to be read), then a bit-stream pack into the upper half
+          for (int ch = 0; ch < 16; ++ch) {
+            const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+            uint32_t f0, f1, f2, f3, f4, f5, f6, f7;
+            pair_levels<DT>(v.x, inv, mlo, mhi, f0, f1);
+            pair_levels<DT>(v.y, inv, mlo, mhi, f2, f3);
+            pair_levels<DT>(v.z, inv, mlo, mhi, f4, f5);
+            pair_levels<DT>(v.w, inv, mlo, mhi, f6, f7);
+            const uint32_t zz = (uint32_t)z;
+            const uint32_t b0 = ((f0 + zz) & 0xFFu) | (((f1 + zz) & 0xFFu) << 8) | (((f2 + zz) & 0xFFu) << 16) | (((f3 + zz) & 0xFFu) << 24);
+            const uint32_t b1 = ((f4 + zz) & 0xFFu) | (((f5 + zz) & 0xFFu) << 8) | (((f6 + zz) & 0xFFu) << 16) | (((f7 + zz) & 0xFFu) << 24);
+            *reinterpret_cast<uint2*>(slot + ch * 8) = make_uint2(b0, b1);
           }
           const unsigned char* ub = slot;
           uint32_t* dst = reinterpret_cast<uint32_t*>(slot + kCodeOff);

@@ -24,7 +24,7 @@ __device__ __forceinline__ void wave_eval_unit(const unsigned char* x, uint32_t 
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const float xv = widen16<DT>((w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
-      const float c = rintf(fminf(fmaxf(xv * inv, clo), chi));
+      const float c = level_of(xv, inv, clo, chi);
       const int ci = (int)c;
       a += ci * ci;
       b += (double)(xv * c);
@@ -115,28 +115,30 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_generic(const MatDesc*
       Adam ad;
       ad.init();
       for (int t = 0; t < kp.iters; ++t) {
-        const float s32 = r32 / kp.D;
-        const float inv = 1.0f / s32;
+        double bc[4];
+        load_bias_corrections(kp, t, bc);
+        float s32, inv;
+        scale_of(kp, r32, s32, inv);
         double A, B, J, g;
         wave_eval_unit<DT>(x, nch_u, lane, inv, clo, chi, A, B);
-        loss_and_grad(s32, A, B, kp.D, J, g);
+        loss_and_grad(kp, s32, A, B, J, g);
         if (J < J_best) { J_best = J; r_sel = r32; }
-        r32 = ad.step(kp, r32, g, floor_r);
+        r32 = ad.step(kp, bc, r32, g, floor_r);
       }
       if (kp.select == EQ_SELECT_LAST) {
         r_sel = r32;
       } else if (kp.iters > 0) {
-        const float s32 = r32 / kp.D;
-        const float inv = 1.0f / s32;
+        float s32, inv;
+        scale_of(kp, r32, s32, inv);
         double A, B, J, g;
         wave_eval_unit<DT>(x, nch_u, lane, inv, clo, chi, A, B);
-        loss_and_grad(s32, A, B, kp.D, J, g);
+        loss_and_grad(kp, s32, A, B, J, g);
         if (J < J_best) r_sel = r32;
       }
     }
     // ---- emit (Algorithm 1, third step): codes at the chosen range, 32 elements per lane ----
-    const float s32 = r_sel / kp.D;
-    const float inv = 1.0f / s32;
+    float s32, inv;
+    scale_of(kp, r_sel, s32, inv);
     const uint32_t nelem = (uint32_t)md.G;
     const unsigned short* xe = reinterpret_cast<const unsigned short*>(x);
     uint32_t* wrow = md.codes + row * (int64_t)md.words_per_row + (int64_t)u * ((int64_t)nelem * kp.bits / 32);
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_generic(const MatDesc*
       int nb = 0, wi = 0;
       for (uint32_t e = 0; e < 32u && g32 * 32u + e < nelem; ++e) {
         const float xv = widen16<DT>(xe[g32 * 32u + e]);
-        const int c = (int)rintf(fminf(fmaxf(xv * inv, clo), chi));
+        const int c = (int)level_of(xv, inv, clo, chi);
         acc |= (unsigned long long)(uint32_t)(c + z) << nb;
         nb += kp.bits;
         if (nb >= 32) {

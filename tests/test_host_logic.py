@@ -1,0 +1,58 @@
+"""Host-side logic of the library that can be checked without a GPU."""
+import ctypes
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2403_02775_amd as eqg
+    if not os.path.exists(eqg.lib_path()):
+        from paper_2403_02775_amd.build import build
+        build()
+    return eqg.lib()
+
+
+def test_division_by_known_reciprocal_is_the_ieee_quotient(lib):
+    """The multiply-add sequence the kernels use for m / (1 - beta^t), v / (1 - beta^t), 2e / D and
+    r / D must return the correctly rounded quotient.  Checked against exact rational arithmetic
+    (Fraction -> float is correctly rounded) and against the hardware division."""
+    rng = np.random.default_rng(0)
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))
+    divisors = [7.0, 15.0, 3.0, 1.0, 127.0, 255.0]
+    p1 = p2 = 1.0
+    for _ in range(500):
+        p1 *= b1
+        p2 *= b2
+        divisors += [1.0 - p1, 1.0 - p2]
+    n = 0
+    for b in divisors:
+        for a in np.concatenate([rng.standard_normal(40) * 10.0 ** rng.integers(-12, 6, 40), [0.0, -0.0, 1e-300, 3e280]]):
+            a = float(a)
+            got = lib.eq_diag_div_f64(a, b)
+            want = a / b
+            assert got == want or (math.isnan(got) and math.isnan(want)), (a, b, got, want)
+            if a != 0 and abs(a) < 1e200 and abs(a) > 1e-200:
+                assert got == float(Fraction(a) / Fraction(b))
+            n += 1
+    assert n > 40000
+    for b in (7.0, 15.0, 3.0, 1.0, 127.0, 255.0):
+        a32 = (rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 3, 20000)).astype(np.float32)
+        for a in a32[:3000]:
+            got = lib.eq_diag_div_f32(ctypes.c_float(float(a)), ctypes.c_float(b))
+            assert np.float32(got) == np.float32(a) / np.float32(b), (a, b)
+
+
+def test_work_split_env_override_does_not_change_workspace_contract(lib, monkeypatch):
+    import paper_2403_02775_amd as eqg
+    p = eqg.Params(group_size=128)
+    a = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
+    monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", "100000")
+    b = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
+    monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", "256")
+    c = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
+    assert a > 0 and b > 0 and c >= a
