@@ -59,6 +59,25 @@ def algorithmic_bytes(Ws, bits, n_outliers):
     return elems * 2 + elems * bits // 8 + units * 5 + n_outliers * 6 + (rows + len(Ws)) * 4
 
 
+def measured_traffic(workload, iters):
+    """HBM bytes per step of the main kernels from the committed counter summary (rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size), if one exists for this workload."""
+    path = os.path.join(ROOT, "profiles", f"quantize_units128_{workload}_hbm_traffic.txt")
+    if workload is None or not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            vals[k.strip()] = v.strip()
+    try:
+        if int(vals.get("iters", -1)) != iters:
+            return None
+        return float(vals["fetch_bytes_per_step"]) + float(vals["write_bytes_per_step"])
+    except (KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(Ws, gp_kwargs, sample_rows):
     """The oracle, as it stands, on the first `sample_rows` rows of the first matrix."""
     import numpy as np
@@ -83,6 +102,9 @@ def main():
     ap.add_argument("--lr", type=float, default=1e-3)
     ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
     ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the first matrix given to the CPU oracle (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 4 GiB device-to-device copy (torch's copy kernel) so that a counter run "
+                         "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) has a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path needs no communication; see DESIGN.md); run with --gpus 1")
@@ -103,6 +125,14 @@ def main():
     torch.cuda.synchronize()
     log(f"[mem] inputs {sum(w.numel() for w in Ws) * 2 / 1e9:.1f} GB, workspace {ws_bytes / 1e9:.1f} GB, "
         f"allocated {torch.cuda.memory_allocated() / 1e9:.1f} GB")
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[calibration] copied 4 GiB (reads 4 GiB, writes 4 GiB)")
+        del src, dst
 
     def step():
         eqg.eq_quantize_batch(Ws, gp, outs, ws)
@@ -144,6 +174,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": alg_bytes / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
+    roof["traffic"] = measured_traffic(args.workload if args.layers < 0 else None, args.iters)
     roof.update({"kernel": "quantize_units128", "launches_per_step": launches / args.steps,
                  "kernel_ms_per_step": kern_ms / args.steps, "avg_launch_ms": kern_ms / max(launches, 1),
                  "algorithmic_bytes": alg_bytes, "hbm_frac": hbm_frac, "alu_frac": alu_frac,

@@ -214,6 +214,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
           vmin = fminf(vmin, fminf(x0, x1));
           vmax = fmaxf(vmax, fmaxf(x0, x1));
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
       float r0;
       int z;
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
       (void)frexpf(fmaxf(-vmin, vmax), &E);                  // max |x| < 2^E
       const int q = 30 - E;
       uint32_t H[kPairs], Lo[kPairs];
-      bool exact = true;
+      uint32_t frac_bits = 0;          // OR of the bit patterns of y - trunc(y): zero iff every y is an integer
 #pragma unroll
       for (int ch = 0; ch < 16; ++ch) {
         const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
@@ -236,11 +237,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
           const float y0 = ldexpf(widen16<DT>(w[j] & 0xFFFFu), q);
           const float y1 = ldexpf(widen16<DT>(w[j] >> 16), q);
           const int i0 = (int)y0, i1 = (int)y1;
-          exact = exact && ((float)i0 == y0) && ((float)i1 == y1);
+          frac_bits |= __float_as_uint(y0 - (float)i0) | __float_as_uint(y1 - (float)i1);
           Lo[k] = __builtin_amdgcn_perm((uint32_t)i1, (uint32_t)i0, 0x05040100u);
           H[k] = __builtin_amdgcn_perm((uint32_t)(i1 + 0x8000), (uint32_t)(i0 + 0x8000), 0x07060302u);
         }
+        // pin the running flag here: otherwise the OR tree is rebalanced, every y and trunc(y) stays
+        // live to the end of the unit, and 256 values are spilled to scratch memory
+        asm volatile("" : "+v"(frac_bits));
       }
+      const bool exact = (frac_bits << 1) == 0;
 
       float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
         eval_regs<DT>(slot, H, Lo, inv, mlo, mhi, q, A, B);
@@ -272,6 +277,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
               word |= ((f1 + (uint32_t)z) & 0xFu) << (8 * j + 4);
             }
             o[ch] = word;
+            __builtin_amdgcn_sched_barrier(0);
           }
           uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);
 #pragma unroll
