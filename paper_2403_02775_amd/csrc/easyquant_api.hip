@@ -90,6 +90,7 @@ KParams make_kparams(const eq_params* p) {
 // One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
 struct LaneClass {
   int32_t cols = 0, upr = 0;
+  int32_t threads = kThreads;           // workgroup size = units per round
   uint32_t pool_slots = 0;
   size_t lds_bytes = 0;
   size_t first_item = 0, n_items = 0;
@@ -157,18 +158,35 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     LaneClass lc;
     lc.cols = (int32_t)c;
     lc.upr = (int32_t)upr;
-    const int64_t g = std::gcd(upr, (int64_t)kThreads);
-    lc.pool_slots = (uint32_t)(upr >= kThreads && upr % kThreads == 0 ? upr : kThreads - g + upr);
-    lc.lds_bytes = 256 + (size_t)lc.pool_slots * kSlotBytes + (size_t)c / 8;
+    // Pool size: a round's worth of units minus what a fill can leave behind, plus one row.
+    // With 256-thread workgroups two pools must share the 160 KB of LDS of a compute unit;
+    // rows too long for that get one 512-thread workgroup per compute unit, whose pool is
+    // capped by the LDS (a fill that finds no room then runs a partly filled round).
+    constexpr size_t kLdsPerCu = 160 * 1024;
+    const size_t fixed = 256 + (size_t)c / 8;
+    auto pool_for = [&](int64_t nt) {
+      const int64_t gg = std::gcd(upr, nt);
+      return (int64_t)(upr >= nt && upr % nt == 0 ? upr : nt - gg + upr);
+    };
+    int64_t nt = kThreads;
+    int64_t slots = pool_for(nt);
+    if (fixed + (size_t)slots * kSlotBytes > kLdsPerCu / 2) {
+      nt = 512;
+      slots = std::min<int64_t>(pool_for(nt), (int64_t)((kLdsPerCu - 64 - fixed) / kSlotBytes));
+    }
+    lc.threads = (int32_t)nt;
+    lc.pool_slots = (uint32_t)slots;
+    lc.lds_bytes = fixed + (size_t)lc.pool_slots * kSlotBytes;
+    const int64_t g = std::gcd(upr, nt);
     // rows per work item: enough units to amortise the partly filled last round of an item,
     // few enough that the grid has several items per compute unit; a multiple of the period
     // after which rows fill whole rounds when that fits
-    int64_t target = std::min<int64_t>(16384, std::max<int64_t>(kThreads, total_units / 4096));
+    int64_t target = std::min<int64_t>(16384, std::max<int64_t>(nt, total_units / 4096));
     if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {   // tuning / test override
       const long v = std::atol(ov);
       if (v > 0) target = v;
     }
-    const int64_t period = kThreads / g;
+    const int64_t period = nt / g;
     int64_t rpi = std::max<int64_t>(1, target / upr);
     if (rpi >= period) rpi -= rpi % period;
     lc.first_item = pl.work.size();
@@ -240,18 +258,24 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
       EQ_HIP(hipGetLastError());
     }
   }
-  static thread_local size_t lds_set[2][2] = {{0, 0}, {0, 0}};   // [kernel][dtype]: largest LDS size enabled so far
+  static thread_local size_t lds_set[3][2] = {{0, 0}, {0, 0}, {0, 0}};   // [kernel][dtype]: largest LDS size enabled so far
   for (const LaneClass& lc : pl.classes) {
     if (lc.n_items == 0) continue;
-    if (lc.lds_bytes > 65536 && lc.lds_bytes > lds_set[1][DT]) {
-      EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_units128<DT>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
-      lds_set[1][DT] = lc.lds_bytes;
+    const int which = lc.threads == 512 ? 2 : 1;
+    const void* fn = which == 2 ? reinterpret_cast<const void*>(&quantize_units128<DT, 512>)
+                                : reinterpret_cast<const void*>(&quantize_units128<DT, kThreads>);
+    if (lc.lds_bytes > 65536 && lc.lds_bytes > lds_set[which][DT]) {
+      EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
+      lds_set[which][DT] = lc.lds_bytes;
     }
     {
       ScopedKernelTimer tm(st);
-      hipLaunchKernelGGL(quantize_units128<DT>, dim3((unsigned)lc.n_items), dim3(kThreads), lc.lds_bytes, st, dmats,
-                         ditems + lc.first_item, kp, lc.pool_slots);
+      if (which == 2)
+        hipLaunchKernelGGL((quantize_units128<DT, 512>), dim3((unsigned)lc.n_items), dim3(512), lc.lds_bytes, st, dmats,
+                           ditems + lc.first_item, kp, lc.pool_slots);
+      else
+        hipLaunchKernelGGL((quantize_units128<DT, kThreads>), dim3((unsigned)lc.n_items), dim3(kThreads), lc.lds_bytes, st,
+                           dmats, ditems + lc.first_item, kp, lc.pool_slots);
     }
     EQ_HIP(hipGetLastError());
   }

@@ -18,9 +18,10 @@
 
 namespace eq {
 
-constexpr int kThreads = 256;            // workgroup size of every kernel here
+constexpr int kThreads = 256;            // default workgroup size
 constexpr int kWave = 64;                // CDNA wavefront
 constexpr int kWaves = kThreads / kWave;
+constexpr int kMaxWaves = 8;             // largest workgroup any kernel here uses: 512 threads
 
 // One matrix of a batch: inputs, outputs and its slice of the workspace.
 struct MatDesc {
@@ -109,25 +110,26 @@ __device__ __forceinline__ float wave_min(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
   return v;
 }
-// Block-wide sums through a small LDS scratch (kWaves entries); ends with a barrier.
+// Block-wide sums through a small LDS scratch (kMaxWaves entries) for any workgroup size up
+// to 512; the partial sums are combined in wavefront order by every thread; ends with a barrier.
 __device__ __forceinline__ double block_sum(double v, double* red) {
+  const int nw = (int)(blockDim.x / kWave);
   v = wave_sum(v);
   __syncthreads();
   if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
   __syncthreads();
   double t = red[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) t += red[w];
+  for (int w = 1; w < nw; ++w) t += red[w];
   return t;
 }
 __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* red) {
+  const int nw = (int)(blockDim.x / kWave);
   v = (uint32_t)wave_sum((int)v);
   __syncthreads();
   if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
   __syncthreads();
   uint32_t t = red[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) t += red[w];
+  for (int w = 1; w < nw; ++w) t += red[w];
   return t;
 }
 

@@ -166,8 +166,11 @@ __device__ __forceinline__ float optimise_range(const KParams& kp, float r0, Eva
   return r_sel;
 }
 
-template <int DT>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_units128(const MatDesc* __restrict__ mats,
+// NT = threads per workgroup = units per round: 256 when two workgroups' pools fit the LDS of
+// a compute unit, 512 (one workgroup per compute unit) for long rows; two wavefronts per SIMD
+// either way.
+template <int DT, int NT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_units128(const MatDesc* __restrict__ mats,
                                                               const WorkItem* __restrict__ items, KParams kp,
                                                               uint32_t pool_slots) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -186,17 +189,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 
   while (true) {
     // ---- fill: stage rows until a full round of units is available ----
-    while (next_row < row_end && pool_units < (uint32_t)kThreads && pool_units + upr <= pool_slots) {
+    while (next_row < row_end && pool_units < (uint32_t)NT && pool_units + upr <= pool_slots) {
       stage_row<DT, Padded128Layout>(md, kp, next_row, pool, pool_units * 16u, maskb, sc);
       pool_units += upr;
       ++next_row;
     }
     if (pool_units == 0) break;
-    const bool last = next_row >= row_end;
-    const uint32_t take = last ? pool_units : (pool_units / kThreads) * kThreads;
-    if (take == 0) break;                                    // cannot happen with pool_slots >= 255 + upr
+    // whole rounds; a partly filled one only at the end of the range or when the pool has no
+    // room for another row
+    const uint32_t take = pool_units >= (uint32_t)NT ? (pool_units / NT) * NT : pool_units;
 
-    for (uint32_t base = 0; base < take; base += kThreads) {
+    for (uint32_t base = 0; base < take; base += NT) {
       const uint32_t slot_i = base + threadIdx.x;
       const bool valid = slot_i < take;
       unsigned char* slot = pool + (size_t)(valid ? slot_i : base) * kSlotBytes;
@@ -333,7 +336,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const uint32_t left = pool_units - take;
     if (left) {
       const uint32_t nch = left * kSlotChunks, shift = take * kSlotChunks;
-      for (uint32_t c0 = 0; c0 < nch; c0 += kThreads) {
+      for (uint32_t c0 = 0; c0 < nch; c0 += NT) {
         const uint32_t ch = c0 + threadIdx.x;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (ch < nch) v = *reinterpret_cast<const uint4*>(pool + (size_t)(ch + shift) * 16u);

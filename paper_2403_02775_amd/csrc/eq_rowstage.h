@@ -23,9 +23,9 @@ struct Padded128Layout {
 };
 
 struct StageScratch {      // small LDS block used by the staging steps
-  double red[kWaves];
-  uint32_t redu[kWaves];
-  uint32_t wtot[kWaves];
+  double red[kMaxWaves];
+  uint32_t redu[kMaxWaves];
+  uint32_t wtot[kMaxWaves];
   unsigned long long base;
 };
 
@@ -35,7 +35,7 @@ template <int DT, class Layout>
 __device__ __forceinline__ void block_mean_sigma(const unsigned char* lds_row, uint32_t ch0, uint32_t nchunks,
                                                  StageScratch* sc, double& mu, double& sigma) {
   double s = 0.0;
-  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) {
+  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += blockDim.x) {
     const uint4 v = *reinterpret_cast<const uint4*>(lds_row + Layout::off(ch0 + ch));
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -47,7 +47,7 @@ __device__ __forceinline__ void block_mean_sigma(const unsigned char* lds_row, u
   const double cnt = (double)nchunks * 8.0;
   mu = block_sum(s, sc->red) / cnt;
   double q = 0.0;
-  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) {
+  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += blockDim.x) {
     const uint4 v = *reinterpret_cast<const uint4*>(lds_row + Layout::off(ch0 + ch));
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -83,7 +83,7 @@ __device__ __forceinline__ void stage_load_row(const MatDesc& md, int64_t row, u
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
   const uint4* src = reinterpret_cast<const uint4*>(md.W + row * md.ld);
   bool bad = false;
-  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) {
+  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += blockDim.x) {
     const uint4 v = load_stream128(src + ch);
     *reinterpret_cast<uint4*>(lds_row + Layout::off(ch0 + ch)) = v;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -104,7 +104,7 @@ __device__ __forceinline__ void stage_compact_row(const MatDesc& md, int64_t row
   const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   uint32_t cnt = 0;
   __syncthreads();
-  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) cnt += __popc((uint32_t)maskb[ch]);
+  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += blockDim.x) cnt += __popc((uint32_t)maskb[ch]);
   const uint32_t total = block_sum_u32(cnt, sc->redu);
   if (threadIdx.x == 0) {
     unsigned long long b = 0;
@@ -120,7 +120,7 @@ __device__ __forceinline__ void stage_compact_row(const MatDesc& md, int64_t row
   const unsigned long long base = sc->base;
   const bool fits = base != ~0ull;
   uint32_t running = 0;
-  for (uint32_t blk = 0; blk < nchunks; blk += kThreads) {
+  for (uint32_t blk = 0; blk < nchunks; blk += blockDim.x) {
     const uint32_t ch = blk + threadIdx.x;
     const uint32_t m = ch < nchunks ? (uint32_t)maskb[ch] : 0u;
     const uint32_t c = __popc(m);
@@ -134,10 +134,9 @@ __device__ __forceinline__ void stage_compact_row(const MatDesc& md, int64_t row
     if (lane == kWave - 1) sc->wtot[wave] = inc;
     __syncthreads();
     uint32_t before = 0, blk_total = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
+    for (uint32_t w = 0; w < blockDim.x / kWave; ++w) {
       const uint32_t t = sc->wtot[w];
-      if ((uint32_t)w < wave) before += t;
+      if (w < wave) before += t;
       blk_total += t;
     }
     if (m) {
@@ -178,7 +177,7 @@ __device__ __forceinline__ void stage_row(const MatDesc& md, const KParams& kp, 
   }
   const double thr = kp.n * sigma;
   const bool any_possible = sigma > 0.0;
-  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) {
+  for (uint32_t ch = threadIdx.x; ch < nchunks; ch += blockDim.x) {
     const uint4 v = *reinterpret_cast<const uint4*>(lds_row + Layout::off(ch0 + ch));
     maskb[ch] = any_possible ? (unsigned char)chunk_mask<DT>(v, mu, thr) : (unsigned char)0;
   }
