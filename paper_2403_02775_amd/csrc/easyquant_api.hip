@@ -91,6 +91,7 @@ KParams make_kparams(const eq_params* p) {
 struct LaneClass {
   int32_t cols = 0, upr = 0;
   int32_t threads = kThreads;           // workgroup size = units per round
+  int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
   uint32_t pool_slots = 0;
   size_t lds_bytes = 0;
   size_t first_item = 0, n_items = 0;
@@ -163,18 +164,22 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     // rows too long for that get one 512-thread workgroup per compute unit, whose pool is
     // capped by the LDS (a fill that finds no room then runs a partly filled round).
     constexpr size_t kLdsPerCu = 160 * 1024;
-    const size_t fixed = 256 + (size_t)c / 8;
+    const size_t fixed = kLdsHeader;
     auto pool_for = [&](int64_t nt) {
       const int64_t gg = std::gcd(upr, nt);
       return (int64_t)(upr >= nt && upr % nt == 0 ? upr : nt - gg + upr);
     };
     int64_t nt = kThreads;
     int64_t slots = pool_for(nt);
-    if (fixed + (size_t)slots * kSlotBytes > kLdsPerCu / 2) {
+    if (fixed + (size_t)slots * kSlotBytes > kLdsPerCu / 2 || c / 8 > 4 * kThreads) {
       nt = 512;
       slots = std::min<int64_t>(pool_for(nt), (int64_t)((kLdsPerCu - 64 - fixed) / kSlotBytes));
     }
     lc.threads = (int32_t)nt;
+    {
+      const int64_t per_thread = (c / 8 + nt - 1) / nt;
+      lc.chunks_per_thread = per_thread <= 1 ? (nt == 512 ? 2 : 1) : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : 8;
+    }
     lc.pool_slots = (uint32_t)slots;
     lc.lds_bytes = fixed + (size_t)lc.pool_slots * kSlotBytes;
     const int64_t g = std::gcd(upr, nt);
@@ -258,34 +263,35 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
       EQ_HIP(hipGetLastError());
     }
   }
-  static thread_local size_t lds_set[3][2] = {{0, 0}, {0, 0}, {0, 0}};   // [kernel][dtype]: largest LDS size enabled so far
   for (const LaneClass& lc : pl.classes) {
     if (lc.n_items == 0) continue;
-    const int which = lc.threads == 512 ? 2 : 1;
-    const void* fn = which == 2 ? reinterpret_cast<const void*>(&quantize_units128<DT, 512>)
-                                : reinterpret_cast<const void*>(&quantize_units128<DT, kThreads>);
-    if (lc.lds_bytes > 65536 && lc.lds_bytes > lds_set[which][DT]) {
+    const void* fn = nullptr;
+    void (*launch)(const LaneClass&, const MatDesc*, const WorkItem*, const KParams&, hipStream_t) = nullptr;
+#define EQ_VARIANT(NT_, K_)                                                                                     \
+  if (lc.threads == NT_ && lc.chunks_per_thread == K_) {                                                        \
+    fn = reinterpret_cast<const void*>(&quantize_units128<DT, NT_, K_>);                                        \
+    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
+      hipLaunchKernelGGL((quantize_units128<DT, NT_, K_>), dim3((unsigned)c.n_items), dim3(NT_), c.lds_bytes, s, \
+                         dm, di + c.first_item, k, c.pool_slots);                                              \
+    };                                                                                                          \
+  }
+    EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4)
+    EQ_VARIANT(512, 2) EQ_VARIANT(512, 4) EQ_VARIANT(512, 8)
+#undef EQ_VARIANT
+    if (!fn) return EQ_E_UNSUPPORTED;
+    if (lc.lds_bytes > 65536)
       EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
-      lds_set[which][DT] = lc.lds_bytes;
-    }
     {
       ScopedKernelTimer tm(st);
-      if (which == 2)
-        hipLaunchKernelGGL((quantize_units128<DT, 512>), dim3((unsigned)lc.n_items), dim3(512), lc.lds_bytes, st, dmats,
-                           ditems + lc.first_item, kp, lc.pool_slots);
-      else
-        hipLaunchKernelGGL((quantize_units128<DT, kThreads>), dim3((unsigned)lc.n_items), dim3(kThreads), lc.lds_bytes, st,
-                           dmats, ditems + lc.first_item, kp, lc.pool_slots);
+      launch(lc, dmats, ditems, kp, st);
     }
     EQ_HIP(hipGetLastError());
   }
   if (gen_rows > 0) {
     const size_t lds = 256 + (size_t)gen_cols * 2 + (size_t)gen_cols / 8;
-    if (lds > 65536 && lds > lds_set[0][DT]) {
+    if (lds > 65536)
       EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_rows_generic<DT>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      lds_set[0][DT] = lds;
-    }
     {
       ScopedKernelTimer tm(st);
       hipLaunchKernelGGL(quantize_rows_generic<DT>, dim3(gen_rows, n), dim3(kThreads), lds, st, dmats, kp);

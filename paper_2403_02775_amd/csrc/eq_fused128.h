@@ -20,6 +20,7 @@
 #pragma once
 
 #include "eq_common.h"
+#include "eq_rowbatch.h"
 #include "eq_rowstage.h"
 
 namespace eq {
@@ -29,6 +30,7 @@ constexpr int kPairs = kG / 2;
 constexpr int kSlotBytes = 272;       // 256 B of data + 16 B of padding (bank spread)
 constexpr int kSlotChunks = 17;
 constexpr int kCodeOff = 128;         // packed codes are assembled in the upper half of the slot
+constexpr int kLdsHeader = 2560;      // scratch of the row staging, in front of the pool
 
 struct WorkItem {
   int32_t mat, row0, nrows, pad_;
@@ -168,15 +170,18 @@ __device__ __forceinline__ float optimise_range(const KParams& kp, float r0, Eva
 
 // NT = threads per workgroup = units per round: 256 when two workgroups' pools fit the LDS of
 // a compute unit, 512 (one workgroup per compute unit) for long rows; two wavefronts per SIMD
-// either way.
-template <int DT, int NT>
+// either way.  K = 16-byte chunks of a row per thread (cols <= 8 * K * NT); rows are staged in
+// batches of 16 / K (NT = 256) or 24 / K (NT = 512) rows.
+template <int DT, int NT, int K>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_units128(const MatDesc* __restrict__ mats,
                                                               const WorkItem* __restrict__ items, KParams kp,
                                                               uint32_t pool_slots) {
+  constexpr int RB = (NT == 256 ? 16 : 24) / K;
+  typedef BatchScratch<RB, K> Scratch;
+  static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
   extern __shared__ __align__(16) unsigned char smem[];
-  StageScratch* sc = reinterpret_cast<StageScratch*>(smem);
-  unsigned char* pool = smem + 256;
-  unsigned char* maskb = pool + (size_t)pool_slots * kSlotBytes;
+  Scratch* sc = reinterpret_cast<Scratch*>(smem);
+  unsigned char* pool = smem + kLdsHeader;
   const WorkItem it = items[blockIdx.x];
   const MatDesc md = mats[it.mat];
   const uint32_t upr = (uint32_t)md.upr;
@@ -190,9 +195,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   while (true) {
     // ---- fill: stage rows until a full round of units is available ----
     while (next_row < row_end && pool_units < (uint32_t)NT && pool_units + upr <= pool_slots) {
-      stage_row<DT, Padded128Layout>(md, kp, next_row, pool, pool_units * 16u, maskb, sc);
-      pool_units += upr;
-      ++next_row;
+      int nb = 0;
+      uint32_t pu = pool_units;
+      while (nb < RB && next_row + nb < row_end && pu < (uint32_t)NT && pu + upr <= pool_slots) {
+        pu += upr;
+        ++nb;
+      }
+      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, next_row, nb, pool, pool_units * 16u, sc);
+      pool_units = pu;
+      next_row += nb;
     }
     if (pool_units == 0) break;
     // whole rounds; a partly filled one only at the end of the range or when the pool has no
