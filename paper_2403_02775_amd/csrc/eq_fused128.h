@@ -85,6 +85,33 @@ __device__ __forceinline__ void chunk_levels(const uint4 v, float inv, float mlo
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// Block fixed-point planes of the lane's unit: xi = x * 2^q (|xi| < 2^30) as 65536 H + L with
+// signed 16-bit halves, two elements per register.  TEST also ORs the bit patterns of
+// y - trunc(y) into frac_bits (zero iff every x * 2^q is an integer).
+template <int DT, bool TEST>
+__device__ __forceinline__ void build_planes(const unsigned char* slot, int q, uint32_t (&H)[kPairs], uint32_t (&Lo)[kPairs],
+                                             uint32_t& frac_bits) {
+#pragma unroll
+  for (int ch = 0; ch < 16; ++ch) {
+    const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = 4 * ch + j;
+      const float y0 = ldexpf(widen16<DT>(w[j] & 0xFFFFu), q);
+      const float y1 = ldexpf(widen16<DT>(w[j] >> 16), q);
+      const int i0 = (int)y0, i1 = (int)y1;
+      if (TEST) frac_bits |= __float_as_uint(y0 - (float)i0) | __float_as_uint(y1 - (float)i1);
+      Lo[k] = __builtin_amdgcn_perm((uint32_t)i1, (uint32_t)i0, 0x05040100u);
+      H[k] = __builtin_amdgcn_perm((uint32_t)(i1 + 0x8000), (uint32_t)(i0 + 0x8000), 0x07060302u);
+    }
+    // pin the running flag here: otherwise the OR tree is rebalanced, every y and trunc(y) stays
+    // live to the end of the unit, and 256 values are spilled to scratch memory
+    if (TEST) asm volatile("" : "+v"(frac_bits));
+    else __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // One evaluation of Eq. 1 / Eq. 2 for the lane's unit: values from its LDS slot (read one
 // chunk ahead of use), planes from registers.  The compiler barrier keeps the reads inside
 // the iteration loop (hoisted, they would pin 64 more registers).
@@ -218,17 +245,35 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       // ---- range of the unit, and its block fixed-point planes ----
       // xi = x * 2^q with |xi| < 2^30, split into signed 16-bit planes xi = 65536 H + L
       float vmin = 0.0f, vmax = 0.0f;
+      if (DT == EQ_F16) {
+        // packed fp16 min / max over the pairs (exact: they only select), widened once at the end
+        __half2 mn = __floats2half2_rn(0.0f, 0.0f), mx = mn;
 #pragma unroll
-      for (int ch = 0; ch < 16; ++ch) {
-        const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        for (int ch = 0; ch < 16; ++ch) {
+          const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float x0 = widen16<DT>(w[j] & 0xFFFFu), x1 = widen16<DT>(w[j] >> 16);
-          vmin = fminf(vmin, fminf(x0, x1));
-          vmax = fmaxf(vmax, fmaxf(x0, x1));
+          for (int j = 0; j < 4; ++j) {
+            const __half2 h = __builtin_bit_cast(__half2, w[j]);
+            mn = __hmin2(mn, h);
+            mx = __hmax2(mx, h);
+          }
         }
-        __builtin_amdgcn_sched_barrier(0);
+        vmin = fminf(__low2float(mn), __high2float(mn));
+        vmax = fmaxf(__low2float(mx), __high2float(mx));
+      } else {
+#pragma unroll
+        for (int ch = 0; ch < 16; ++ch) {
+          const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float x0 = widen16<DT>(w[j] & 0xFFFFu), x1 = widen16<DT>(w[j] >> 16);
+            vmin = fminf(vmin, fminf(x0, x1));
+            vmax = fmaxf(vmax, fmaxf(x0, x1));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       float r0;
       int z;
@@ -241,23 +286,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       const int q = 30 - E;
       uint32_t H[kPairs], Lo[kPairs];
       uint32_t frac_bits = 0;          // OR of the bit patterns of y - trunc(y): zero iff every y is an integer
-#pragma unroll
-      for (int ch = 0; ch < 16; ++ch) {
-        const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int k = 4 * ch + j;
-          const float y0 = ldexpf(widen16<DT>(w[j] & 0xFFFFu), q);
-          const float y1 = ldexpf(widen16<DT>(w[j] >> 16), q);
-          const int i0 = (int)y0, i1 = (int)y1;
-          frac_bits |= __float_as_uint(y0 - (float)i0) | __float_as_uint(y1 - (float)i1);
-          Lo[k] = __builtin_amdgcn_perm((uint32_t)i1, (uint32_t)i0, 0x05040100u);
-          H[k] = __builtin_amdgcn_perm((uint32_t)(i1 + 0x8000), (uint32_t)(i0 + 0x8000), 0x07060302u);
-        }
-        // pin the running flag here: otherwise the OR tree is rebalanced, every y and trunc(y) stays
-        // live to the end of the unit, and 256 values are spilled to scratch memory
-        asm volatile("" : "+v"(frac_bits));
+      // every fp16 value is a multiple of 2^-24, so q >= 24 needs no test (wavefront-uniform branch)
+      const bool need_test = !(DT == EQ_F16 && __all(q >= 24));
+      if (kp.iters > 0) {
+        if (need_test) build_planes<DT, true>(slot, q, H, Lo, frac_bits);
+        else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
       }
       const bool exact = (frac_bits << 1) == 0;
 
@@ -277,20 +310,31 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       if (valid) {
         if (kp.bits == 4) {
           // all 16 words first (they overwrite the upper half of the values), then one store burst
+          // The zero-point goes into the magic constant, so the low byte of each pattern is the
+          // unsigned code itself; even and odd elements are gathered into bytes and merged.
+          const float mz = kMagic + (float)z, ulo = kMagic, uhi = kMagic + (float)kp.L;
           uint32_t o[16];
 #pragma unroll
           for (int ch = 0; ch < 16; ++ch) {
             const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-            uint32_t word = 0;
+            uint32_t f[8];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              uint32_t f0, f1;
-              pair_levels<DT>(w[j], inv, mlo, mhi, f0, f1);
-              word |= ((f0 + (uint32_t)z) & 0xFu) << (8 * j);
-              word |= ((f1 + (uint32_t)z) & 0xFu) << (8 * j + 4);
+              float x0, x1;
+              if (DT == EQ_F16) {
+                x0 = __half2float(__ushort_as_half((unsigned short)(w[j] & 0xFFFFu)));
+                x1 = __half2float(__ushort_as_half((unsigned short)(w[j] >> 16)));
+              } else {
+                x0 = __uint_as_float(w[j] << 16);
+                x1 = __uint_as_float(w[j] & 0xFFFF0000u);
+              }
+              f[2 * j] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
+              f[2 * j + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
             }
-            o[ch] = word;
+            const uint32_t even = __builtin_amdgcn_perm(f[2], f[0], 0x0C0C0400u) | __builtin_amdgcn_perm(f[6], f[4], 0x04000C0Cu);
+            const uint32_t odd = __builtin_amdgcn_perm(f[3], f[1], 0x0C0C0400u) | __builtin_amdgcn_perm(f[7], f[5], 0x04000C0Cu);
+            o[ch] = (odd << 4) | even;
             __builtin_amdgcn_sched_barrier(0);
           }
           uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);

@@ -75,13 +75,20 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
     for (int i = 0; i < K; ++i) {
       float x[8];
       chunk_floats<DT>(v[r][i], x);
-      const uint32_t w[4] = {v[r][i].x, v[r][i].y, v[r][i].z, v[r][i].w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) bad = bad || nonfinite16<DT>(w[k] & 0xFFFFu) || nonfinite16<DT>(w[k] >> 16);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         s1 += x[k];
         s2 = __builtin_fmaf(x[k], x[k], s2);
+      }
+    }
+    // An Inf or NaN makes the sum of squares non-finite; only then look at the elements (for
+    // bf16 a huge finite value can overflow the square too, so the sum alone does not decide).
+    if (!(s2 < __builtin_inff())) {
+#pragma unroll
+      for (int i = 0; i < K; ++i) {
+        const uint32_t w[4] = {v[r][i].x, v[r][i].y, v[r][i].z, v[r][i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) bad = bad || nonfinite16<DT>(w[k] & 0xFFFFu) || nonfinite16<DT>(w[k] >> 16);
       }
     }
 #pragma unroll

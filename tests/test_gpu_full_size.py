@@ -1,0 +1,130 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
+`bench.py` times (one eq_quantize_batch call over the whole weight set).
+
+The oracle cannot redo 65 G elements, so: (1) rows are independent under row statistics, hence a
+seeded sample of rows of EVERY matrix is recomputed by the oracle and compared element by element
+(codes, scale, zero-point, outlier columns and values of those rows); (2) properties that hold at
+any size are checked on everything on the GPU with torch: status words, monotone row pointers,
+ascending columns, outlier values verbatim, outlier fraction, positive scales."""
+import numpy as np
+import pytest
+import torch
+
+import bench
+import eq_inputs
+import paper_2403_02775_amd as eqg
+from oracle import easyquant_oracle as eqo
+from parity import raw_of, to_gpu_params
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _quantize_all(Ws, p, capacity_frac=0.02):
+    gp = to_gpu_params(p)
+    caps = [int(w.numel() * capacity_frac) + 64 for w in Ws]
+    outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, DEV) for w, c in zip(Ws, caps)]
+    ws = torch.empty(eqg.eq_workspace_bytes([w.shape[0] for w in Ws], [w.shape[1] for w in Ws], caps, gp),
+                     dtype=torch.uint8, device=DEV)
+    eqg.eq_quantize_batch(Ws, gp, outs, ws)
+    torch.cuda.synchronize()
+    return outs
+
+
+def _global_properties(Ws, outs, p, what):
+    total_out = total = 0
+    for k, (W, o) in enumerate(zip(Ws, outs)):
+        rows, cols = W.shape
+        assert int(o.status.item()) == 0, (what, k)
+        rp = o.out_row_ptr.to(torch.int64) & 0xFFFFFFFF
+        assert int(rp[0]) == 0 and bool((rp[1:] >= rp[:-1]).all()), (what, k, "row_ptr")
+        n = int(rp[-1])
+        assert n <= o.capacity
+        col = o.out_col[:n].to(torch.int64)
+        rr = torch.repeat_interleave(torch.arange(rows, device=DEV), (rp[1:] - rp[:-1]))
+        assert bool((col >= 0).all()) and bool((col < cols).all())
+        if n > 1:
+            same = rr[1:] == rr[:-1]
+            assert bool((col[1:][same] > col[:-1][same]).all()), (what, k, "columns not ascending")
+        assert bool((W.view(torch.int16)[rr, col] == o.out_val[:n]).all()), (what, k, "outlier values not verbatim")
+        assert bool((o.scales > 0).all()) and bool(torch.isfinite(o.scales).all())
+        assert bool((o.zero_points == (1 << (p.bits - 1)) - 1).all())
+        total_out += n
+        total += rows * cols
+    frac = total_out / total
+    assert 0.003 < frac < 0.012, (what, frac)
+    return frac
+
+
+def _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix, seed, what):
+    """Oracle on a sample of rows of every matrix, grouped by row length."""
+    rng = np.random.default_rng(seed)
+    by_cols = {}
+    for k, W in enumerate(Ws):
+        rows = W.shape[0]
+        pick = np.sort(rng.choice(rows, size=min(rows_per_matrix, rows), replace=False))
+        by_cols.setdefault(int(W.shape[1]), []).append((k, pick))
+    checked = 0
+    for cols, group in by_cols.items():
+        print(f"[full-size] {what}: cols={cols}, {sum(len(pk) for _, pk in group)} sampled rows", flush=True)
+        G = p.group_size
+        upr = cols // G
+        raws, got_u, got_s, got_z, got_out = [], [], [], [], []
+        for k, pick in group:
+            W, o = Ws[k], outs[k]
+            idx = torch.from_numpy(pick).to(DEV)
+            raws.append(raw_of(W[idx]))
+            got_u.append(eqo.unpack_codes(o.codes[idx].cpu().numpy().view(np.uint32), cols, p.bits))
+            got_s.append(o.scales[idx].cpu().numpy())
+            got_z.append(o.zero_points[idx].cpu().numpy())
+            rp = o.out_row_ptr.cpu().numpy().view(np.uint32).astype(np.int64)
+            oc = o.out_col.cpu().numpy().view(np.uint32)
+            ov = o.out_val.cpu().numpy().view(np.uint16)
+            for r in pick:
+                got_out.append((oc[rp[r]:rp[r + 1]].copy(), ov[rp[r]:rp[r + 1]].copy()))
+        raw = np.concatenate(raws)
+        want = eqo.quantize_matrix(raw, p)
+        gu, gs, gz = np.concatenate(got_u), np.concatenate(got_s), np.concatenate(got_z)
+        assert (gu == want["u"]).all(), (what, cols, "codes", int((gu != want["u"]).sum()))
+        assert (gs == want["scales"]).all(), (what, cols, "scales")
+        assert (gz == want["zero_points"]).all(), (what, cols, "zero points")
+        wrp = want["out_row_ptr"].astype(np.int64)
+        for i, (c, v) in enumerate(got_out):
+            assert np.array_equal(c, want["out_col"][wrp[i]:wrp[i + 1]]), (what, cols, i, "outlier columns")
+            assert np.array_equal(v, want["out_val"][wrp[i]:wrp[i + 1]]), (what, cols, i, "outlier values")
+        checked += raw.shape[0]
+    return checked
+
+
+def test_config3_llama7b_mlp_set_3bit_and_4bit():
+    rec = eq_inputs.RECIPES["c3"]
+    Ws = [eq_inputs.gen_matrix(r, c, rec, seed=eq_inputs.mix_seed(3, 0, i), device=DEV)
+          for i, (_, r, c) in enumerate(eq_inputs.mlp_set_shapes())]
+    for bits in (3, 4):
+        p = eqo.Params(bits=bits, group_size=128, iters=100)
+        outs = _quantize_all(Ws, p)
+        frac = _global_properties(Ws, outs, p, f"c3 {bits}-bit")
+        n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=48, seed=bits, what=f"c3 {bits}-bit")
+        print(f"c3 {bits}-bit: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
+
+
+def test_config4_llama7b_bf16_whole_model():
+    Ws, names, bits, dt = bench.build_workload("llama7b_bf16_w4g128", -1, DEV)
+    assert len(Ws) == 224 and dt == "bf16"
+    p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=100)
+    outs = _quantize_all(Ws, p)
+    frac = _global_properties(Ws, outs, p, "c4")
+    n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=3, seed=4, what="c4")
+    print(f"c4: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
+
+
+def test_config5_llama65b_whole_model():
+    Ws, names, bits, dt = bench.build_workload("llama65b_f16_w4g128", -1, DEV)
+    assert len(Ws) == 560 and sum(w.numel() for w in Ws) == 64760053760
+    p = eqo.Params(bits=4, group_size=128, iters=100)
+    outs = _quantize_all(Ws, p)
+    frac = _global_properties(Ws, outs, p, "c5")
+    n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=2, seed=5, what="c5")
+    print(f"c5: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
+    del Ws, outs
+    torch.cuda.empty_cache()
