@@ -198,13 +198,13 @@ __device__ __forceinline__ float optimise_range(const KParams& kp, float r0, Eva
 // NT = threads per workgroup = units per round: 256 when two workgroups' pools fit the LDS of
 // a compute unit, 512 (one workgroup per compute unit) for long rows; two wavefronts per SIMD
 // either way.  K = 16-byte chunks of a row per thread (cols <= 8 * K * NT); rows are staged in
-// batches of 16 / K (NT = 256) or 24 / K (NT = 512) rows.
+// batches of 16 / K rows (16 chunks = 64 registers of row data per thread).
 template <int DT, int NT, int K>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_units128(const MatDesc* __restrict__ mats,
                                                               const WorkItem* __restrict__ items, KParams kp,
                                                               uint32_t pool_slots) {
-  constexpr int RB = (NT == 256 ? 16 : 24) / K;
-  typedef BatchScratch<RB, K> Scratch;
+  constexpr int RB = 16 / K;
+  typedef BatchScratch<RB> Scratch;
   static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
   extern __shared__ __align__(16) unsigned char smem[];
   Scratch* sc = reinterpret_cast<Scratch*>(smem);
@@ -247,20 +247,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       float vmin = 0.0f, vmax = 0.0f;
       if (DT == EQ_F16) {
         // packed fp16 min / max over the pairs (exact: they only select), widened once at the end
-        __half2 mn = __floats2half2_rn(0.0f, 0.0f), mx = mn;
+        typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+        half2_t mn = {(_Float16)0.0f, (_Float16)0.0f}, mx = mn;
 #pragma unroll
         for (int ch = 0; ch < 16; ++ch) {
           const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
           const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const __half2 h = __builtin_bit_cast(__half2, w[j]);
-            mn = __hmin2(mn, h);
-            mx = __hmax2(mx, h);
+            const half2_t h = __builtin_bit_cast(half2_t, w[j]);
+            mn = __builtin_elementwise_min(mn, h);
+            mx = __builtin_elementwise_max(mx, h);
           }
         }
-        vmin = fminf(__low2float(mn), __high2float(mn));
-        vmax = fmaxf(__low2float(mx), __high2float(mx));
+        vmin = fminf((float)mn.x, (float)mn.y);
+        vmax = fmaxf((float)mx.x, (float)mx.y);
       } else {
 #pragma unroll
         for (int ch = 0; ch < 16; ++ch) {
@@ -288,10 +289,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       uint32_t frac_bits = 0;          // OR of the bit patterns of y - trunc(y): zero iff every y is an integer
       // every fp16 value is a multiple of 2^-24, so q >= 24 needs no test (wavefront-uniform branch)
       const bool need_test = !(DT == EQ_F16 && __all(q >= 24));
-      if (kp.iters > 0) {
-        if (need_test) build_planes<DT, true>(slot, q, H, Lo, frac_bits);
-        else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
-      }
+      if (need_test) build_planes<DT, true>(slot, q, H, Lo, frac_bits);
+      else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
       const bool exact = (frac_bits << 1) == 0;
 
       float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {

@@ -50,8 +50,10 @@ __global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __res
   if (threadIdx.x == 0) md.out_row_ptr[md.rows] = running;
 }
 
-// Moves each row's run of outliers from the staging area (arrival order of the rows) to its
-// CSR position.  One wavefront per row; blockIdx.y = matrix.
+// Moves each row's run of outliers from the staging area (rows in arrival order, entries
+// within a run in any order) to its CSR position, sorted by column.  One wavefront per row;
+// blockIdx.y = matrix.  Columns are distinct, so the rank of an entry (the number of entries
+// of the run with a smaller column) is its position; a run has a few dozen entries.
 __global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats) {
   const MatDesc md = mats[blockIdx.y];
   const int64_t row = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
@@ -61,9 +63,22 @@ __global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __res
   const uint32_t src = md.row_stage[row];
   const uint32_t dst = md.out_row_ptr[row];
   if (src == 0xFFFFFFFFu || (unsigned long long)dst + cnt > (unsigned long long)md.capacity) return;
-  for (uint32_t i = lane; i < cnt; i += kWave) {
-    md.out_col[dst + i] = md.st_col[src + i];
-    md.out_val[dst + i] = md.st_val[src + i];
+  for (uint32_t e0 = 0; e0 < cnt; e0 += kWave) {
+    const uint32_t e = e0 + lane;
+    const bool have = e < cnt;
+    const uint32_t col = have ? md.st_col[src + e] : 0xFFFFFFFFu;
+    const uint16_t val = have ? md.st_val[src + e] : (uint16_t)0;
+    uint32_t rank = 0;
+    for (uint32_t f0 = 0; f0 < cnt; f0 += kWave) {
+      const uint32_t f = f0 + lane;
+      const uint32_t cf = f < cnt ? md.st_col[src + f] : 0xFFFFFFFFu;
+      const int m = (int)min((uint32_t)kWave, cnt - f0);
+      for (int j = 0; j < m; ++j) rank += __shfl(cf, j) < col ? 1u : 0u;
+    }
+    if (have) {
+      md.out_col[dst + rank] = col;
+      md.out_val[dst + rank] = val;
+    }
   }
 }
 

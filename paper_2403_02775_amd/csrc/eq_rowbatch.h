@@ -2,17 +2,24 @@
 //
 // Several rows are staged at once by all threads of the workgroup, with every 128-bit HBM
 // load of the batch in flight before the first one is used, a handful of barriers per batch
-// instead of per row, and one staging reservation per batch.  The row's data stays in
-// registers from the load until it is written (once) to the LDS pool.
+// and one staging reservation per batch.
+//
+// Outliers are rare (< 1 % of the elements, Sec. 5), so only a few 16-byte chunks per thread
+// hold one.  The bulk pass therefore does the minimum per element (the sums, and one test per
+// chunk: can anything in it reach the threshold?), and the chunks that pass the test
+// ("candidates") are handled one per loop iteration by the lanes that have one.  Within a
+// row the outliers are written in arrival order; gather_outliers sorts each row's run by
+// column when it moves it to its final place, so the result does not depend on timing.
 //
 // Statistics (Eq. 3) take a fast path and an exact path with identical results:
 //   fast  : sum x and sum x^2 in binary32 per thread, binary64 across threads.  The outlier
 //           test is decided only for elements whose |x - mean| is farther than a relative
-//           1e-4 from n*sigma; the error of the fast sums is below 2e-5 of the threshold
+//           1e-4 from n*sigma; the error of the fast sums is below 2.2e-5 of the threshold
 //           (<= 70 roundings of 2^-24 on sums whose terms are bounded through the guard
-//           mean^2 < variance), so those decisions equal the exact ones.
-//   exact : a row with an element inside that band, or with mean^2 >= variance (which also
-//           covers constant rows), is redone with the two-pass binary64 sums.
+//           mean^2 < variance, n >= 0.5), so those decisions equal the exact ones.
+//   exact : a row with an element inside that band, or that fails the guard (which also
+//           covers constant rows), is redone with the two-pass binary64 sums and decided
+//           element by element in binary64.
 #pragma once
 
 #include "eq_common.h"
@@ -22,14 +29,15 @@ namespace eq {
 
 constexpr float kBand = 1.0e-4f;
 
-template <int RB, int K>
+template <int RB>
 struct BatchScratch {
   float part[RB][kMaxWaves][2];      // per wavefront: sum x, sum x^2 of each row
   double dred[kMaxWaves];
-  uint32_t wtot[RB][K][kMaxWaves];   // outliers per (row, chunk slice, wavefront)
-  uint32_t rowtot[RB];
+  double mu[RB], thr[RB];            // exact mean and n*sigma of the rows that were redone
   unsigned long long rowbase[RB];    // staging position of the row, ~0 when it does not fit
-  uint32_t slow[RB];
+  uint32_t rowcnt[RB];               // outliers of the row
+  uint32_t rowpos[RB];               // next free entry of the row's run while it is written
+  uint32_t slow[RB];                 // row takes the exact path
 };
 
 template <int DT>
@@ -45,10 +53,11 @@ __device__ __forceinline__ void chunk_floats(const uint4 v, float (&x)[8]) {
 // Stages rows [row0, row0 + nrows), nrows <= RB, of matrix md: chunk ch of row r goes to
 // Layout::off(ch0 + r * chunks_per_row + ch).  Thread t owns chunks t, t + NT, ... (K of them
 // per row).  Ends with a barrier; afterwards the pool holds the normal values and 0 at
-// outlier positions, and the outliers sit in the staging area (one run per row).
+// outlier positions, and the outliers sit in the staging area (one run per row, any order).
 template <int DT, int NT, int RB, int K, class Layout>
 __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
-                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB, K>* sc) {
+                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc) {
+  static_assert(RB * K <= 32, "candidate flags are one 32-bit word");
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int NW = NT / kWave;
@@ -64,9 +73,13 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
       v[r][i] = (r < nrows && ch < nchunks) ? load_stream128(src + ch) : make_uint4(0, 0, 0, 0);
     }
   }
-  if (tid < (uint32_t)RB) sc->slow[tid] = 0;
+  if (tid < (uint32_t)RB) {
+    sc->slow[tid] = 0;
+    sc->rowcnt[tid] = 0;
+    sc->rowpos[tid] = 0;
+  }
 
-  // ---- fast sums ----
+  // ---- fast sums; the values go to the pool as they are ----
   bool bad = false;
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
@@ -80,6 +93,9 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
         s1 += x[k];
         s2 = __builtin_fmaf(x[k], x[k], s2);
       }
+      const uint32_t ch = (uint32_t)i * NT + tid;
+      if (r < nrows && ch < nchunks)
+        *reinterpret_cast<uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)) = v[r][i];
     }
     // An Inf or NaN makes the sum of squares non-finite; only then look at the elements (for
     // bf16 a huge finite value can overflow the square too, so the sum alone does not decide).
@@ -104,10 +120,10 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
   if (__any(bad) && lane == 0) atomicOr(md.status, EQ_S_NONFINITE);
   __syncthreads();
 
-  // ---- thresholds and masks ----
+  // ---- thresholds; one test per chunk: can any of its elements be an outlier? ----
   const double cnt = (double)md.cols;
-  uint32_t m[RB][K];
-  float mu_f[RB];
+  float mu_f[RB], thr_lo[RB], thr_hi[RB];
+  uint32_t cand = 0;                      // bit r * K + i: chunk i of row r needs a look
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
     double S1 = 0.0, S2 = 0.0;
@@ -117,14 +133,14 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
       S2 += (double)sc->part[r][w][1];
     }
     double mu, sigma;
-    bool slow = false;
+    bool slow;
     if (kp.scope == EQ_STAT_MATRIX) {
       mu = md.mat_stats[0];
       sigma = md.mat_stats[1];
-      slow = true;                       // whole-matrix statistics are exact already: decide every element exactly
+      slow = true;                        // the matrix-wide statistics are exact: decide every element exactly
     } else {
       mu = S1 / cnt;
-      const double ms = S2 / cnt;        // mean square = variance + mean^2
+      const double ms = S2 / cnt;         // mean square = variance + mean^2
       const double var = ms - mu * mu;
       slow = !(var + var > ms) || kp.n < 0.5;   // mean^2 >= variance, a constant row, NaN; or a threshold so
                                                  // small that the error of the mean is not negligible against it
@@ -132,31 +148,56 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
     }
     const double thr = kp.n * sigma;
     mu_f[r] = (float)mu;
-    const float thr_lo = (float)thr * (1.0f - kBand), thr_hi = (float)thr * (1.0f + kBand);
-    bool border = false;
+    thr_lo[r] = (float)thr * (1.0f - kBand);
+    thr_hi[r] = (float)thr * (1.0f + kBand);
+    if (slow) {
+      if (r < nrows) sc->slow[r] = 1u;    // benign race: every writer stores 1
+    } else {
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-      float x[8], d[8];
-      chunk_floats<DT>(v[r][i], x);
+      for (int i = 0; i < K; ++i) {
+        float x[8];
+        chunk_floats<DT>(v[r][i], x);
+        float dmax = 0.0f;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) d[k] = fabsf(x[k] - mu_f[r]);
-      const float dmax = fmaxf(fmaxf(fmaxf(d[0], d[1]), fmaxf(d[2], d[3])), fmaxf(fmaxf(d[4], d[5]), fmaxf(d[6], d[7])));
-      uint32_t mm = 0;
-      if (dmax >= thr_lo) {
+        for (int k = 0; k < 8; ++k) dmax = fmaxf(dmax, fabsf(x[k] - mu_f[r]));
+        const uint32_t ch = (uint32_t)i * NT + tid;
+        if (r < nrows && ch < nchunks && dmax >= thr_lo[r]) cand |= 1u << (r * K + i);
+      }
+    }
+  }
+
+  // ---- candidates, one per iteration: count the outliers, notice borderline elements ----
+  {
+    uint32_t todo = cand;
+    while (__any(todo != 0)) {
+      if (todo) {
+        const int slot = __ffs((int)todo) - 1;
+        todo &= todo - 1;
+        const int r = slot / K, i = slot - r * K;
+        const uint32_t ch = (uint32_t)i * NT + tid;
+        const uint4 c = *reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch));
+        float x[8];
+        chunk_floats<DT>(c, x);
+        float mf = 0.0f, lo = 0.0f, hi = 0.0f;
+#pragma unroll
+        for (int rr = 0; rr < RB; ++rr)
+          if (rr == r) { mf = mu_f[rr]; lo = thr_lo[rr]; hi = thr_hi[rr]; }
+        uint32_t n_out = 0;
+        bool border = false;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          mm |= (d[k] >= thr_hi ? 1u : 0u) << k;
-          border = border || (d[k] >= thr_lo && d[k] < thr_hi);
+          const float d = fabsf(x[k] - mf);
+          n_out += d >= hi ? 1u : 0u;
+          border = border || (d >= lo && d < hi);
         }
+        if (border) sc->slow[r] = 1u;
+        if (n_out) atomicAdd(&sc->rowcnt[r], n_out);
       }
-      const uint32_t ch = (uint32_t)i * NT + tid;
-      m[r][i] = (r < nrows && ch < nchunks) ? mm : 0u;
     }
-    if (r < nrows && (slow || border)) sc->slow[r] = 1u;    // benign race: every writer stores 1
   }
   __syncthreads();
 
-  // ---- exact redo of the rows that asked for it (uniform branch per row) ----
+  // ---- exact statistics and counts of the rows that asked for them (uniform branch per row) ----
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
     if (r < nrows && sc->slow[r]) {
@@ -191,61 +232,34 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
         sigma = sqrt(block_sum(q, sc->dred) / cnt);
       }
       const double thr = kp.n * sigma;
+      if (tid == 0) {
+        sc->mu[r] = mu;
+        sc->thr[r] = sigma > 0.0 ? thr : __builtin_inf();    // a constant scope has no outliers
+        sc->rowcnt[r] = 0;
+      }
+      __syncthreads();
+      uint32_t n_out = 0;
 #pragma unroll
       for (int i = 0; i < K; ++i) {
         const uint32_t ch = (uint32_t)i * NT + tid;
-        m[r][i] = (ch < nchunks && sigma > 0.0) ? chunk_mask<DT>(v[r][i], mu, thr) : 0u;
+        const uint32_t mm = (ch < nchunks && sigma > 0.0) ? chunk_mask<DT>(v[r][i], mu, thr) : 0u;
+        n_out += __popc(mm);
+        if (mm) cand |= 1u << (r * K + i);
+        else cand &= ~(1u << (r * K + i));
       }
-    }
-  }
-
-  // ---- values to the pool (raw; outliers are zeroed below by the thread that owns them) ----
-#pragma unroll
-  for (int r = 0; r < RB; ++r) {
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
-      const uint32_t ch = (uint32_t)i * NT + tid;
-      if (r < nrows && ch < nchunks)
-        *reinterpret_cast<uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)) = v[r][i];
-    }
-  }
-
-  // ---- outlier compaction in column order: chunk order is (slice i, thread) ----
-  uint32_t inc[RB][K];
-  bool any_mine = false;
-#pragma unroll
-  for (int r = 0; r < RB; ++r) {
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
-      const uint32_t c = __popc(m[r][i]);
-      any_mine = any_mine || c != 0;
-      uint32_t s = c;
-#pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t t = __shfl_up(s, o);
-        if (lane >= (uint32_t)o) s += t;
-      }
-      inc[r][i] = s;
-      if (lane == kWave - 1) sc->wtot[r][i][wave] = s;
+      if (n_out) atomicAdd(&sc->rowcnt[r], n_out);
     }
   }
   __syncthreads();
-  if (tid < (uint32_t)RB) {
-    uint32_t t = 0;
-    if ((int)tid < nrows) {
-      for (int i = 0; i < K; ++i)
-        for (int w = 0; w < NW; ++w) t += sc->wtot[tid][i][w];
-    }
-    sc->rowtot[tid] = t;
-  }
-  __syncthreads();
+
+  // ---- one reservation for the batch ----
   if (tid == 0) {
     uint32_t total = 0;
-    for (int r = 0; r < nrows; ++r) total += sc->rowtot[r];
+    for (int r = 0; r < nrows; ++r) total += sc->rowcnt[r];
     unsigned long long b = 0;
     if (total) b = atomicAdd(md.cursor, (unsigned long long)total);
     for (int r = 0; r < nrows; ++r) {
-      const uint32_t t = sc->rowtot[r];
+      const uint32_t t = sc->rowcnt[r];
       const bool fits = b + t <= (unsigned long long)md.capacity;
       md.row_count[row0 + r] = t;
       md.row_stage[row0 + r] = fits ? (uint32_t)b : 0xFFFFFFFFu;
@@ -255,32 +269,44 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
     }
   }
   __syncthreads();
-  if (any_mine) {
+
+  // ---- candidates again: write (column, raw value), zero the pool copy ----
+  {
+    uint32_t todo = cand;
+    while (__any(todo != 0)) {
+      if (todo) {
+        const int slot = __ffs((int)todo) - 1;
+        todo &= todo - 1;
+        const int r = slot / K, i = slot - r * K;
+        const uint32_t ch = (uint32_t)i * NT + tid;
+        unsigned char* cp = pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch);
+        const uint4 c = *reinterpret_cast<const uint4*>(cp);
+        uint32_t mm = 0;
+        if (sc->slow[r]) {
+          mm = chunk_mask<DT>(c, sc->mu[r], sc->thr[r]);
+        } else {
+          float x[8];
+          chunk_floats<DT>(c, x);
+          float mf = 0.0f, hi = 0.0f;
 #pragma unroll
-    for (int r = 0; r < RB; ++r) {
+          for (int rr = 0; rr < RB; ++rr)
+            if (rr == r) { mf = mu_f[rr]; hi = thr_hi[rr]; }
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        const uint32_t mm = m[r][i];
+          for (int k = 0; k < 8; ++k) mm |= (fabsf(x[k] - mf) >= hi ? 1u : 0u) << k;
+        }
         if (mm) {
-          uint32_t before = 0;
-          for (int i2 = 0; i2 < i; ++i2)
-            for (int w = 0; w < NW; ++w) before += sc->wtot[r][i2][w];
-          for (uint32_t w = 0; w < wave; ++w) before += sc->wtot[r][i][w];
           const unsigned long long base = sc->rowbase[r];
-          const bool fits = base != ~0ull;
-          unsigned long long pos = base + before + (inc[r][i] - __popc(mm));
-          const uint32_t ch = (uint32_t)i * NT + tid;
-          unsigned short* e = reinterpret_cast<unsigned short*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch));
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            if (mm & (1u << j)) {
-              if (fits) {
-                md.st_col[pos] = ch * 8u + (uint32_t)j;
-                md.st_val[pos] = e[j];
-              }
-              ++pos;
-              e[j] = 0;
+          unsigned long long pos = base + atomicAdd(&sc->rowpos[r], (uint32_t)__popc(mm));
+          unsigned short* e = reinterpret_cast<unsigned short*>(cp);
+          while (mm) {
+            const int j = __ffs((int)mm) - 1;
+            mm &= mm - 1;
+            if (base != ~0ull) {
+              md.st_col[pos] = ch * 8u + (uint32_t)j;
+              md.st_val[pos] = e[j];
             }
+            ++pos;
+            e[j] = 0;
           }
         }
       }
