@@ -91,6 +91,48 @@ def cpu_baseline(Ws, gp_kwargs, sample_rows):
     return raw.size * 2 / dt / 1e9, dt, raw.shape
 
 
+def bench_dequantize(args):
+    """Secondary measurement: eq_dequantize (Eq. 4) on the shape of the paper's latency paragraph
+    (the first FFN layer of BLOOM-176B, 14336 x 57344; the paper prints 14336 x 53746), 4-bit,
+    per-channel, with synthetic outlier lists of the ratios of the paper's Table 4."""
+    import torch
+    import paper_2403_02775_amd as eqg
+    dev = "cuda:0"
+    rows, cols = 14336, 57344
+    gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=0)
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (rows, cols * 4 // 32), dtype=torch.int32, device=dev, generator=g)
+    scales = torch.rand((rows, 1), device=dev, generator=g) * 0.01 + 0.001
+    zps = torch.full((rows, 1), 7, dtype=torch.uint8, device=dev)
+    out = torch.empty((rows, cols), dtype=torch.float16, device=dev)
+    res = {}
+    for ratio in (0.0, 1e-4, 1e-3, 5e-3, 1e-2, 5e-2, 1e-1):
+        k = int(round(cols * ratio))
+        col = torch.randint(cols, (rows, max(k, 1)), device=dev, generator=g, dtype=torch.int32)[:, :k].sort(dim=1).values.contiguous()
+        rp = (torch.arange(rows + 1, device=dev, dtype=torch.int64) * k).to(torch.int32)
+        q = eqg.QMatrix(codes=codes, scales=scales, zero_points=zps, out_row_ptr=rp, out_col=col.view(-1),
+                        out_val=torch.zeros(rows * k, dtype=torch.int16, device=dev), status=torch.zeros(1, dtype=torch.int32, device=dev))
+        for _ in range(2):
+            eqg.eq_dequantize(q, rows, cols, gp, out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            eqg.eq_dequantize(q, rows, cols, gp, out)
+        e1.record()
+        torch.cuda.synchronize()
+        res[f"{ratio:.4%}"] = e0.elapsed_time(e1) / args.steps
+    dense_ms = res["0.0000%"]
+    traffic = rows * cols * 2.5 + rows * 5
+    print(json.dumps({"metric": "eq_dequantize ms (14336x57344, int4 -> fp16)", "value": dense_ms, "unit": "ms",
+                      "n_gpus": 1, "steps": args.steps, "higher_is_better": False, "data": "synthetic",
+                      "dense_GBps": traffic / (dense_ms * 1e-3) / 1e9, "dense_hbm_frac": traffic / (dense_ms * 1e-3) / HBM_PEAK,
+                      "outlier_overhead_ms": {k: v - dense_ms for k, v in res.items() if k != "0.0000%"},
+                      "paper_context_A100": {"dequant_ms": 5.0, "outlier_ms": {"0.01%": 0.027, "0.10%": 0.055, "0.50%": 0.093,
+                                                                           "1%": 0.117, "5%": 0.186, "10%": 0.212}}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,7 +147,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GiB device-to-device copy (torch's copy kernel) so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) has a kernel of known traffic to scale by")
+    ap.add_argument("--dequant", action="store_true", help="measure eq_dequantize instead (secondary benchmark, own JSON line)")
     args = ap.parse_args()
+    if args.dequant:
+        return bench_dequantize(args)
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path needs no communication; see DESIGN.md); run with --gpus 1")
 

@@ -481,10 +481,20 @@ int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_para
   d.words_per_row = (int32_t)eq_code_words_per_row(cols, p->bits);
   d.bits = p->bits;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (p->dtype == EQ_F16)
-    hipLaunchKernelGGL(dequantize_rows<EQ_F16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
-  else
-    hipLaunchKernelGGL(dequantize_rows<EQ_BF16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
+  const unsigned chunk_blocks = (unsigned)((cols / 8 + kThreads - 1) / kThreads);
+  if (chunk_blocks > 65535u) return EQ_E_UNSUPPORTED;
+  {
+    ScopedKernelTimer tm(st);
+    if (p->dtype == EQ_F16)
+      hipLaunchKernelGGL(dequantize_dense<EQ_F16>, dim3((unsigned)rows, chunk_blocks), dim3(kThreads), 0, st, d);
+    else
+      hipLaunchKernelGGL(dequantize_dense<EQ_BF16>, dim3((unsigned)rows, chunk_blocks), dim3(kThreads), 0, st, d);
+  }
+  EQ_HIP(hipGetLastError());
+  if (q->out_col && q->out_val) {
+    ScopedKernelTimer tm(st);
+    hipLaunchKernelGGL(scatter_outliers, dim3((unsigned)((rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, st, d);
+  }
   EQ_HIP(hipGetLastError());
   return EQ_OK;
 }

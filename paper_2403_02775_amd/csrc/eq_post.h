@@ -123,8 +123,6 @@ __global__ __launch_bounds__(kThreads) void matrix_finish_sums(const MatDesc* __
 }
 
 // ---- Eq. 4 ---------------------------------------------------------------------------
-// One workgroup per row: dense reconstruction scale * (code - zero_point) rounded to the
-// 16-bit type, then the row's outliers written over it.
 struct DeqDesc {
   const uint32_t* codes;
   const float* scales;
@@ -137,39 +135,56 @@ struct DeqDesc {
   int32_t rows, cols, upr, G, words_per_row, bits;
 };
 
+// Dense part of Eq. 4: scale * (code - zero_point) for every element, outliers included (their
+// slot holds the zero level, so they come out as 0 and are overwritten by scatter_outliers).
+// One thread per 8 consecutive elements of a row: 8 codes are `bits` whole bytes of the row's
+// bit stream, the 8 results are one 128-bit store; consecutive threads take consecutive
+// chunks, so code loads and stores are coalesced.  blockIdx.x = row, blockIdx.y = block of chunks.
 template <int DT>
-__global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
+__global__ __launch_bounds__(kThreads) void dequantize_dense(DeqDesc d) {
   const int64_t row = blockIdx.x;
-  const uint32_t* wrow = d.codes + row * (int64_t)d.words_per_row;
-  uint16_t* orow = d.W + row * d.ld;
+  const uint32_t ch = blockIdx.y * kThreads + threadIdx.x;        // chunk of 8 elements
+  if (ch * 8u >= (uint32_t)d.cols) return;
+  const unsigned char* stream = reinterpret_cast<const unsigned char*>(d.codes + row * (int64_t)d.words_per_row);
+  const uint32_t byte0 = ch * (uint32_t)d.bits;
+  // the chunk's bits sit in at most three aligned words; the row is padded to whole words
+  const uint32_t* wp = reinterpret_cast<const uint32_t*>(stream) + (byte0 >> 2);
+  const uint32_t last_word = (uint32_t)d.words_per_row - 1u;
+  const uint32_t w0 = wp[0];
+  const uint32_t w1 = (byte0 >> 2) + 1u <= last_word ? wp[1] : 0u;
+  const uint32_t w2 = (byte0 >> 2) + 2u <= last_word ? wp[2] : 0u;
+  const uint32_t sh = (byte0 & 3u) * 8u;
+  unsigned long long lo = ((unsigned long long)w1 << 32) | w0;
+  unsigned long long acc = sh ? (lo >> sh) | ((unsigned long long)w2 << (64u - sh)) : lo;
+  const int64_t unit = row * (int64_t)d.upr + (ch * 8u) / (uint32_t)d.G;
+  const float s = d.scales[unit];
+  const int z = (int)d.zps[unit];
   const uint32_t mask = (1u << d.bits) - 1u;
-  for (uint32_t g32 = threadIdx.x; g32 * 32u < (uint32_t)d.cols; g32 += kThreads) {
-    const uint32_t* wp = wrow + g32 * (uint32_t)d.bits;
-    unsigned long long acc = 0;
-    int nb = 0, wi = 0;
-    const uint32_t e_end = min(32u, (uint32_t)d.cols - g32 * 32u);
-    for (uint32_t e = 0; e < e_end; ++e) {
-      if (nb < d.bits) {
-        acc |= (unsigned long long)wp[wi++] << nb;
-        nb += 32;
-      }
-      const uint32_t u = (uint32_t)acc & mask;
-      acc >>= d.bits;
-      nb -= d.bits;
-      const uint32_t col = g32 * 32u + e;
-      const int64_t unit = row * (int64_t)d.upr + col / (uint32_t)d.G;
-      const float s = d.scales[unit];
-      const int z = (int)d.zps[unit];
-      float prod = s * (float)((int)u - z);
-      // Eq. 4 is evaluated as a binary32 product that is then rounded to the 16-bit type.  The
-      // empty asm keeps the compiler from fusing both into one rounding (v_fma_mixlo_f16).
-      asm volatile("" : "+v"(prod));
-      orow[col] = (uint16_t)narrow16<DT>(prod);
-    }
+  uint32_t h[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const uint32_t u = (uint32_t)acc & mask;
+    acc >>= d.bits;
+    float prod = s * (float)((int)u - z);
+    // Eq. 4 is evaluated as a binary32 product that is then rounded to the 16-bit type.  The
+    // empty asm keeps the compiler from fusing both into one rounding (v_fma_mixlo_f16).
+    asm volatile("" : "+v"(prod));
+    h[k] = narrow16<DT>(prod);
   }
-  __syncthreads();
+  uint4 o;
+  o.x = h[0] | (h[1] << 16); o.y = h[2] | (h[3] << 16); o.z = h[4] | (h[5] << 16); o.w = h[6] | (h[7] << 16);
+  *reinterpret_cast<uint4*>(d.W + row * d.ld + ch * 8u) = o;
+}
+
+// Sparse part of Eq. 4: the stored raw values over the dense result.  One wavefront per row.
+// Runs after dequantize_dense on the same stream.
+__global__ __launch_bounds__(kThreads) void scatter_outliers(DeqDesc d) {
+  const int64_t row = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (row >= d.rows) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t b = d.out_row_ptr[row], e = d.out_row_ptr[row + 1];
-  for (uint32_t i = b + threadIdx.x; i < e; i += kThreads) {
+  uint16_t* orow = d.W + row * d.ld;
+  for (uint32_t i = b + lane; i < e; i += kWave) {
     const uint32_t col = d.out_col[i];
     if (col < (uint32_t)d.cols) orow[col] = d.out_val[i];
   }
