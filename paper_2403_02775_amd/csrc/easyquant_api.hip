@@ -12,6 +12,7 @@
 
 #include "easyquant.h"
 #include "eq_common.h"
+#include "eq_channel128.h"
 #include "eq_fused128.h"
 #include "eq_generic.h"
 #include "eq_post.h"
@@ -89,6 +90,7 @@ KParams make_kparams(const eq_params* p) {
 
 // One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
 struct LaneClass {
+  int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes
   int32_t cols = 0, upr = 0;
   int32_t threads = kThreads;           // workgroup size = units per round
   int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
@@ -121,7 +123,7 @@ struct Plan {
   size_t items = 0;                     // WorkItem[]
   size_t adam = 0;                      // double[4 * max(T, 1)]
   std::vector<size_t> cursor, row_count, row_stage, st_col, st_val, mat_stats, mat_partial;
-  std::vector<int32_t> path;            // per matrix: 0 = general kernel, 1 = unit-per-lane kernel
+  std::vector<int32_t> path;            // per matrix: 0 = general kernel, 1 = unit-per-lane kernel, 2 = per-channel lane kernel
   std::vector<LaneClass> classes;
   std::vector<WorkItem> work;
   bool any_general = false;
@@ -136,6 +138,12 @@ bool lane_kernel_ok(int64_t rows, int64_t cols, const eq_params* p) {
   return p->group_size == kG && p->stat_scope != EQ_STAT_GROUP && rows > 0 && cols > 0 && cols <= 32768;
 }
 
+// The per-channel lane kernel serves rows of 2048 .. 32768 elements in multiples of 128 (a
+// per-group statistic scope is the row scope when the row is the unit).
+bool channel_kernel_ok(int64_t rows, int64_t cols, const eq_params* p) {
+  return (p->group_size == 0 || p->group_size == cols) && rows > 0 && cols % kG == 0 && cols >= 2048 && cols <= 32768;
+}
+
 Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* cap, const eq_params* p) {
   Plan pl;
   pl.path.assign((size_t)n, 0);
@@ -144,6 +152,9 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
   for (int32_t i = 0; i < n; ++i) {
     if (lane_kernel_ok(rows[i], cols[i], p)) {
       pl.path[(size_t)i] = 1;
+      order.push_back(i);
+    } else if (channel_kernel_ok(rows[i], cols[i], p)) {
+      pl.path[(size_t)i] = 2;
       order.push_back(i);
     } else if (rows[i] > 0 && cols[i] > 0) {
       pl.any_general = true;
@@ -159,6 +170,33 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     LaneClass lc;
     lc.cols = (int32_t)c;
     lc.upr = (int32_t)upr;
+    if (pl.path[(size_t)order[k]] == 2) {
+      // per-channel: a round is floor(256 / segments) whole rows; items are multiples of that
+      lc.kind = 2;
+      lc.threads = kChanThreads;
+      const int64_t per_thread = (c / 8 + kChanThreads - 1) / kChanThreads;
+      lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : per_thread <= 8 ? 8 : 16;
+      lc.pool_slots = kChanThreads;
+      lc.lds_bytes = (size_t)kChanHeader + (size_t)kChanThreads * kSlotBytes;
+      const int64_t rpr = std::min<int64_t>(kChanThreads / upr, kChanMaxRows);
+      int64_t target = std::min<int64_t>(16384, std::max<int64_t>(kChanThreads, total_units / 4096));
+      if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
+        const long v = std::atol(ov);
+        if (v > 0) target = v;
+      }
+      int64_t rpi = std::max<int64_t>(rpr, target / upr);
+      rpi -= rpi % rpr;
+      lc.first_item = pl.work.size();
+      for (size_t j = k; j < e; ++j) {
+        const int32_t m = order[j];
+        for (int64_t r = 0; r < rows[m]; r += rpi)
+          pl.work.push_back(WorkItem{m, (int32_t)r, (int32_t)std::min<int64_t>(rpi, rows[m] - r), 0});
+      }
+      lc.n_items = pl.work.size() - lc.first_item;
+      pl.classes.push_back(lc);
+      k = e;
+      continue;
+    }
     // Pool size: a round's worth of units minus what a fill can leave behind, plus one row.
     // With 256-thread workgroups two pools must share the 160 KB of LDS of a compute unit;
     // rows too long for that get one 512-thread workgroup per compute unit, whose pool is
@@ -275,9 +313,22 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
                          dm, di + c.first_item, k, c.pool_slots);                                              \
     };                                                                                                          \
   }
-    EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4)
-    EQ_VARIANT(512, 2) EQ_VARIANT(512, 4) EQ_VARIANT(512, 8)
+#define EQ_CHAN_VARIANT(K_)                                                                                     \
+  if (lc.chunks_per_thread == K_) {                                                                             \
+    fn = reinterpret_cast<const void*>(&quantize_channels128<DT, K_>);                                          \
+    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
+      hipLaunchKernelGGL((quantize_channels128<DT, K_>), dim3((unsigned)c.n_items), dim3(kChanThreads),         \
+                         c.lds_bytes, s, dm, di + c.first_item, k);                                             \
+    };                                                                                                          \
+  }
+    if (lc.kind == 2) {
+      EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
+    } else {
+      EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4)
+      EQ_VARIANT(512, 2) EQ_VARIANT(512, 4) EQ_VARIANT(512, 8)
+    }
 #undef EQ_VARIANT
+#undef EQ_CHAN_VARIANT
     if (!fn) return EQ_E_UNSUPPORTED;
     if (lc.lds_bytes > 65536)
       EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
@@ -436,7 +487,7 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
     m.upr = m.G ? m.cols / m.G : 0;
     m.words_per_row = (int32_t)eq_code_words_per_row(cols[i], p->bits);
     m.path = pl.path[(size_t)i];
-    if (m.path == 1 && ((uintptr_t)o.codes & 15)) return EQ_E_ALIGN;   // 128-bit code stores
+    if (m.path != 0 && ((uintptr_t)o.codes & 15)) return EQ_E_ALIGN;   // 128-bit code stores
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   MatDesc* dmats = reinterpret_cast<MatDesc*>(ws + pl.descs);

@@ -1,0 +1,165 @@
+// Per-channel rows (one range per output channel, the setting of the paper's main tables;
+// Sec. 5, Setup) on the lane-per-128-elements machinery of eq_fused128.h.
+//
+// A row of `cols` = 128 * segs elements is spread over segs consecutive lanes; a workgroup of
+// 256 lanes takes floor(256 / segs) rows per round.  Every lane holds the fixed-point planes of
+// its segment in registers and evaluates its share of the two exact sums of Eq. 2 exactly as
+// the group kernel does; the shares are integers in a fixed-point format common to the row
+// (one exponent from the row's largest magnitude), so the row totals are formed with integer
+// LDS atomics: exact, hence independent of the order in which lanes arrive.  After one barrier
+// per evaluation every lane of the row reads the totals and takes the same Adam step
+// (Sec. 4.2 / Algorithm 1), redundantly, in binary64.
+//
+// Rotation of the accumulators: evaluation p adds into set p mod 3; after its barrier one lane
+// per row clears set (p + 2) mod 3, which was last read before that barrier and is next
+// written after the following one, so one barrier per evaluation suffices.
+//
+// A row whose values are not all multiples of 2^-q (possible for bf16) is evaluated with
+// binary64 partial sums combined in lane order (the whole round then repeats the optimisation
+// that way: the branch has to be uniform for the barriers).
+#pragma once
+
+#include "eq_fused128.h"
+
+namespace eq {
+
+constexpr int kChanThreads = 256;
+constexpr int kChanMaxRows = 16;     // rows per round (rows shorter than 2048 go to the general kernel)
+constexpr int kChanHeader = 5120;    // LDS in front of the pool: staging scratch, then ChanScratch
+constexpr int kChanScratchOff = 2048;
+
+struct RowAcc {
+  uint32_t max_bits, negmin_bits;    // bit patterns of max(x, 0) and max(-x, 0) over the row
+  uint32_t cc[3];                    // sum c^2, three rotating sets
+  uint32_t pad_;
+  unsigned long long xc[3];          // sum (x 2^q) c as a two's-complement 64-bit integer
+};
+struct ChanScratch {
+  RowAcc acc[kChanMaxRows];
+  uint32_t inexact;                  // some row of the round cannot use the fixed-point form
+  uint32_t pad_[3];
+  double part[kChanThreads];         // binary64 shares of the lanes (slow path only)
+};
+static_assert(kChanScratchOff + sizeof(ChanScratch) <= kChanHeader, "LDS header too small");
+
+// K = 16-byte chunks of a row per thread (cols <= 8 * K * 256); rows are staged 16 / K at a time.
+template <int DT, int K>
+__global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_channels128(
+    const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
+  constexpr int NT = kChanThreads;
+  constexpr int RB = 16 / K;
+  typedef BatchScratch<RB> Scratch;
+  static_assert(sizeof(Scratch) <= kChanScratchOff, "staging scratch overlaps the row accumulators");
+  extern __shared__ __align__(16) unsigned char smem[];
+  Scratch* sc = reinterpret_cast<Scratch*>(smem);
+  ChanScratch* cs = reinterpret_cast<ChanScratch*>(smem + kChanScratchOff);
+  unsigned char* pool = smem + kChanHeader;
+  const WorkItem it = items[blockIdx.x];
+  const MatDesc md = mats[it.mat];
+  const uint32_t segs = (uint32_t)md.cols >> 7;                 // lanes per row
+  const uint32_t R = min((uint32_t)NT / segs, (uint32_t)kChanMaxRows);
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const uint32_t my_row = tid / segs, seg = tid - my_row * segs;
+  const int64_t row_end = (int64_t)it.row0 + it.nrows;
+
+  for (int64_t row0 = it.row0; row0 < row_end; row0 += R) {
+    const uint32_t nr = (uint32_t)min((int64_t)R, row_end - row0);
+    if (tid < (uint32_t)kChanMaxRows) {
+      RowAcc z0;
+      z0.max_bits = z0.negmin_bits = z0.pad_ = 0;
+      z0.cc[0] = z0.cc[1] = z0.cc[2] = 0;
+      z0.xc[0] = z0.xc[1] = z0.xc[2] = 0;
+      cs->acc[tid] = z0;
+    }
+    if (tid == 0) cs->inexact = 0;
+    for (uint32_t b = 0; b < nr; b += RB)       // ends with a barrier, which also publishes the clears above
+      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, row0 + b, (int)min((uint32_t)RB, nr - b), pool, b * segs * 16u, sc);
+
+    const bool valid = my_row < nr;
+    unsigned char* slot = pool + (size_t)(valid ? tid : 0u) * kSlotBytes;
+    RowAcc* ra = &cs->acc[valid ? my_row : 0u];
+
+    // ---- range and zero-point of the row; the row's fixed-point exponent ----
+    {
+      float vmin, vmax;
+      slot_min_max<DT>(slot, vmin, vmax);
+      if (valid) {                               // non-negative floats order like their bit patterns
+        atomicMax(&ra->max_bits, __float_as_uint(vmax));
+        atomicMax(&ra->negmin_bits, __float_as_uint(0.0f - vmin));
+      }
+    }
+    __syncthreads();
+    const float vmax = __uint_as_float(ra->max_bits), vmin = -__uint_as_float(ra->negmin_bits);
+    float r0;
+    int z;
+    const bool active = init_unit(kp, vmin, vmax, r0, z);
+    const float clo = (float)(-z), chi = (float)(kp.L - z);
+    const float mlo = clo + kMagic, mhi = chi + kMagic;
+    const float r_start = active ? r0 : kp.D;
+    int E = 0;
+    (void)frexpf(fmaxf(-vmin, vmax), &E);
+    const int q = 30 - E;
+    uint32_t H[kPairs], Lo[kPairs];
+    uint32_t frac_bits = 0;
+    const bool need_test = !(DT == EQ_F16 && __all(q >= 24));
+    if (need_test) build_planes<DT, true>(slot, q, H, Lo, frac_bits);
+    else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
+    if (valid && (frac_bits << 1) != 0) cs->inexact = 1u;      // benign race: every writer stores 1
+
+    uint32_t pass = 0;                           // evaluations so far in this round (selects the accumulator set)
+    float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
+      int cc, hc, lc;
+      eval_sums<DT>(slot, H, Lo, inv, mlo, mhi, cc, hc, lc);
+      const uint32_t set = pass % 3u;
+      if (valid) {
+        atomicAdd(&ra->cc[set], (uint32_t)cc);
+        atomicAdd(&ra->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
+      }
+      __syncthreads();
+      A = (double)ra->cc[set];
+      B = ldexp((double)(long long)ra->xc[set], -q);            // the integer is exact; one rounding at most
+      if (valid && seg == 0) {
+        const uint32_t clr = (pass + 2u) % 3u;
+        ra->cc[clr] = 0;
+        ra->xc[clr] = 0;
+      }
+      ++pass;
+    });
+    __syncthreads();                             // the flag is complete (no evaluation ran when iters == 0)
+    if (cs->inexact) {
+      r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
+        double a_lane, b_lane;
+        eval_slot<DT>(slot, inv, clo, chi, a_lane, b_lane);
+        const uint32_t set = pass % 3u;
+        cs->part[tid] = valid ? b_lane : 0.0;
+        if (valid) atomicAdd(&ra->cc[set], (uint32_t)a_lane);
+        __syncthreads();
+        A = (double)ra->cc[set];
+        double b = 0.0;
+        const uint32_t first = (valid ? my_row : 0u) * segs;
+        for (uint32_t j = 0; j < segs; ++j) b += cs->part[first + j];
+        B = b;
+        if (valid && seg == 0) ra->cc[(pass + 2u) % 3u] = 0;
+        ++pass;
+        __syncthreads();                         // part[] is rewritten by the next evaluation
+      });
+    }
+
+    // ---- emit (Algorithm 1, third step) ----
+    float s32, inv;
+    scale_of(kp, r_sel, s32, inv);
+    __syncthreads();
+    if (valid) {
+      emit_codes_to_slot<DT>(kp, slot, inv, z, mlo, mhi);
+      if (seg == 0) {
+        md.scales[row0 + my_row] = s32;
+        md.zps[row0 + my_row] = (unsigned char)z;
+      }
+    }
+    __syncthreads();
+    copy_wave_codes(kp, md, pool, row0 * (int64_t)segs, wave * kWave, nr * segs, lane);
+    __syncthreads();                             // the pool is overwritten by the next round's staging
+  }
+}
+
+}  // namespace eq

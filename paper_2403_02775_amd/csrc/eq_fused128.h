@@ -116,9 +116,9 @@ __device__ __forceinline__ void build_planes(const unsigned char* slot, int q, u
 // chunk ahead of use), planes from registers.  The compiler barrier keeps the reads inside
 // the iteration loop (hoisted, they would pin 64 more registers).
 template <int DT>
-__device__ __forceinline__ void eval_regs(const unsigned char* slot, const uint32_t (&H)[kPairs],
-                                          const uint32_t (&Lo)[kPairs], float inv, float mlo, float mhi, int q,
-                                          double& A, double& B) {
+__device__ __forceinline__ void eval_sums(const unsigned char* slot, const uint32_t (&H)[kPairs],
+                                          const uint32_t (&Lo)[kPairs], float inv, float mlo, float mhi,
+                                          int& sum_cc, int& sum_hc, int& sum_lc) {
   asm volatile("" ::: "memory");
   int a[4] = {0, 0, 0, 0}, bh[4] = {0, 0, 0, 0}, bl[4] = {0, 0, 0, 0};   // four chains each
   uint4 nxt = *reinterpret_cast<const uint4*>(slot);
@@ -136,8 +136,18 @@ __device__ __forceinline__ void eval_regs(const unsigned char* slot, const uint3
     for (int j = 0; j < 4; ++j) bl[j] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[4 * ch + j]), c[j], bl[j], false);
     __builtin_amdgcn_sched_barrier(0);
   }
-  A = (double)((a[0] + a[1]) + (a[2] + a[3]));
-  B = ldexp((double)((bh[0] + bh[1]) + (bh[2] + bh[3])) * 65536.0 + (double)((bl[0] + bl[1]) + (bl[2] + bl[3])), -q);  // exact: |.| < 2^47
+  sum_cc = (a[0] + a[1]) + (a[2] + a[3]);
+  sum_hc = (bh[0] + bh[1]) + (bh[2] + bh[3]);
+  sum_lc = (bl[0] + bl[1]) + (bl[2] + bl[3]);
+}
+template <int DT>
+__device__ __forceinline__ void eval_regs(const unsigned char* slot, const uint32_t (&H)[kPairs],
+                                          const uint32_t (&Lo)[kPairs], float inv, float mlo, float mhi, int q,
+                                          double& A, double& B) {
+  int cc, hc, lc;
+  eval_sums<DT>(slot, H, Lo, inv, mlo, mhi, cc, hc, lc);
+  A = (double)cc;
+  B = ldexp((double)hc * 65536.0 + (double)lc, -q);  // exact: |.| < 2^47
 }
 
 // The same from the LDS slot with a binary64 accumulation (units the fixed-point form cannot hold).
@@ -159,6 +169,126 @@ __device__ __forceinline__ void eval_slot(const unsigned char* slot, float inv, 
   }
   A = (double)a;
   B = b;
+}
+
+// Smallest and largest value of the unit in `slot`, 0 included.
+template <int DT>
+__device__ __forceinline__ void slot_min_max(const unsigned char* slot, float& vmin, float& vmax) {
+  vmin = 0.0f;
+  vmax = 0.0f;
+  if (DT == EQ_F16) {
+    // packed fp16 min / max over the pairs (exact: they only select), widened once at the end
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    half2_t mn = {(_Float16)0.0f, (_Float16)0.0f}, mx = mn;
+#pragma unroll
+    for (int ch = 0; ch < 16; ++ch) {
+      const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const half2_t h = __builtin_bit_cast(half2_t, w[j]);
+        mn = __builtin_elementwise_min(mn, h);
+        mx = __builtin_elementwise_max(mx, h);
+      }
+    }
+    vmin = fminf((float)mn.x, (float)mn.y);
+    vmax = fmaxf((float)mx.x, (float)mx.y);
+  } else {
+#pragma unroll
+    for (int ch = 0; ch < 16; ++ch) {
+      const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float x0 = widen16<DT>(w[j] & 0xFFFFu), x1 = widen16<DT>(w[j] >> 16);
+        vmin = fminf(vmin, fminf(x0, x1));
+        vmax = fmaxf(vmax, fmaxf(x0, x1));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// Packed codes of the unit in `slot` at reciprocal scale `inv` (Eq. 1), assembled in the upper
+// half of the slot (the values in the lower half stay intact for 4-bit codes only).
+template <int DT>
+__device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned char* slot, float inv, int z, float mlo, float mhi) {
+  if (kp.bits == 4) {
+    // all 16 words first (they overwrite the upper half of the values), then one store burst
+    // The zero-point goes into the magic constant, so the low byte of each pattern is the
+    // unsigned code itself; even and odd elements are gathered into bytes and merged.
+    const float mz = kMagic + (float)z, ulo = kMagic, uhi = kMagic + (float)kp.L;
+    uint32_t o[16];
+#pragma unroll
+    for (int ch = 0; ch < 16; ++ch) {
+      const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      uint32_t f[8];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float x0, x1;
+        if (DT == EQ_F16) {
+          x0 = __half2float(__ushort_as_half((unsigned short)(w[j] & 0xFFFFu)));
+          x1 = __half2float(__ushort_as_half((unsigned short)(w[j] >> 16)));
+        } else {
+          x0 = __uint_as_float(w[j] << 16);
+          x1 = __uint_as_float(w[j] & 0xFFFF0000u);
+        }
+        f[2 * j] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
+        f[2 * j + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
+      }
+      const uint32_t even = __builtin_amdgcn_perm(f[2], f[0], 0x0C0C0400u) | __builtin_amdgcn_perm(f[6], f[4], 0x04000C0Cu);
+      const uint32_t odd = __builtin_amdgcn_perm(f[3], f[1], 0x0C0C0400u) | __builtin_amdgcn_perm(f[7], f[5], 0x04000C0Cu);
+      o[ch] = (odd << 4) | even;
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);
+#pragma unroll
+    for (int wd = 0; wd < 4; ++wd) dst[wd] = make_uint4(o[4 * wd], o[4 * wd + 1], o[4 * wd + 2], o[4 * wd + 3]);
+  } else {
+    // unsigned codes as bytes over the front of the slot (chunk ch yields bytes 8 ch .. 8 ch + 7,
+    // never ahead of the values still to be read), then a bit-stream pack into the upper half
+    for (int ch = 0; ch < 16; ++ch) {
+      const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+      uint32_t f0, f1, f2, f3, f4, f5, f6, f7;
+      pair_levels<DT>(v.x, inv, mlo, mhi, f0, f1);
+      pair_levels<DT>(v.y, inv, mlo, mhi, f2, f3);
+      pair_levels<DT>(v.z, inv, mlo, mhi, f4, f5);
+      pair_levels<DT>(v.w, inv, mlo, mhi, f6, f7);
+      const uint32_t zz = (uint32_t)z;
+      const uint32_t b0 = ((f0 + zz) & 0xFFu) | (((f1 + zz) & 0xFFu) << 8) | (((f2 + zz) & 0xFFu) << 16) | (((f3 + zz) & 0xFFu) << 24);
+      const uint32_t b1 = ((f4 + zz) & 0xFFu) | (((f5 + zz) & 0xFFu) << 8) | (((f6 + zz) & 0xFFu) << 16) | (((f7 + zz) & 0xFFu) << 24);
+      *reinterpret_cast<uint2*>(slot + ch * 8) = make_uint2(b0, b1);
+    }
+    const unsigned char* ub = slot;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(slot + kCodeOff);
+    unsigned long long acc = 0;
+    int nb = 0, wi = 0;
+    for (int e = 0; e < kG; ++e) {
+      acc |= (unsigned long long)ub[e] << nb;
+      nb += kp.bits;
+      if (nb >= 32) {
+        dst[wi++] = (uint32_t)acc;
+        acc >>= 32;
+        nb -= 32;
+      }
+    }
+  }
+}
+
+// The codes of the wavefront's 64 units (slots w_first ..) are contiguous in HBM: coalesced
+// 128-bit stores.  `take` = number of valid slots in the pool, unit_base = matrix-wide index of
+// the unit in slot 0.
+__device__ __forceinline__ void copy_wave_codes(const KParams& kp, const MatDesc& md, const unsigned char* pool,
+                                                int64_t unit_base, uint32_t w_first, uint32_t take, uint32_t lane) {
+  const uint32_t code_words = 4u * (uint32_t)kp.bits;
+  const uint32_t nvalid = w_first < take ? min((uint32_t)kWave, take - w_first) : 0u;
+  const uint32_t nchunk = nvalid * (uint32_t)kp.bits;   // 16-byte chunks
+  uint4* gdst = reinterpret_cast<uint4*>(md.codes + (unit_base + w_first) * (int64_t)code_words);
+  for (uint32_t j = lane; j < nchunk; j += kWave) {
+    const uint32_t un = j / (uint32_t)kp.bits, part = j - un * (uint32_t)kp.bits;
+    gdst[j] = *reinterpret_cast<const uint4*>(pool + (size_t)(w_first + un) * kSlotBytes + kCodeOff + part * 16u);
+  }
 }
 
 // Adam on the range of one unit (per lane); `ev(inv, A, B)` evaluates the exact sums.
@@ -213,7 +343,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   const MatDesc md = mats[it.mat];
   const uint32_t upr = (uint32_t)md.upr;
   const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const uint32_t code_words = 4u * (uint32_t)kp.bits;      // packed words per unit
   int64_t next_row = it.row0;
   const int64_t row_end = (int64_t)it.row0 + it.nrows;
   int64_t unit_base = (int64_t)it.row0 * upr;               // matrix-wide index of the unit in slot 0
@@ -244,38 +373,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
       // ---- range of the unit, and its block fixed-point planes ----
       // xi = x * 2^q with |xi| < 2^30, split into signed 16-bit planes xi = 65536 H + L
-      float vmin = 0.0f, vmax = 0.0f;
-      if (DT == EQ_F16) {
-        // packed fp16 min / max over the pairs (exact: they only select), widened once at the end
-        typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-        half2_t mn = {(_Float16)0.0f, (_Float16)0.0f}, mx = mn;
-#pragma unroll
-        for (int ch = 0; ch < 16; ++ch) {
-          const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const half2_t h = __builtin_bit_cast(half2_t, w[j]);
-            mn = __builtin_elementwise_min(mn, h);
-            mx = __builtin_elementwise_max(mx, h);
-          }
-        }
-        vmin = fminf((float)mn.x, (float)mn.y);
-        vmax = fmaxf((float)mx.x, (float)mx.y);
-      } else {
-#pragma unroll
-        for (int ch = 0; ch < 16; ++ch) {
-          const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float x0 = widen16<DT>(w[j] & 0xFFFFu), x1 = widen16<DT>(w[j] >> 16);
-            vmin = fminf(vmin, fminf(x0, x1));
-            vmax = fmaxf(vmax, fmaxf(x0, x1));
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
+      float vmin, vmax;
+      slot_min_max<DT>(slot, vmin, vmax);
       float r0;
       int z;
       const bool active = init_unit(kp, vmin, vmax, r0, z);
@@ -307,83 +406,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       scale_of(kp, r_sel, s32, inv);
       __syncthreads();              // every lane has finished reading slots that are not its own
       if (valid) {
-        if (kp.bits == 4) {
-          // all 16 words first (they overwrite the upper half of the values), then one store burst
-          // The zero-point goes into the magic constant, so the low byte of each pattern is the
-          // unsigned code itself; even and odd elements are gathered into bytes and merged.
-          const float mz = kMagic + (float)z, ulo = kMagic, uhi = kMagic + (float)kp.L;
-          uint32_t o[16];
-#pragma unroll
-          for (int ch = 0; ch < 16; ++ch) {
-            const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-            uint32_t f[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              float x0, x1;
-              if (DT == EQ_F16) {
-                x0 = __half2float(__ushort_as_half((unsigned short)(w[j] & 0xFFFFu)));
-                x1 = __half2float(__ushort_as_half((unsigned short)(w[j] >> 16)));
-              } else {
-                x0 = __uint_as_float(w[j] << 16);
-                x1 = __uint_as_float(w[j] & 0xFFFF0000u);
-              }
-              f[2 * j] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
-              f[2 * j + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
-            }
-            const uint32_t even = __builtin_amdgcn_perm(f[2], f[0], 0x0C0C0400u) | __builtin_amdgcn_perm(f[6], f[4], 0x04000C0Cu);
-            const uint32_t odd = __builtin_amdgcn_perm(f[3], f[1], 0x0C0C0400u) | __builtin_amdgcn_perm(f[7], f[5], 0x04000C0Cu);
-            o[ch] = (odd << 4) | even;
-            __builtin_amdgcn_sched_barrier(0);
-          }
-          uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);
-#pragma unroll
-          for (int wd = 0; wd < 4; ++wd) dst[wd] = make_uint4(o[4 * wd], o[4 * wd + 1], o[4 * wd + 2], o[4 * wd + 3]);
-        } else {
-          // unsigned codes as bytes over the front of the slot (chunk ch yields bytes 8 ch .. 8 ch + 7,
-          // never ahead of the values still to be read), then a bit-stream pack into the upper half
-          for (int ch = 0; ch < 16; ++ch) {
-            const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-            uint32_t f0, f1, f2, f3, f4, f5, f6, f7;
-            pair_levels<DT>(v.x, inv, mlo, mhi, f0, f1);
-            pair_levels<DT>(v.y, inv, mlo, mhi, f2, f3);
-            pair_levels<DT>(v.z, inv, mlo, mhi, f4, f5);
-            pair_levels<DT>(v.w, inv, mlo, mhi, f6, f7);
-            const uint32_t zz = (uint32_t)z;
-            const uint32_t b0 = ((f0 + zz) & 0xFFu) | (((f1 + zz) & 0xFFu) << 8) | (((f2 + zz) & 0xFFu) << 16) | (((f3 + zz) & 0xFFu) << 24);
-            const uint32_t b1 = ((f4 + zz) & 0xFFu) | (((f5 + zz) & 0xFFu) << 8) | (((f6 + zz) & 0xFFu) << 16) | (((f7 + zz) & 0xFFu) << 24);
-            *reinterpret_cast<uint2*>(slot + ch * 8) = make_uint2(b0, b1);
-          }
-          const unsigned char* ub = slot;
-          uint32_t* dst = reinterpret_cast<uint32_t*>(slot + kCodeOff);
-          unsigned long long acc = 0;
-          int nb = 0, wi = 0;
-          for (int e = 0; e < kG; ++e) {
-            acc |= (unsigned long long)ub[e] << nb;
-            nb += kp.bits;
-            if (nb >= 32) {
-              dst[wi++] = (uint32_t)acc;
-              acc >>= 32;
-              nb -= 32;
-            }
-          }
-        }
+        emit_codes_to_slot<DT>(kp, slot, inv, z, mlo, mhi);
         const int64_t gu = unit_base + slot_i;
         md.scales[gu] = s32;
         md.zps[gu] = (unsigned char)z;
       }
       __syncthreads();
-      // ---- the wavefront's 64 units' codes are contiguous in HBM: coalesced 128-bit stores ----
-      {
-        const uint32_t w_first = base + wave * kWave;
-        const uint32_t nvalid = w_first < take ? min((uint32_t)kWave, take - w_first) : 0u;
-        const uint32_t nchunk = nvalid * (uint32_t)kp.bits;   // 16-byte chunks
-        uint4* gdst = reinterpret_cast<uint4*>(md.codes + (unit_base + w_first) * (int64_t)code_words);
-        for (uint32_t j = lane; j < nchunk; j += kWave) {
-          const uint32_t un = j / (uint32_t)kp.bits, part = j - un * (uint32_t)kp.bits;
-          gdst[j] = *reinterpret_cast<const uint4*>(pool + (size_t)(w_first + un) * kSlotBytes + kCodeOff + part * 16u);
-        }
-      }
+      copy_wave_codes(kp, md, pool, unit_base, base + wave * kWave, take, lane);
     }
     __syncthreads();
     // ---- carry the units that did not fill a round to the front of the pool ----

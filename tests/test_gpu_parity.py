@@ -63,6 +63,47 @@ def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_it
         assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
 
+@pytest.mark.parametrize("rows,cols,units_per_item", [(37, 4096, 0), (21, 8192, 300), (5, 22016, 0), (11, 11008, 0),
+                                                      (13, 5120, 0), (40, 2048, 512), (3, 32768, 0)])
+def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, monkeypatch):
+    # one range per row, the row spread over cols / 128 lanes: rounds of 8, 4, 1, 2, 6, 16 and 1
+    # rows, a ragged last round, several rounds per work item, staging in one or several batches
+    if units_per_item:
+        monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", str(units_per_item))
+    W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows * 7 + cols, device=DEV)
+    for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
+        res = _check(W, eqo.Params(bits=bits, group_size=0, mode=mode, iters=12), f"channel kernel {rows}x{cols}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+
+
+def test_per_channel_lane_kernel_variants():
+    W = eq_inputs.gen_matrix(19, 4096, eq_inputs.RECIPES["c5"], seed=77, device=DEV)
+    _check(W, eqo.Params(bits=4, group_size=0, iters=0), "channel T=0")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=1), "channel T=1")
+    _check(W, eqo.Params(bits=4, group_size=4096, iters=40, select=eqo.SELECT_LAST), "channel select=last, G=cols")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=10, stat_scope=eqo.STAT_MATRIX), "channel matrix scope")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=10, stat_scope=eqo.STAT_GROUP), "channel group scope")
+    _check(W, eqo.Params(bits=8, group_size=0, iters=10), "channel 8-bit")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=200, lr=1e-4), "channel T=200 lr=1e-4")
+    Wz = W.clone()
+    Wz[4] = 0                                            # an all-zero row keeps scale 1
+    Wz[7, 100:] = 0
+    _check(Wz, eqo.Params(bits=4, group_size=0, iters=10), "channel zero rows")
+
+
+@pytest.mark.parametrize("G", [128, 0])
+def test_bf16_wide_exponent_span_takes_the_binary64_evaluation(G):
+    # values far below the block fixed-point resolution of their unit (2^-22 of its largest
+    # magnitude) cannot be held in the integer planes: those units / rows are evaluated in binary64
+    W = eq_inputs.gen_matrix(24, 4096, eq_inputs.with_dtype(eq_inputs.RECIPES["c5"], "bf16"), seed=91, device=DEV)
+    W[1, 5] = 1e-12
+    W[1, 700] = -3e-15
+    W[9, 4095] = 7e-20
+    W[17, 0] = 1e-30
+    res = _check(W, eqo.Params(dtype=eqo.BF16, bits=4, group_size=G, iters=15), f"bf16 wide span G={G}")
+    assert res["excused_elems"] == 0
+
+
 def test_bf16_and_student_t_inputs():
     W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
