@@ -51,18 +51,18 @@ def build_workload(name, layers, device):
     return Ws, names, bits, dt
 
 
-def algorithmic_bytes(Ws, bits, n_outliers):
+def algorithmic_bytes(Ws, bits, n_outliers, group_size=128):
     """HBM bytes the path must move: read W once; write codes, scale + zero-point, outliers (col + value) and row_ptr."""
     elems = sum(w.numel() for w in Ws)
-    units = elems // 128
     rows = sum(w.shape[0] for w in Ws)
+    units = elems // group_size if group_size else rows
     return elems * 2 + elems * bits // 8 + units * 5 + n_outliers * 6 + (rows + len(Ws)) * 4
 
 
-def measured_traffic(workload, iters):
+def measured_traffic(workload, iters, kernel="quantize_units128"):
     """HBM bytes per step of the main kernels from the committed counter summary (rocprofv3 --pmc
     FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size), if one exists for this workload."""
-    path = os.path.join(ROOT, "profiles", f"quantize_units128_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
     if workload is None or not os.path.exists(path):
         return None
     vals = {}
@@ -142,6 +142,7 @@ def main():
     ap.add_argument("--layers", type=int, default=-1, help="limit the number of layers (debugging; changes the workload)")
     ap.add_argument("--iters", type=int, default=100, help="Adam steps T on the range")
     ap.add_argument("--lr", type=float, default=1e-3)
+    ap.add_argument("--group-size", type=int, default=128, help="0 = one range per output channel (secondary measurement)")
     ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
     ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the first matrix given to the CPU oracle (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -161,7 +162,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     Ws, names, bits, dt = build_workload(args.workload, args.layers, dev)
-    gp = eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=128, mode=eqg.EQ_SYMMETRIC,
+    gp = eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=args.group_size, mode=eqg.EQ_SYMMETRIC,
                     stat_scope=eqg.EQ_STAT_ROW, n_sigma=3.0, iters=args.iters, lr=args.lr, select=eqg.EQ_SELECT_BEST)
     caps = [int(w.numel() * args.capacity_frac) for w in Ws]
     outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, dev) for w, c in zip(Ws, caps)]
@@ -210,7 +211,7 @@ def main():
     passes = args.iters + 2                       # T+1 evaluations (best-iterate selection) + the emitting one
     lane_ops = elems * (5 * passes + 12)          # useful lane-operations: 5 per element and pass, 12 fixed
     kern_s = kern_ms * 1e-3 / args.steps          # main kernels per step (one launch per row-length class)
-    alg_bytes = algorithmic_bytes(Ws, bits, n_out)
+    alg_bytes = algorithmic_bytes(Ws, bits, n_out, args.group_size)
     alu_frac = lane_ops / kern_s / ALU_PEAK
     hbm_frac = alg_bytes / kern_s / HBM_PEAK
     if alu_frac >= hbm_frac:
@@ -219,8 +220,9 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": alg_bytes / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
-    roof["traffic"] = measured_traffic(args.workload if args.layers < 0 else None, args.iters)
-    roof.update({"kernel": "quantize_units128", "launches_per_step": launches / args.steps,
+    kernel = "quantize_units128" if args.group_size == 128 else "quantize_channels128" if args.group_size == 0 else "quantize_rows_generic"
+    roof["traffic"] = measured_traffic(args.workload if args.layers < 0 else None, args.iters, kernel)
+    roof.update({"kernel": kernel, "launches_per_step": launches / args.steps,
                  "kernel_ms_per_step": kern_ms / args.steps, "avg_launch_ms": kern_ms / max(launches, 1),
                  "algorithmic_bytes": alg_bytes, "hbm_frac": hbm_frac, "alu_frac": alu_frac,
                  "lane_ops_per_element": 5 * passes + 12})
@@ -231,7 +233,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if True else None, "data": "synthetic",
         "config": {"workload": args.workload + ("" if args.layers < 0 else f"[first {args.layers} layers]"),
-                   "matrices": len(Ws), "elements": elems, "bits": bits, "group_size": 128, "mode": "symmetric",
+                   "matrices": len(Ws), "elements": elems, "bits": bits, "group_size": args.group_size, "mode": "symmetric",
                    "n_sigma": 3.0, "iters": args.iters, "lr": args.lr, "select": "best", "weights_dtype": dt,
                    "parallelism": "1 GPU, one batch call"},
         "seconds_per_model": ms_per_step * 1e-3,
@@ -241,7 +243,7 @@ def main():
         "roofline": roof,
     }
     if args.cpu_rows > 0:
-        kw = dict(dtype=gp.dtype, bits=bits, group_size=128, mode=0, stat_scope=0, n_sigma=3.0, iters=args.iters,
+        kw = dict(dtype=gp.dtype, bits=bits, group_size=args.group_size, mode=0, stat_scope=0, n_sigma=3.0, iters=args.iters,
                   lr=args.lr, select=0)
         gbs, secs, shape = cpu_baseline(Ws, kw, args.cpu_rows)
         out["cpu_baseline"] = {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",

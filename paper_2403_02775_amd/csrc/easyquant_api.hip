@@ -149,8 +149,12 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
   pl.path.assign((size_t)n, 0);
   // ---- launch plan ----
   std::vector<int32_t> order;
+  const char* fg = std::getenv("EASYQUANT_FORCE_GENERAL");        // test / measurement override
+  const bool force_general = fg && fg[0] == '1';
   for (int32_t i = 0; i < n; ++i) {
-    if (lane_kernel_ok(rows[i], cols[i], p)) {
+    if (force_general) {
+      if (rows[i] > 0 && cols[i] > 0) pl.any_general = true;
+    } else if (lane_kernel_ok(rows[i], cols[i], p)) {
       pl.path[(size_t)i] = 1;
       order.push_back(i);
     } else if (channel_kernel_ok(rows[i], cols[i], p)) {

@@ -42,6 +42,21 @@ struct ChanScratch {
 };
 static_assert(kChanScratchOff + sizeof(ChanScratch) <= kChanHeader, "LDS header too small");
 
+// Sums over aligned groups of lanes with data-parallel-primitive adds (no LDS): after the four
+// row_shr steps lane 15 of every 16-lane row holds the row's sum; WIDE adds row 0 into row 1
+// and row 2 into row 3 (row_bcast:15), so that lanes 31 and 63 hold the sums of their 32-lane
+// halves.  Other lanes hold partial sums.  32-bit wrap-around cannot occur for the callers:
+// |level| <= 15 and 16-bit plane values over 32 * 128 elements stay below 2^31.
+template <bool WIDE>
+__device__ __forceinline__ int group_sum_dpp(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+  if (WIDE) v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, true);   // row_bcast:15 into rows 1 and 3
+  return v;
+}
+
 // K = 16-byte chunks of a row per thread (cols <= 8 * K * 256); rows are staged 16 / K at a time.
 template <int DT, int K>
 __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_channels128(
@@ -106,12 +121,67 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
     else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
     if (valid && (frac_bits << 1) != 0) cs->inexact = 1u;      // benign race: every writer stores 1
 
+    // How the lanes of a row combine their shares (all three choices give the same exact sums):
+    //  * a row that lies inside one wavefront in an aligned group of 16, 32 or 64 lanes needs no
+    //    LDS and no barrier: group sums by lane shifts, then every lane fetches its group's sums;
+    //  * otherwise the shares go to the row's LDS accumulators, one barrier per evaluation;
+    //    a wavefront whose 32-lane halves each hold lanes of one row only adds the two half sums
+    //    instead of 64 single shares (64 atomics on one address serialise).
+    // The 32-bit group sums need |level| <= 15, i.e. at most 4 bits.
+    const bool small_levels = kp.bits <= 4;
+    const bool in_wave = small_levels && (segs == 16u || segs == 32u || segs == 64u);     // uniform over the grid
+    const uint32_t half_row = (uint32_t)__shfl((int)my_row, (int)(lane & 32u));
+    const bool half_valid = __shfl((int)valid, (int)(lane & 32u)) != 0;
+    const bool halves_uniform = small_levels && __all(!valid || my_row == half_row);      // uniform over the wavefront
+    RowAcc* ha = &cs->acc[half_valid ? half_row : 0u];
+
     uint32_t pass = 0;                           // evaluations so far in this round (selects the accumulator set)
     float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
       int cc, hc, lc;
       eval_sums<DT>(slot, H, Lo, inv, mlo, mhi, cc, hc, lc);
+      if (in_wave) {
+        if (!valid) cc = hc = lc = 0;
+        int tc, th, tl;
+        long long xq;
+        if (segs == 16u) {
+          cc = group_sum_dpp<false>(cc);
+          hc = group_sum_dpp<false>(hc);
+          lc = group_sum_dpp<false>(lc);
+          const int src = (int)(lane | 15u);
+          tc = __shfl(cc, src);
+          th = __shfl(hc, src);
+          tl = __shfl(lc, src);
+          xq = (long long)th * 65536 + (long long)tl;
+        } else {
+          cc = group_sum_dpp<true>(cc);
+          hc = group_sum_dpp<true>(hc);
+          lc = group_sum_dpp<true>(lc);
+          const int c0 = __builtin_amdgcn_readlane(cc, 31), c1 = __builtin_amdgcn_readlane(cc, 63);
+          const long long x0 = (long long)__builtin_amdgcn_readlane(hc, 31) * 65536 + (long long)__builtin_amdgcn_readlane(lc, 31);
+          const long long x1 = (long long)__builtin_amdgcn_readlane(hc, 63) * 65536 + (long long)__builtin_amdgcn_readlane(lc, 63);
+          if (segs == 64u) {
+            tc = c0 + c1;
+            xq = x0 + x1;
+          } else {
+            tc = lane < 32u ? c0 : c1;
+            xq = lane < 32u ? x0 : x1;
+          }
+        }
+        A = (double)tc;
+        B = ldexp((double)xq, -q);
+        return;
+      }
       const uint32_t set = pass % 3u;
-      if (valid) {
+      if (halves_uniform) {
+        if (!valid) cc = hc = lc = 0;
+        cc = group_sum_dpp<true>(cc);
+        hc = group_sum_dpp<true>(hc);
+        lc = group_sum_dpp<true>(lc);
+        if ((lane & 31u) == 31u && half_valid) {
+          atomicAdd(&ha->cc[set], (uint32_t)cc);
+          atomicAdd(&ha->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
+        }
+      } else if (valid) {
         atomicAdd(&ra->cc[set], (uint32_t)cc);
         atomicAdd(&ra->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
       }
