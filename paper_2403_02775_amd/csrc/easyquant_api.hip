@@ -17,6 +17,7 @@
 #include "eq_generic.h"
 #include "eq_post.h"
 #include "eq_rowstage.h"
+#include "eq_rtn128.h"
 
 namespace {
 
@@ -44,6 +45,10 @@ struct ScopedKernelTimer {
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// A caller's device pointer as the descriptors store it (global address space).
+template <class T>
+inline EQ_GLOBAL T* dev(T* p) { return (EQ_GLOBAL T*)p; }
 
 constexpr int kMatrixStatParts = 1024;   // workgroups of the whole-matrix statistics pre-pass
 
@@ -90,7 +95,8 @@ KParams make_kparams(const eq_params* p) {
 
 // One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
 struct LaneClass {
-  int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes
+  int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes,
+                                        // 3: group of 128 without optimisation steps (load-pipelined kernel)
   int32_t cols = 0, upr = 0;
   int32_t threads = kThreads;           // workgroup size = units per round
   int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
@@ -190,6 +196,33 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       }
       int64_t rpi = std::max<int64_t>(rpr, target / upr);
       rpi -= rpi % rpr;
+      lc.first_item = pl.work.size();
+      for (size_t j = k; j < e; ++j) {
+        const int32_t m = order[j];
+        for (int64_t r = 0; r < rows[m]; r += rpi)
+          pl.work.push_back(WorkItem{m, (int32_t)r, (int32_t)std::min<int64_t>(rpi, rows[m] - r), 0});
+      }
+      lc.n_items = pl.work.size() - lc.first_item;
+      pl.classes.push_back(lc);
+      k = e;
+      continue;
+    }
+    if (p->iters == 0) {
+      // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
+      lc.kind = 3;
+      lc.threads = kRtnThreads;
+      const int64_t per_thread = (c / 8 + kRtnThreads - 1) / kRtnThreads;
+      lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : per_thread <= 8 ? 8 : 16;
+      const int64_t rpb = 16 / lc.chunks_per_thread;
+      lc.pool_slots = (uint32_t)(rpb * upr);
+      lc.lds_bytes = (size_t)kLdsHeader + (size_t)lc.pool_slots * kSlotBytes;
+      int64_t target = std::min<int64_t>(32768, std::max<int64_t>(kRtnThreads, total_units / 4096));
+      if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
+        const long v = std::atol(ov);
+        if (v > 0) target = v;
+      }
+      int64_t rpi = std::max<int64_t>(rpb, target / upr);
+      rpi -= rpi % rpb;
       lc.first_item = pl.work.size();
       for (size_t j = k; j < e; ++j) {
         const int32_t m = order[j];
@@ -325,7 +358,17 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
                          c.lds_bytes, s, dm, di + c.first_item, k);                                             \
     };                                                                                                          \
   }
-    if (lc.kind == 2) {
+#define EQ_RTN_VARIANT(K_)                                                                                      \
+  if (lc.chunks_per_thread == K_) {                                                                             \
+    fn = reinterpret_cast<const void*>(&quantize_rtn128<DT, K_>);                                               \
+    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
+      hipLaunchKernelGGL((quantize_rtn128<DT, K_>), dim3((unsigned)c.n_items), dim3(kRtnThreads), c.lds_bytes,  \
+                         s, dm, di + c.first_item, k);                                                          \
+    };                                                                                                          \
+  }
+    if (lc.kind == 3) {
+      EQ_RTN_VARIANT(1) EQ_RTN_VARIANT(2) EQ_RTN_VARIANT(4) EQ_RTN_VARIANT(8) EQ_RTN_VARIANT(16)
+    } else if (lc.kind == 2) {
       EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
     } else {
       EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4)
@@ -333,6 +376,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
     }
 #undef EQ_VARIANT
 #undef EQ_CHAN_VARIANT
+#undef EQ_RTN_VARIANT
     if (!fn) return EQ_E_UNSUPPORTED;
     if (lc.lds_bytes > 65536)
       EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
@@ -471,17 +515,17 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
     MatDesc& m = h[(size_t)i];
     std::memset(&m, 0, sizeof(m));
     const eq_qmatrix& o = outs[i];
-    m.W = static_cast<const uint16_t*>(W[i]);
-    m.codes = o.codes; m.scales = o.scales; m.zps = o.zero_points;
-    m.out_row_ptr = o.out_row_ptr; m.out_col = o.out_col; m.out_val = o.out_val; m.status = o.status;
-    m.cursor = reinterpret_cast<unsigned long long*>(ws + pl.cursor[(size_t)i]);
-    m.row_count = reinterpret_cast<uint32_t*>(ws + pl.row_count[(size_t)i]);
-    m.row_stage = reinterpret_cast<uint32_t*>(ws + pl.row_stage[(size_t)i]);
-    m.st_col = reinterpret_cast<uint32_t*>(ws + pl.st_col[(size_t)i]);
-    m.st_val = reinterpret_cast<uint16_t*>(ws + pl.st_val[(size_t)i]);
+    m.W = dev(static_cast<const uint16_t*>(W[i]));
+    m.codes = dev(o.codes); m.scales = dev(o.scales); m.zps = dev(o.zero_points);
+    m.out_row_ptr = dev(o.out_row_ptr); m.out_col = dev(o.out_col); m.out_val = dev(o.out_val); m.status = dev(o.status);
+    m.cursor = dev(reinterpret_cast<unsigned long long*>(ws + pl.cursor[(size_t)i]));
+    m.row_count = dev(reinterpret_cast<uint32_t*>(ws + pl.row_count[(size_t)i]));
+    m.row_stage = dev(reinterpret_cast<uint32_t*>(ws + pl.row_stage[(size_t)i]));
+    m.st_col = dev(reinterpret_cast<uint32_t*>(ws + pl.st_col[(size_t)i]));
+    m.st_val = dev(reinterpret_cast<uint16_t*>(ws + pl.st_val[(size_t)i]));
     if (p->stat_scope == EQ_STAT_MATRIX) {
-      m.mat_stats = reinterpret_cast<double*>(ws + pl.mat_stats[(size_t)i]);
-      m.mat_partial = reinterpret_cast<double*>(ws + pl.mat_partial[(size_t)i]);
+      m.mat_stats = dev(reinterpret_cast<double*>(ws + pl.mat_stats[(size_t)i]));
+      m.mat_partial = dev(reinterpret_cast<double*>(ws + pl.mat_partial[(size_t)i]));
     }
     m.ld = ld[i];
     m.capacity = clamp_capacity(o.out_capacity);
@@ -504,7 +548,7 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   const std::vector<double> tab = make_adam_table(p);
   double* dtab = reinterpret_cast<double*>(ws + pl.adam);
   EQ_HIP(hipMemcpyAsync(dtab, tab.data(), sizeof(double) * tab.size(), hipMemcpyHostToDevice, st));
-  kp.adam_tab = dtab;
+  kp.adam_tab = dev(dtab);
   return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, h, pl, kp, st)
                             : launch_all<EQ_BF16>(n, dmats, ditems, h, pl, kp, st);
 }

@@ -23,24 +23,30 @@ constexpr int kWave = 64;                // CDNA wavefront
 constexpr int kWaves = kThreads / kWave;
 constexpr int kMaxWaves = 8;             // largest workgroup any kernel here uses: 512 threads
 
+// Pointers into device memory carry the global address space: a pointer read back from a
+// descriptor is otherwise a generic one, every access through it a FLAT instruction, and a
+// workgroup barrier then has to wait for all of them (stores included), because a generic
+// access might have been to LDS.
+#define EQ_GLOBAL __attribute__((address_space(1)))
+
 // One matrix of a batch: inputs, outputs and its slice of the workspace.
 struct MatDesc {
-  const uint16_t* W;
-  uint32_t* codes;
-  float* scales;
-  uint8_t* zps;
-  uint32_t* out_row_ptr;
-  uint32_t* out_col;
-  uint16_t* out_val;
-  int32_t* status;
+  const EQ_GLOBAL uint16_t* W;
+  EQ_GLOBAL uint32_t* codes;
+  EQ_GLOBAL float* scales;
+  EQ_GLOBAL uint8_t* zps;
+  EQ_GLOBAL uint32_t* out_row_ptr;
+  EQ_GLOBAL uint32_t* out_col;
+  EQ_GLOBAL uint16_t* out_val;
+  EQ_GLOBAL int32_t* status;
   // workspace
-  unsigned long long* cursor;   // next free staging entry
-  uint32_t* row_count;          // outliers per row
-  uint32_t* row_stage;          // first staging entry of the row
-  uint32_t* st_col;             // staging (arrival order, one contiguous run per row)
-  uint16_t* st_val;
-  double* mat_stats;            // [0] mean, [1] sigma of the whole matrix (EQ_STAT_MATRIX)
-  double* mat_partial;          // per-workgroup partial sums of the pre-pass
+  EQ_GLOBAL unsigned long long* cursor;   // next free staging entry
+  EQ_GLOBAL uint32_t* row_count;          // outliers per row
+  EQ_GLOBAL uint32_t* row_stage;          // first staging entry of the row
+  EQ_GLOBAL uint32_t* st_col;             // staging (arrival order, one contiguous run per row)
+  EQ_GLOBAL uint16_t* st_val;
+  EQ_GLOBAL double* mat_stats;            // [0] mean, [1] sigma of the whole matrix (EQ_STAT_MATRIX)
+  EQ_GLOBAL double* mat_partial;          // per-workgroup partial sums of the pre-pass
   int64_t ld;
   int64_t capacity;
   int32_t rows, cols;
@@ -62,13 +68,46 @@ struct KParams {
   double rD64;      // RN(1 / D) in binary64
   float rD32;       // RN(1 / D) in binary32
   float pad2_;
-  const double* adam_tab;   // device: per step t (0-based) {1 - b1^(t+1), RN(1 / that), 1 - b2^(t+1), RN(1 / that)}
+  const EQ_GLOBAL double* adam_tab;   // device: per step t (0-based) {1 - b1^(t+1), RN(1 / that), 1 - b2^(t+1), RN(1 / that)}
 };
 
-// 128-bit streaming load: the data is used once, so it is marked non-temporal.
+// Relaxed device-scope atomics on global memory (the HIP wrappers take generic pointers).
+__device__ __forceinline__ unsigned long long global_atomic_add(EQ_GLOBAL unsigned long long* p, unsigned long long v) {
+  return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void global_atomic_or(EQ_GLOBAL int32_t* p, int32_t v) {
+  (void)__hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// 128-bit accesses to global memory (vector types without constructors: the HIP ones cannot be
+// read through an address-space-qualified pointer).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_stream128(const void* p) {
-  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+typedef double f64x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 global_load128(const EQ_GLOBAL void* p) {
+  const u32x4_t v = *reinterpret_cast<const EQ_GLOBAL u32x4_t*>(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+// streaming variant: the data is used once, so it is marked non-temporal
+__device__ __forceinline__ uint4 global_load_stream128(const EQ_GLOBAL void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const EQ_GLOBAL u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void global_store128(EQ_GLOBAL void* p, const uint4 v) {
+  u32x4_t t;
+  t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  *reinterpret_cast<EQ_GLOBAL u32x4_t*>(p) = t;
+}
+
+// Range-checked view of `bytes` bytes at the wavefront-uniform address `base` (a raw buffer
+// resource, stride 0): a load whose offset lies beyond the end returns zero and touches no
+// memory, so ragged rows and absent rows need no branch around their loads, and the loads do
+// not count as LDS traffic the way loads through generic pointers do.
+typedef __amdgpu_buffer_rsrc_t BufferRsrc;
+__device__ __forceinline__ BufferRsrc make_buffer(const EQ_GLOBAL void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);   // untyped 32-bit data
+}
+__device__ __forceinline__ uint4 buffer_load_stream128(BufferRsrc rs, uint32_t byte_offset) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_offset, 0, 2);           // 2: non-temporal
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -198,8 +237,8 @@ struct Adam {
   }
 };
 __device__ __forceinline__ void load_bias_corrections(const KParams& kp, int t, double (&bc)[4]) {
-  const double2* p = reinterpret_cast<const double2*>(kp.adam_tab + 4 * t);
-  const double2 a = p[0], b = p[1];
+  const EQ_GLOBAL f64x2_t* p = reinterpret_cast<const EQ_GLOBAL f64x2_t*>(kp.adam_tab + 4 * t);
+  const f64x2_t a = p[0], b = p[1];
   bc[0] = a.x; bc[1] = a.y; bc[2] = b.x; bc[3] = b.y;
 }
 // scale and reciprocal scale of a range (binary32, correctly rounded)

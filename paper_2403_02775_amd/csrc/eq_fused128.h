@@ -217,7 +217,12 @@ __device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned c
     // all 16 words first (they overwrite the upper half of the values), then one store burst
     // The zero-point goes into the magic constant, so the low byte of each pattern is the
     // unsigned code itself; even and odd elements are gathered into bytes and merged.
-    const float mz = kMagic + (float)z, ulo = kMagic, uhi = kMagic + (float)kp.L;
+    // Ties go to the even value of the whole sum, so the constant added must stay even for
+    // them to go to the even level: an odd zero-point is folded in as z + 1, and the 1 is
+    // taken off the gathered bytes (every byte is then >= 1: no borrow between bytes).
+    const int zodd = z & 1;
+    const uint32_t unfold = zodd ? 0x01010101u : 0u;
+    const float mz = kMagic + (float)(z + zodd), ulo = kMagic + (float)zodd, uhi = kMagic + (float)(kp.L + zodd);
     uint32_t o[16];
 #pragma unroll
     for (int ch = 0; ch < 16; ++ch) {
@@ -239,7 +244,7 @@ __device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned c
       }
       const uint32_t even = __builtin_amdgcn_perm(f[2], f[0], 0x0C0C0400u) | __builtin_amdgcn_perm(f[6], f[4], 0x04000C0Cu);
       const uint32_t odd = __builtin_amdgcn_perm(f[3], f[1], 0x0C0C0400u) | __builtin_amdgcn_perm(f[7], f[5], 0x04000C0Cu);
-      o[ch] = (odd << 4) | even;
+      o[ch] = ((odd - unfold) << 4) | (even - unfold);
       __builtin_amdgcn_sched_barrier(0);
     }
     uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);
@@ -284,10 +289,10 @@ __device__ __forceinline__ void copy_wave_codes(const KParams& kp, const MatDesc
   const uint32_t code_words = 4u * (uint32_t)kp.bits;
   const uint32_t nvalid = w_first < take ? min((uint32_t)kWave, take - w_first) : 0u;
   const uint32_t nchunk = nvalid * (uint32_t)kp.bits;   // 16-byte chunks
-  uint4* gdst = reinterpret_cast<uint4*>(md.codes + (unit_base + w_first) * (int64_t)code_words);
+  EQ_GLOBAL uint32_t* gdst = md.codes + (unit_base + w_first) * (int64_t)code_words;
   for (uint32_t j = lane; j < nchunk; j += kWave) {
     const uint32_t un = j / (uint32_t)kp.bits, part = j - un * (uint32_t)kp.bits;
-    gdst[j] = *reinterpret_cast<const uint4*>(pool + (size_t)(w_first + un) * kSlotBytes + kCodeOff + part * 16u);
+    global_store128(gdst + 4 * (size_t)j, *reinterpret_cast<const uint4*>(pool + (size_t)(w_first + un) * kSlotBytes + kCodeOff + part * 16u));
   }
 }
 

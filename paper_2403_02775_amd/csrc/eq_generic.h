@@ -141,9 +141,9 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_generic(const MatDesc*
     scale_of(kp, r_sel, s32, inv);
     const uint32_t nelem = (uint32_t)md.G;
     const unsigned short* xe = reinterpret_cast<const unsigned short*>(x);
-    uint32_t* wrow = md.codes + row * (int64_t)md.words_per_row + (int64_t)u * ((int64_t)nelem * kp.bits / 32);
+    EQ_GLOBAL uint32_t* wrow = md.codes + row * (int64_t)md.words_per_row + (int64_t)u * ((int64_t)nelem * kp.bits / 32);
     for (uint32_t g32 = lane; g32 * 32u < nelem; g32 += kWave) {
-      uint32_t* wp = wrow + g32 * (uint32_t)kp.bits;
+      EQ_GLOBAL uint32_t* wp = wrow + g32 * (uint32_t)kp.bits;
       unsigned long long acc = 0;
       int nb = 0, wi = 0;
       for (uint32_t e = 0; e < 32u && g32 * 32u + e < nelem; ++e) {

@@ -94,9 +94,9 @@ __global__ __launch_bounds__(kThreads) void matrix_partial_sums(const MatDesc* _
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
   double s = 0.0;
   for (int64_t row = blockIdx.x; row < md.rows; row += gridDim.x) {
-    const uint4* src = reinterpret_cast<const uint4*>(md.W + row * md.ld);
+    const EQ_GLOBAL uint16_t* src = md.W + row * md.ld;
     for (uint32_t ch = threadIdx.x; ch < nchunks; ch += kThreads) {
-      const uint4 v = src[ch];
+      const uint4 v = global_load128(src + 8 * (size_t)ch);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int k = 0; k < 8; ++k) {

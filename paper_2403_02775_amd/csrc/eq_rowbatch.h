@@ -50,29 +50,34 @@ __device__ __forceinline__ void chunk_floats(const uint4 v, float (&x)[8]) {
   }
 }
 
-// Stages rows [row0, row0 + nrows), nrows <= RB, of matrix md: chunk ch of row r goes to
+// Staging of rows [row0, row0 + nrows), nrows <= RB, of matrix md: chunk ch of row r goes to
 // Layout::off(ch0 + r * chunks_per_row + ch).  Thread t owns chunks t, t + NT, ... (K of them
 // per row).  Ends with a barrier; afterwards the pool holds the normal values and 0 at
 // outlier positions, and the outliers sit in the staging area (one run per row, any order).
+// Split in two so that a caller can have the next batch's loads in flight while it works.
+// Issues every 128-bit load of rows [row0, row0 + nrows): thread t takes chunks t, t + NT, ...
+// of each row; absent rows and chunks read as zero.
+template <int NT, int RB, int K>
+__device__ __forceinline__ void batch_issue_loads(const MatDesc& md, int64_t row0, int nrows, uint4 (&v)[RB][K]) {
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    const bool present = r < nrows;
+    const BufferRsrc rs = make_buffer(md.W + (present ? row0 + r : row0) * md.ld, present ? (uint32_t)md.cols * 2u : 0u);
+#pragma unroll
+    for (int i = 0; i < K; ++i) v[r][i] = buffer_load_stream128(rs, ((uint32_t)i * NT + threadIdx.x) * 16u);
+  }
+}
+
+// Everything after the loads (v = what batch_issue_loads returned for the same rows).
 template <int DT, int NT, int RB, int K, class Layout>
-__device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
-                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc) {
+__device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
+                                                  unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc,
+                                                  const uint4 (&v)[RB][K]) {
   static_assert(RB * K <= 32, "candidate flags are one 32-bit word");
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int NW = NT / kWave;
 
-  // ---- every load of the batch in flight ----
-  uint4 v[RB][K];
-#pragma unroll
-  for (int r = 0; r < RB; ++r) {
-    const uint4* src = reinterpret_cast<const uint4*>(md.W + (row0 + r) * md.ld);
-#pragma unroll
-    for (int i = 0; i < K; ++i) {
-      const uint32_t ch = (uint32_t)i * NT + tid;
-      v[r][i] = (r < nrows && ch < nchunks) ? load_stream128(src + ch) : make_uint4(0, 0, 0, 0);
-    }
-  }
   if (tid < (uint32_t)RB) {
     sc->slow[tid] = 0;
     sc->rowcnt[tid] = 0;
@@ -117,7 +122,7 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
       sc->part[r][wave][1] = s2;
     }
   }
-  if (__any(bad) && lane == 0) atomicOr(md.status, EQ_S_NONFINITE);
+  if (__any(bad) && lane == 0) global_atomic_or(md.status, EQ_S_NONFINITE);
   __syncthreads();
 
   // ---- thresholds; one test per chunk: can any of its elements be an outlier? ----
@@ -257,13 +262,13 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
     uint32_t total = 0;
     for (int r = 0; r < nrows; ++r) total += sc->rowcnt[r];
     unsigned long long b = 0;
-    if (total) b = atomicAdd(md.cursor, (unsigned long long)total);
+    if (total) b = global_atomic_add(md.cursor, (unsigned long long)total);
     for (int r = 0; r < nrows; ++r) {
       const uint32_t t = sc->rowcnt[r];
       const bool fits = b + t <= (unsigned long long)md.capacity;
       md.row_count[row0 + r] = t;
       md.row_stage[row0 + r] = fits ? (uint32_t)b : 0xFFFFFFFFu;
-      if (!fits) atomicOr(md.status, EQ_S_OUTLIER_OVERFLOW);
+      if (!fits) global_atomic_or(md.status, EQ_S_OUTLIER_OVERFLOW);
       sc->rowbase[r] = fits ? b : ~0ull;
       b += t;
     }
@@ -313,6 +318,14 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
     }
   }
   __syncthreads();
+}
+
+template <int DT, int NT, int RB, int K, class Layout>
+__device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
+                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc) {
+  uint4 v[RB][K];
+  batch_issue_loads<NT, RB, K>(md, row0, nrows, v);     // every load of the batch in flight
+  stage_loaded_rows<DT, NT, RB, K, Layout>(md, kp, row0, nrows, pool, ch0, sc, v);
 }
 
 }  // namespace eq

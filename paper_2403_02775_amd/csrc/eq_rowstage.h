@@ -81,16 +81,16 @@ __device__ __forceinline__ uint32_t chunk_mask(const uint4 v, double mu, double 
 template <int DT, class Layout>
 __device__ __forceinline__ void stage_load_row(const MatDesc& md, int64_t row, unsigned char* lds_row, uint32_t ch0) {
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
-  const uint4* src = reinterpret_cast<const uint4*>(md.W + row * md.ld);
+  const EQ_GLOBAL uint16_t* src = md.W + row * md.ld;
   bool bad = false;
   for (uint32_t ch = threadIdx.x; ch < nchunks; ch += blockDim.x) {
-    const uint4 v = load_stream128(src + ch);
+    const uint4 v = global_load_stream128(src + 8 * (size_t)ch);
     *reinterpret_cast<uint4*>(lds_row + Layout::off(ch0 + ch)) = v;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) bad = bad || nonfinite16<DT>(w[k] & 0xFFFFu) || nonfinite16<DT>(w[k] >> 16);
   }
-  if (__any(bad) && (threadIdx.x & (kWave - 1)) == 0) atomicOr(md.status, EQ_S_NONFINITE);
+  if (__any(bad) && (threadIdx.x & (kWave - 1)) == 0) global_atomic_or(md.status, EQ_S_NONFINITE);
 }
 
 // Given the mask bytes of the row's chunks (maskb[ch], LDS), counts the row's outliers,
@@ -108,11 +108,11 @@ __device__ __forceinline__ void stage_compact_row(const MatDesc& md, int64_t row
   const uint32_t total = block_sum_u32(cnt, sc->redu);
   if (threadIdx.x == 0) {
     unsigned long long b = 0;
-    if (total) b = atomicAdd(md.cursor, (unsigned long long)total);
+    if (total) b = global_atomic_add(md.cursor, (unsigned long long)total);
     const bool fits = b + total <= (unsigned long long)md.capacity;
     md.row_count[row] = total;
     md.row_stage[row] = fits ? (uint32_t)b : 0xFFFFFFFFu;
-    if (!fits) atomicOr(md.status, EQ_S_OUTLIER_OVERFLOW);
+    if (!fits) global_atomic_or(md.status, EQ_S_OUTLIER_OVERFLOW);
     sc->base = fits ? b : ~0ull;
   }
   __syncthreads();

@@ -1,0 +1,69 @@
+// Zero optimisation steps (iters = 0): outlier isolation followed by round-to-nearest at the
+// initial range (Algorithm 1 without its second step), group size 128.
+//
+// This end of the path is bound by HBM, not by arithmetic, so the kernel is organised around
+// keeping loads in flight: while a workgroup takes one batch of rows through statistics,
+// outlier compaction (eq_rowbatch.h) and code emission, the 128-bit loads of its next batch
+// are already under way into a second set of registers.  Emission is the unit-per-lane scheme
+// of eq_fused128.h (the transposition through the padded LDS slots makes both the HBM reads
+// and the code writes fully coalesced), one round per batch, nothing carried over.
+#pragma once
+
+#include "eq_fused128.h"
+
+namespace eq {
+
+constexpr int kRtnThreads = 256;
+
+// K = 16-byte chunks of a row per thread (cols <= 8 * K * 256); a batch is 16 / K rows, i.e. at
+// most 256 units, which one round of the 256 lanes emits.
+template <int DT, int K>
+__global__ __launch_bounds__(kRtnThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_rtn128(
+    const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
+  constexpr int NT = kRtnThreads;
+  constexpr int RB = 16 / K;
+  typedef BatchScratch<RB> Scratch;
+  static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
+  extern __shared__ __align__(16) unsigned char smem[];
+  Scratch* sc = reinterpret_cast<Scratch*>(smem);
+  unsigned char* pool = smem + kLdsHeader;
+  const WorkItem it = items[blockIdx.x];
+  const MatDesc md = mats[it.mat];
+  const uint32_t upr = (uint32_t)md.upr;
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int64_t row_end = (int64_t)it.row0 + it.nrows;
+
+  auto rows_at = [&](int64_t row) { return (int)max((int64_t)0, min((int64_t)RB, row_end - row)); };
+  auto finish_batch = [&](int64_t row0, int nb, const uint4 (&v)[RB][K]) {
+    stage_loaded_rows<DT, NT, RB, K, Padded128Layout>(md, kp, row0, nb, pool, 0u, sc, v);
+    const uint32_t take = (uint32_t)nb * upr;              // <= 256
+    const bool valid = tid < take;
+    unsigned char* slot = pool + (size_t)(valid ? tid : 0u) * kSlotBytes;
+    float vmin, vmax;
+    slot_min_max<DT>(slot, vmin, vmax);
+    float r0;
+    int z;
+    const bool active = init_unit(kp, vmin, vmax, r0, z);
+    const float mlo = (float)(-z) + kMagic, mhi = (float)(kp.L - z) + kMagic;
+    float s32, inv;
+    scale_of(kp, active ? r0 : kp.D, s32, inv);            // an all-zero unit keeps s = 1
+    if (valid) {
+      emit_codes_to_slot<DT>(kp, slot, inv, z, mlo, mhi);
+      const int64_t gu = row0 * (int64_t)upr + tid;
+      md.scales[gu] = s32;
+      md.zps[gu] = (unsigned char)z;
+    }
+    __syncthreads();
+    copy_wave_codes(kp, md, pool, row0 * (int64_t)upr, wave * kWave, take, lane);
+    __syncthreads();                                       // the pool is refilled by the next batch
+  };
+
+  for (int64_t row = it.row0; row < row_end; row += RB) {
+    const int nb = rows_at(row);
+    uint4 v[RB][K];
+    batch_issue_loads<NT, RB, K>(md, row, nb, v);
+    finish_batch(row, nb, v);
+  }
+}
+
+}  // namespace eq

@@ -104,6 +104,37 @@ def test_bf16_wide_exponent_span_takes_the_binary64_evaluation(G):
     assert res["excused_elems"] == 0
 
 
+@pytest.mark.parametrize("rows,cols,units_per_item", [(130, 1280, 1000), (9, 22016, 0), (24, 11008, 1500), (3, 32768, 0),
+                                                      (70, 8192, 2048), (64, 4096, 0), (33, 2048, 0), (5, 128, 0)])
+def test_no_optimisation_steps_kernel_row_shapes(rows, cols, units_per_item, monkeypatch):
+    # iters = 0, group 128: the load-pipelined kernel (batches of 16, 8, 4, 2 or 1 rows, odd and
+    # even numbers of batches per work item, a ragged last batch)
+    if units_per_item:
+        monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", str(units_per_item))
+    W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows + 3 * cols, device=DEV)
+    for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
+        res = _check(W, eqo.Params(bits=bits, group_size=128, mode=mode, iters=0), f"rtn kernel {rows}x{cols}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+    Wb = eq_inputs.gen_matrix(rows, cols, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=rows, device=DEV)
+    _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=0, n_sigma=2.0), f"rtn kernel bf16 {rows}x{cols}")
+
+
+@pytest.mark.parametrize("iters", [0, 3])
+def test_exact_rounding_ties_go_to_the_even_level(iters):
+    # scale = 2^-7 exactly (largest magnitude 7 * 2^-7), values at every half level: x / s is an
+    # exact tie for half of the elements, and Eq. 1's rounding takes them to the even level
+    k = np.arange(-14, 15, dtype=np.float64)                    # half levels -7.0, -6.5 ... 7.0
+    vals = (k / 2.0) * 2.0 ** -7
+    row = np.resize(vals, 256)
+    row[5] = 7 * 2.0 ** -7
+    W = torch.tensor(np.stack([row, -row, np.roll(row, 3)]), dtype=torch.float16, device=DEV)
+    for bits, mode in ((4, eqo.SYMMETRIC), (4, eqo.ASYMMETRIC), (3, eqo.SYMMETRIC)):
+        res = _check(W, eqo.Params(bits=bits, group_size=128, mode=mode, iters=iters, lr=0.0), f"ties T={iters}")
+        assert res["excused_elems"] == 0
+    res = _check(W, eqo.Params(bits=4, group_size=0, iters=iters, lr=0.0), f"ties per-channel T={iters}")
+    assert res["excused_elems"] == 0
+
+
 def test_bf16_and_student_t_inputs():
     W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
