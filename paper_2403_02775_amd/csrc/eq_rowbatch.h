@@ -12,11 +12,11 @@
 // column when it moves it to its final place, so the result does not depend on timing.
 //
 // Statistics (Eq. 3) take a fast path and an exact path with identical results:
-//   fast  : sum x and sum x^2 in binary32 per thread, binary64 across threads.  The outlier
+//   fast  : sum x and sum x^2, mean and sigma in binary32.  The outlier
 //           test is decided only for elements whose |x - mean| is farther than a relative
-//           1e-4 from n*sigma; the error of the fast sums is below 2.2e-5 of the threshold
-//           (<= 70 roundings of 2^-24 on sums whose terms are bounded through the guard
-//           mean^2 < variance, n >= 0.5), so those decisions equal the exact ones.
+//           1e-4 from n*sigma; the error of the fast mean and threshold is below 2.7e-5 of the
+//           threshold (<= 90 roundings of 2^-24 on quantities that are bounded through the
+//           guard mean^2 < variance, n >= 0.5), so those decisions equal the exact ones.
 //   exact : a row with an element inside that band, or that fails the guard (which also
 //           covers constant rows), is redone with the two-pass binary64 sums and decided
 //           element by element in binary64.
@@ -93,11 +93,13 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
     for (int i = 0; i < K; ++i) {
       float x[8];
       chunk_floats<DT>(v[r][i], x);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        s1 += x[k];
-        s2 = __builtin_fmaf(x[k], x[k], s2);
-      }
+      // pairwise within the chunk: short dependency chains (a dependent instruction cannot issue
+      // back to back), and fewer roundings along any path than a running sum
+      const float a01 = x[0] + x[1], a23 = x[2] + x[3], a45 = x[4] + x[5], a67 = x[6] + x[7];
+      const float q01 = __builtin_fmaf(x[1], x[1], x[0] * x[0]), q23 = __builtin_fmaf(x[3], x[3], x[2] * x[2]);
+      const float q45 = __builtin_fmaf(x[5], x[5], x[4] * x[4]), q67 = __builtin_fmaf(x[7], x[7], x[6] * x[6]);
+      s1 += (a01 + a23) + (a45 + a67);
+      s2 += (q01 + q23) + (q45 + q67);
       const uint32_t ch = (uint32_t)i * NT + tid;
       if (r < nrows && ch < nchunks)
         *reinterpret_cast<uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)) = v[r][i];
@@ -127,34 +129,35 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
 
   // ---- thresholds; one test per chunk: can any of its elements be an outlier? ----
   const double cnt = (double)md.cols;
+  const float rcnt = 1.0f / (float)md.cols;
   float mu_f[RB], thr_lo[RB], thr_hi[RB];
   uint32_t cand = 0;                      // bit r * K + i: chunk i of row r needs a look
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
-    double S1 = 0.0, S2 = 0.0;
+    float S1 = 0.0f, S2 = 0.0f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-      S1 += (double)sc->part[r][w][0];
-      S2 += (double)sc->part[r][w][1];
+      S1 += sc->part[r][w][0];
+      S2 += sc->part[r][w][1];
     }
-    double mu, sigma;
+    float mu, thr;
     bool slow;
     if (kp.scope == EQ_STAT_MATRIX) {
-      mu = md.mat_stats[0];
-      sigma = md.mat_stats[1];
+      mu = (float)md.mat_stats[0];
+      thr = (float)(kp.n * md.mat_stats[1]);
       slow = true;                        // the matrix-wide statistics are exact: decide every element exactly
     } else {
-      mu = S1 / cnt;
-      const double ms = S2 / cnt;         // mean square = variance + mean^2
-      const double var = ms - mu * mu;
+      // binary32 throughout: a dozen more roundings of 2^-24 on top of those of the sums
+      mu = S1 * rcnt;
+      const float ms = S2 * rcnt;         // mean square = variance + mean^2
+      const float var = ms - mu * mu;
       slow = !(var + var > ms) || kp.n < 0.5;   // mean^2 >= variance, a constant row, NaN; or a threshold so
                                                  // small that the error of the mean is not negligible against it
-      sigma = sqrt(fmax(var, 0.0));
+      thr = (float)kp.n * __builtin_sqrtf(fmaxf(var, 0.0f));
     }
-    const double thr = kp.n * sigma;
-    mu_f[r] = (float)mu;
-    thr_lo[r] = (float)thr * (1.0f - kBand);
-    thr_hi[r] = (float)thr * (1.0f + kBand);
+    mu_f[r] = mu;
+    thr_lo[r] = thr * (1.0f - kBand);
+    thr_hi[r] = thr * (1.0f + kBand);
     if (slow) {
       if (r < nrows) sc->slow[r] = 1u;    // benign race: every writer stores 1
     } else {
