@@ -208,7 +208,7 @@ def main():
     elems = sum(w.numel() for w in Ws)
     ms_per_step = gpu_ms / args.steps
     weight_gbs = elems * 2 / (ms_per_step * 1e-3) / 1e9
-    passes = args.iters + 2                       # T+1 evaluations (best-iterate selection) + the emitting one
+    passes = args.iters + 2 if args.iters else 1  # T+1 evaluations (best-iterate selection) + the emitting one
     lane_ops = elems * (5 * passes + 12)          # useful lane-operations: 5 per element and pass, 12 fixed
     kern_s = kern_ms * 1e-3 / args.steps          # main kernels per step (one launch per row-length class)
     alg_bytes = algorithmic_bytes(Ws, bits, n_out, args.group_size)
@@ -220,7 +220,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": alg_bytes / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
-    kernel = "quantize_units128" if args.group_size == 128 else "quantize_channels128" if args.group_size == 0 else "quantize_rows_generic"
+    kernel = "quantize_rtn128" if args.group_size == 128 and args.iters == 0 else "quantize_units128" if args.group_size == 128 else "quantize_channels128" if args.group_size == 0 else "quantize_rows_generic"
     roof["traffic"] = measured_traffic(args.workload if args.layers < 0 else None, args.iters, kernel)
     roof.update({"kernel": kernel, "launches_per_step": launches / args.steps,
                  "kernel_ms_per_step": kern_ms / args.steps, "avg_launch_ms": kern_ms / max(launches, 1),

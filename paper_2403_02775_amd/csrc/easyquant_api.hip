@@ -210,13 +210,14 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     if (p->iters == 0) {
       // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
       lc.kind = 3;
-      lc.threads = kRtnThreads;
-      const int64_t per_thread = (c / 8 + kRtnThreads - 1) / kRtnThreads;
-      lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : per_thread <= 8 ? 8 : 16;
+      lc.threads = c > 8192 ? 512 : 256;
+      const int64_t per_thread = (c / 8 + lc.threads - 1) / lc.threads;
+      lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : 8;
+      if (lc.threads == 512 && lc.chunks_per_thread < 4) lc.chunks_per_thread = 4;
       const int64_t rpb = 16 / lc.chunks_per_thread;
       lc.pool_slots = (uint32_t)(rpb * upr);
       lc.lds_bytes = (size_t)kLdsHeader + (size_t)lc.pool_slots * kSlotBytes;
-      int64_t target = std::min<int64_t>(32768, std::max<int64_t>(kRtnThreads, total_units / 4096));
+      int64_t target = std::min<int64_t>(32768, std::max<int64_t>(lc.threads, total_units / 4096));
       if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
         const long v = std::atol(ov);
         if (v > 0) target = v;
@@ -358,16 +359,16 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
                          c.lds_bytes, s, dm, di + c.first_item, k);                                             \
     };                                                                                                          \
   }
-#define EQ_RTN_VARIANT(K_)                                                                                      \
-  if (lc.chunks_per_thread == K_) {                                                                             \
-    fn = reinterpret_cast<const void*>(&quantize_rtn128<DT, K_>);                                               \
+#define EQ_RTN_VARIANT(NT_, K_)                                                                                 \
+  if (lc.threads == NT_ && lc.chunks_per_thread == K_) {                                                        \
+    fn = reinterpret_cast<const void*>(&quantize_rtn128<DT, NT_, K_>);                                          \
     launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
-      hipLaunchKernelGGL((quantize_rtn128<DT, K_>), dim3((unsigned)c.n_items), dim3(kRtnThreads), c.lds_bytes,  \
-                         s, dm, di + c.first_item, k);                                                          \
+      hipLaunchKernelGGL((quantize_rtn128<DT, NT_, K_>), dim3((unsigned)c.n_items), dim3(NT_), c.lds_bytes, s,  \
+                         dm, di + c.first_item, k);                                                             \
     };                                                                                                          \
   }
     if (lc.kind == 3) {
-      EQ_RTN_VARIANT(1) EQ_RTN_VARIANT(2) EQ_RTN_VARIANT(4) EQ_RTN_VARIANT(8) EQ_RTN_VARIANT(16)
+      EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
     } else if (lc.kind == 2) {
       EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
     } else {

@@ -13,14 +13,12 @@
 
 namespace eq {
 
-constexpr int kRtnThreads = 256;
-
-// K = 16-byte chunks of a row per thread (cols <= 8 * K * 256); a batch is 16 / K rows, i.e. at
-// most 256 units, which one round of the 256 lanes emits.
-template <int DT, int K>
-__global__ __launch_bounds__(kRtnThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_rtn128(
+// NT threads (256, two workgroups per compute unit; 512 for rows longer than 8192, one per compute
+// unit); K = 16-byte chunks of a row per thread (cols <= 8 * K * NT); a batch is 16 / K rows,
+// i.e. at most NT units, which one round of the NT lanes emits.
+template <int DT, int NT, int K>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_rtn128(
     const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
-  constexpr int NT = kRtnThreads;
   constexpr int RB = 16 / K;
   typedef BatchScratch<RB> Scratch;
   static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
@@ -36,7 +34,7 @@ __global__ __launch_bounds__(kRtnThreads) __attribute__((amdgpu_waves_per_eu(2, 
   auto rows_at = [&](int64_t row) { return (int)max((int64_t)0, min((int64_t)RB, row_end - row)); };
   auto finish_batch = [&](int64_t row0, int nb, const uint4 (&v)[RB][K]) {
     stage_loaded_rows<DT, NT, RB, K, Padded128Layout>(md, kp, row0, nb, pool, 0u, sc, v);
-    const uint32_t take = (uint32_t)nb * upr;              // <= 256
+    const uint32_t take = (uint32_t)nb * upr;              // <= NT
     const bool valid = tid < take;
     unsigned char* slot = pool + (size_t)(valid ? tid : 0u) * kSlotBytes;
     float vmin, vmax;
