@@ -132,7 +132,10 @@ EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* row
 /* Algorithm 1, "Dequantize" (Eq. 4): W_out[i][j] = round_to_dtype(scale * (code - zero_point))
  * for normal values, the stored raw pattern for outliers.  W_out DEVICE, rows x cols of
  * p->dtype with row stride ld_out (>= cols, % 8 == 0, 16-byte aligned).  Only dtype, bits
- * and group_size of p are read.  q->status is not touched. */
+ * and group_size of p are read.  q->status is not touched.  The outlier list must be in the
+ * form eq_quantize_* writes it: columns ascending within each row (an entry out of order, or
+ * with a column >= cols, ends the row's list: it and the entries after it are not applied;
+ * nothing outside W_out is ever written).  q->out_col / q->out_val NULL: no outliers. */
 EQ_API int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p,
                   void* W_out, int64_t ld_out, void* hip_stream);
 

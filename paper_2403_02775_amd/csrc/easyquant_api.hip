@@ -572,28 +572,22 @@ int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_para
   if (!W_out || !q->codes || !q->scales || !q->zero_points || !q->out_row_ptr) return EQ_E_NULL;
   if (((uintptr_t)W_out & 15) || ((uintptr_t)q->codes & 3)) return EQ_E_ALIGN;
   DeqDesc d;
-  d.codes = q->codes; d.scales = q->scales; d.zps = q->zero_points;
-  d.out_row_ptr = q->out_row_ptr; d.out_col = q->out_col; d.out_val = q->out_val;
-  d.W = static_cast<uint16_t*>(W_out);
+  const bool sparse = q->out_col && q->out_val;
+  d.codes = dev(q->codes); d.scales = dev(q->scales); d.zps = dev(q->zero_points);
+  d.out_row_ptr = dev(q->out_row_ptr);
+  d.out_col = sparse ? dev(q->out_col) : nullptr;
+  d.out_val = sparse ? dev(q->out_val) : nullptr;
+  d.W = dev(static_cast<uint16_t*>(W_out));
   d.ld = ld_out; d.rows = (int32_t)rows; d.cols = (int32_t)cols;
   d.G = p->group_size ? p->group_size : (int32_t)cols;
   d.upr = d.cols / d.G;
   d.words_per_row = (int32_t)eq_code_words_per_row(cols, p->bits);
   d.bits = p->bits;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const unsigned chunk_blocks = (unsigned)((cols / 8 + kThreads - 1) / kThreads);
-  if (chunk_blocks > 65535u) return EQ_E_UNSUPPORTED;
   {
     ScopedKernelTimer tm(st);
-    if (p->dtype == EQ_F16)
-      hipLaunchKernelGGL(dequantize_dense<EQ_F16>, dim3((unsigned)rows, chunk_blocks), dim3(kThreads), 0, st, d);
-    else
-      hipLaunchKernelGGL(dequantize_dense<EQ_BF16>, dim3((unsigned)rows, chunk_blocks), dim3(kThreads), 0, st, d);
-  }
-  EQ_HIP(hipGetLastError());
-  if (q->out_col && q->out_val) {
-    ScopedKernelTimer tm(st);
-    hipLaunchKernelGGL(scatter_outliers, dim3((unsigned)((rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, st, d);
+    if (p->dtype == EQ_F16) hipLaunchKernelGGL(dequantize_rows<EQ_F16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
+    else hipLaunchKernelGGL(dequantize_rows<EQ_BF16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
   }
   EQ_HIP(hipGetLastError());
   return EQ_OK;

@@ -124,31 +124,25 @@ __global__ __launch_bounds__(kThreads) void matrix_finish_sums(const MatDesc* __
 
 // ---- Eq. 4 ---------------------------------------------------------------------------
 struct DeqDesc {
-  const uint32_t* codes;
-  const float* scales;
-  const uint8_t* zps;
-  const uint32_t* out_row_ptr;
-  const uint32_t* out_col;
-  const uint16_t* out_val;
-  uint16_t* W;
+  const EQ_GLOBAL uint32_t* codes;
+  const EQ_GLOBAL float* scales;
+  const EQ_GLOBAL uint8_t* zps;
+  const EQ_GLOBAL uint32_t* out_row_ptr;
+  const EQ_GLOBAL uint32_t* out_col;      // null: no outlier list
+  const EQ_GLOBAL uint16_t* out_val;
+  EQ_GLOBAL uint16_t* W;
   int64_t ld;
   int32_t rows, cols, upr, G, words_per_row, bits;
 };
 
-// Dense part of Eq. 4: scale * (code - zero_point) for every element, outliers included (their
-// slot holds the zero level, so they come out as 0 and are overwritten by scatter_outliers).
-// One thread per 8 consecutive elements of a row: 8 codes are `bits` whole bytes of the row's
-// bit stream, the 8 results are one 128-bit store; consecutive threads take consecutive
-// chunks, so code loads and stores are coalesced.  blockIdx.x = row, blockIdx.y = block of chunks.
+// Eq. 4 for one chunk of 8 consecutive elements of a row: scale * (code - zero_point), outliers
+// included (their slot holds the zero level, so they come out as 0).  8 codes are `bits` whole
+// bytes of the row's bit stream, which sit in at most three aligned words (the row is padded to
+// whole words).
 template <int DT>
-__global__ __launch_bounds__(kThreads) void dequantize_dense(DeqDesc d) {
-  const int64_t row = blockIdx.x;
-  const uint32_t ch = blockIdx.y * kThreads + threadIdx.x;        // chunk of 8 elements
-  if (ch * 8u >= (uint32_t)d.cols) return;
-  const unsigned char* stream = reinterpret_cast<const unsigned char*>(d.codes + row * (int64_t)d.words_per_row);
+__device__ __forceinline__ uint4 dequantize_chunk(const DeqDesc& d, int64_t row, uint32_t ch) {
   const uint32_t byte0 = ch * (uint32_t)d.bits;
-  // the chunk's bits sit in at most three aligned words; the row is padded to whole words
-  const uint32_t* wp = reinterpret_cast<const uint32_t*>(stream) + (byte0 >> 2);
+  const EQ_GLOBAL uint32_t* wp = d.codes + row * (int64_t)d.words_per_row + (byte0 >> 2);
   const uint32_t last_word = (uint32_t)d.words_per_row - 1u;
   const uint32_t w0 = wp[0];
   const uint32_t w1 = (byte0 >> 2) + 1u <= last_word ? wp[1] : 0u;
@@ -171,22 +165,53 @@ __global__ __launch_bounds__(kThreads) void dequantize_dense(DeqDesc d) {
     asm volatile("" : "+v"(prod));
     h[k] = narrow16<DT>(prod);
   }
-  uint4 o;
-  o.x = h[0] | (h[1] << 16); o.y = h[2] | (h[3] << 16); o.z = h[4] | (h[5] << 16); o.w = h[6] | (h[7] << 16);
-  *reinterpret_cast<uint4*>(d.W + row * d.ld + ch * 8u) = o;
+  return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
 }
 
-// Sparse part of Eq. 4: the stored raw values over the dense result.  One wavefront per row.
-// Runs after dequantize_dense on the same stream.
-__global__ __launch_bounds__(kThreads) void scatter_outliers(DeqDesc d) {
-  const int64_t row = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
-  if (row >= d.rows) return;
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t b = d.out_row_ptr[row], e = d.out_row_ptr[row + 1];
-  uint16_t* orow = d.W + row * d.ld;
-  for (uint32_t i = b + lane; i < e; i += kWave) {
-    const uint32_t col = d.out_col[i];
-    if (col < (uint32_t)d.cols) orow[col] = d.out_val[i];
+constexpr int kDeqChunks = 2;      // chunks per thread and segment: a segment is 2 * 256 * 8 = 4096 columns
+
+// Eq. 4, dense and sparse part in one pass over the output: one workgroup per row walks the
+// row in segments.  A segment's dense results go to LDS, the row's outliers that fall into
+// the segment (the list is sorted by column, so they are the next entries of the row's run)
+// overwrite their 16-bit slots there, and the segment leaves with coalesced 128-bit stores.
+// Each output byte is written to HBM once; there is no read-modify-write of cache lines.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
+  __shared__ uint4 seg[kDeqChunks * kThreads];
+  const int64_t row = blockIdx.x;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t nchunks = (uint32_t)d.cols >> 3;
+  uint32_t next = 0, end = 0;                  // the row's outliers not yet written
+  if (d.out_col) {
+    next = d.out_row_ptr[row];
+    end = d.out_row_ptr[row + 1];
+  }
+  EQ_GLOBAL uint16_t* orow = d.W + row * d.ld;
+  for (uint32_t ch0 = 0; ch0 < nchunks; ch0 += kDeqChunks * kThreads) {
+#pragma unroll
+    for (int j = 0; j < kDeqChunks; ++j) {
+      const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
+      if (ch < nchunks) seg[j * kThreads + tid] = dequantize_chunk<DT>(d, row, ch);
+    }
+    const uint32_t col0 = ch0 * 8u, col1 = min(col0 + kDeqChunks * kThreads * 8u, (uint32_t)d.cols);
+    uint32_t taken;
+    do {                                       // uniform: every thread sees the same counts
+      __syncthreads();                         // dense results (or the previous patches) are in place
+      const uint32_t i = next + tid;
+      bool mine = false;
+      if (i < end) {
+        const uint32_t col = d.out_col[i];
+        mine = col >= col0 && col < col1;
+        if (mine) reinterpret_cast<uint16_t*>(seg)[col - col0] = d.out_val[i];
+      }
+      taken = (uint32_t)__syncthreads_count(mine);
+      next += taken;
+    } while (taken == (uint32_t)kThreads);     // all of this batch fell into the segment: there may be more
+#pragma unroll
+    for (int j = 0; j < kDeqChunks; ++j) {     // every thread reads back the entries it wrote itself
+      const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
+      if (ch < nchunks) global_store128(orow + 8 * (size_t)ch, seg[j * kThreads + tid]);
+    }
   }
 }
 
