@@ -111,6 +111,12 @@ __device__ __forceinline__ uint4 buffer_load_stream128(BufferRsrc rs, uint32_t b
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+__device__ __forceinline__ void global_store_stream128(EQ_GLOBAL void* p, const uint4 v) {   // written once, not re-read
+  u32x4_t t;
+  t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<EQ_GLOBAL u32x4_t*>(p));
+}
+
 // ---- 16-bit formats -------------------------------------------------------------------
 template <int DT>
 __device__ __forceinline__ float widen16(uint32_t h) {

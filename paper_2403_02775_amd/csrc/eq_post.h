@@ -168,7 +168,7 @@ __device__ __forceinline__ uint4 dequantize_chunk(const DeqDesc& d, int64_t row,
   return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
 }
 
-constexpr int kDeqChunks = 2;      // chunks per thread and segment: a segment is 2 * 256 * 8 = 4096 columns
+constexpr int kDeqChunks = 4;      // chunks per thread and segment: a segment is 4 * 256 * 8 = 8192 columns
 
 // Eq. 4, dense and sparse part in one pass over the output: one workgroup per row walks the
 // row in segments.  A segment's dense results go to LDS, the row's outliers that fall into
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
 #pragma unroll
     for (int j = 0; j < kDeqChunks; ++j) {     // every thread reads back the entries it wrote itself
       const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
-      if (ch < nchunks) global_store128(orow + 8 * (size_t)ch, seg[j * kThreads + tid]);
+      if (ch < nchunks) global_store_stream128(orow + 8 * (size_t)ch, seg[j * kThreads + tid]);
     }
   }
 }
