@@ -9,8 +9,8 @@
  *      reconstruction error ||Q[x] - x||^2 with respect to the range (Eq. 2, Sec. 4.2);
  *   3. quantize the normal values at that range (Eq. 1);
  *   4. dequantize as  Mask * W + (1 - Mask) * Q[W]  (Eq. 4).
- * "We store the index and value for all outliers together with the quantized
- * normal values" (Sec. 5, Implementation) is the output format below.
+ * The output format below follows Sec. 5, Implementation: the quantized normal values
+ * plus the position and the original value of every outlier.
  *
  * Conventions that hold for every entry point
  * -------------------------------------------
@@ -40,8 +40,8 @@ extern "C" {
 /* exported symbol (the library is built with hidden visibility by default) */
 #define EQ_API __attribute__((visibility("default")))
 
-/* element type of W: the paper keeps outliers "in full precision (fp32/fp16/bf16)" (Fig. 1);
- * this library takes the two 16-bit formats. */
+/* element type of W: outliers keep their original floating-point type (Fig. 1); this library
+ * takes the two 16-bit formats. */
 enum { EQ_F16 = 0, EQ_BF16 = 1 };
 /* EQ_SYMMETRIC is the paper's setting (Sec. 5, Setup).  EQ_ASYMMETRIC is an extension:
  * an integer zero-point fixed from min/max at initialisation, only the range optimised. */
@@ -49,8 +49,8 @@ enum { EQ_SYMMETRIC = 0, EQ_ASYMMETRIC = 1 };
 /* scope of mean / sigma in Eq. 3: one row (default), one unit, or the whole matrix (Eq. 3 as printed). */
 enum { EQ_STAT_ROW = 0, EQ_STAT_GROUP = 1, EQ_STAT_MATRIX = 2 };
 /* which iterate of the optimisation is returned: the best of the trajectory (step 0
- * included, so never worse than min/max scaling), or the last one ("we choose the
- * quantization ranges from step 100 / 500", Sec. 5, Setup). */
+ * included, so never worse than min/max scaling), or the last one (the ranges of step 100 /
+ * 500, as in Sec. 5, Setup). */
 enum { EQ_SELECT_BEST = 0, EQ_SELECT_LAST = 1 };
 
 /* return codes */
@@ -117,13 +117,23 @@ typedef struct eq_qmatrix {
  *   workspace  DEVICE scratch, 256-byte aligned, at least eq_workspace_bytes() bytes;
  *          contents are undefined afterwards; must not be shared by calls that overlap.
  * The outlier list comes out sorted by (row, column) whatever the execution order.
- * Same inputs give bit-identical outputs on every run. */
+ * Same inputs give bit-identical outputs on every run.
+ *
+ * Which kernel serves a matrix is decided from its shape and p alone (the results do not
+ * depend on the choice): group_size 128 with row or matrix statistics and cols <= 32768 runs
+ * one unit per lane (without optimisation steps, iters == 0, a load-pipelined variant of it);
+ * one range per row with cols a multiple of 128 in 2048..32768 spreads the row over
+ * cols / 128 lanes; everything else goes to a general kernel (one workgroup per row, one
+ * wavefront per unit).  Two environment variables, read at every call, exist for tests and
+ * measurements: EASYQUANT_UNITS_PER_ITEM=<n> sets the number of units a workgroup walks
+ * through (changes only how the work is cut up), EASYQUANT_FORCE_GENERAL=1 sends every
+ * matrix to the general kernel. */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,
                        const eq_params* p, const eq_qmatrix* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* The same for n independent matrices in ONE pass over the GPU ("each weight can be
- * quantized in parallel", Sec. 5, Implementation): W, rows, cols, ld, outs are HOST
+/* The same for n independent matrices in ONE pass over the GPU (weights are independent of one
+ * another, Sec. 5, Implementation): W, rows, cols, ld, outs are HOST
  * arrays of length n; all matrices share p.  n == 0 is a no-op. */
 EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols,
                       const int64_t* ld, const eq_params* p, const eq_qmatrix* outs,

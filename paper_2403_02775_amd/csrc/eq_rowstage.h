@@ -4,7 +4,7 @@
 // computes the row's mean and sigma, builds the outlier mask of Eq. 3, compacts the
 // outliers in column order into the staging area of the workspace, and replaces them by 0
 // in the LDS copy, so that the range optimisation that follows only sees normal values
-// (Sec. 4.2: "for the normal elements, we optimize ...").
+// (Sec. 4.2: only the normal elements are optimised).
 #pragma once
 
 #include "eq_common.h"
