@@ -19,6 +19,8 @@
 // by a plain binary64 loop instead; the result is the same exact sum either way.
 #pragma once
 
+#include <type_traits>
+
 #include "eq_common.h"
 #include "eq_rowbatch.h"
 #include "eq_rowstage.h"
@@ -296,6 +298,41 @@ __device__ __forceinline__ void copy_wave_codes(const KParams& kp, const MatDesc
   }
 }
 
+// A bf16 unit as fp16: x' = x * 2^k is exactly representable in fp16 for every x of the unit
+// unless the unit spans more than ~2^38 in magnitude (k puts the largest magnitude just below
+// 2^15; fp16 then reaches down to multiples of 2^-24).  Levels and sums are unchanged when the
+// reciprocal scale is multiplied by 2^-k (both exact), and the fp16 forms of the inner loop are
+// a quarter cheaper: the widening folds into the multiply-add, which bf16 has no instruction for.
+__device__ __forceinline__ bool slot_fits_f16(const unsigned char* slot, int k) {
+  uint32_t bad = 0;
+#pragma unroll
+  for (int ch = 0; ch < 16; ++ch) {
+    const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float y0 = ldexpf(widen16<EQ_BF16>(w[j] & 0xFFFFu), k), y1 = ldexpf(widen16<EQ_BF16>(w[j] >> 16), k);
+      bad |= (__half2float(__float2half_rn(y0)) != y0 ? 1u : 0u) | (__half2float(__float2half_rn(y1)) != y1 ? 1u : 0u);
+    }
+    asm volatile("" : "+v"(bad));       // keep the running flag: no long-lived temporaries
+  }
+  return bad == 0;
+}
+__device__ __forceinline__ void slot_bf16_to_f16(unsigned char* slot, int k) {
+#pragma unroll
+  for (int ch = 0; ch < 16; ++ch) {
+    const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float y0 = ldexpf(widen16<EQ_BF16>(w[j] & 0xFFFFu), k), y1 = ldexpf(widen16<EQ_BF16>(w[j] >> 16), k);
+      o[j] = (uint32_t)__half_as_ushort(__float2half_rn(y0)) | ((uint32_t)__half_as_ushort(__float2half_rn(y1)) << 16);
+    }
+    *reinterpret_cast<uint4*>(slot + ch * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
 // Adam on the range of one unit (per lane); `ev(inv, A, B)` evaluates the exact sums.
 template <class Eval>
 __device__ __forceinline__ float optimise_range(const KParams& kp, float r0, Eval&& ev) {
@@ -389,33 +426,48 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       int E = 0;
       (void)frexpf(fmaxf(-vmin, vmax), &E);                  // max |x| < 2^E
       const int q = 30 - E;
-      uint32_t H[kPairs], Lo[kPairs];
-      uint32_t frac_bits = 0;          // OR of the bit patterns of y - trunc(y): zero iff every y is an integer
-      // every fp16 value is a multiple of 2^-24, so q >= 24 needs no test (wavefront-uniform branch)
-      const bool need_test = !(DT == EQ_F16 && __all(q >= 24));
-      if (need_test) build_planes<DT, true>(slot, q, H, Lo, frac_bits);
-      else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
-      const bool exact = (frac_bits << 1) == 0;
+      // What follows works on the slot either in the input type or, for bf16, in the fp16 form
+      // described at slot_fits_f16 (DX, with k = shift): planes, optimisation, emission.
+      auto rest = [&](auto dx, const int shift) {
+        constexpr int DX = decltype(dx)::value;
+        const float unshift = ldexpf(1.0f, -shift);          // exact power of two
+        uint32_t H[kPairs], Lo[kPairs];
+        uint32_t frac_bits = 0;          // OR of the bit patterns of y - trunc(y): zero iff every y is an integer
+        // every fp16 value is a multiple of 2^-24, so an exponent >= 24 needs no test (wavefront-uniform branch)
+        const bool need_test = !(DX == EQ_F16 && __all(q - shift >= 24));
+        if (need_test) build_planes<DX, true>(slot, q - shift, H, Lo, frac_bits);
+        else build_planes<DX, false>(slot, q - shift, H, Lo, frac_bits);
+        const bool exact = (frac_bits << 1) == 0;
 
-      float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
-        eval_regs<DT>(slot, H, Lo, inv, mlo, mhi, q, A, B);
-      });
-      if (!exact) {
-        r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
-          eval_slot<DT>(slot, inv, clo, chi, A, B);
+        float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
+          eval_regs<DX>(slot, H, Lo, inv * unshift, mlo, mhi, q, A, B);
         });
-      }
+        if (!exact) {
+          r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
+            eval_slot<DX>(slot, inv * unshift, clo, chi, A, B);
+            B = ldexp(B, -shift);
+          });
+        }
 
-      // ---- emit (Algorithm 1, third step) ----
-      float s32, inv;
-      scale_of(kp, r_sel, s32, inv);
-      __syncthreads();              // every lane has finished reading slots that are not its own
-      if (valid) {
-        emit_codes_to_slot<DT>(kp, slot, inv, z, mlo, mhi);
-        const int64_t gu = unit_base + slot_i;
-        md.scales[gu] = s32;
-        md.zps[gu] = (unsigned char)z;
+        // ---- emit (Algorithm 1, third step) ----
+        float s32, inv;
+        scale_of(kp, r_sel, s32, inv);
+        __syncthreads();              // every lane has finished reading slots that are not its own
+        if (valid) {
+          emit_codes_to_slot<DX>(kp, slot, inv * unshift, z, mlo, mhi);
+          const int64_t gu = unit_base + slot_i;
+          md.scales[gu] = s32;
+          md.zps[gu] = (unsigned char)z;
+        }
+      };
+      bool as_f16 = false;
+      const int shift = 15 - E;
+      if (DT == EQ_BF16) {
+        as_f16 = __all(!valid || slot_fits_f16(slot, shift));
+        if (as_f16 && valid) slot_bf16_to_f16(slot, shift);
       }
+      if (DT == EQ_BF16 && as_f16) rest(std::integral_constant<int, EQ_F16>{}, shift);
+      else rest(std::integral_constant<int, DT>{}, 0);
       __syncthreads();
       copy_wave_codes(kp, md, pool, unit_base, base + wave * kWave, take, lane);
     }
