@@ -189,7 +189,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       lc.pool_slots = kChanThreads;
       lc.lds_bytes = (size_t)kChanHeader + (size_t)kChanThreads * kSlotBytes;
       const int64_t rpr = std::min<int64_t>(kChanThreads / upr, kChanMaxRows);
-      int64_t target = std::min<int64_t>(16384, std::max<int64_t>(kChanThreads, total_units / 4096));
+      int64_t target = std::min<int64_t>(8192, std::max<int64_t>(kChanThreads, total_units / 16384));
       if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
         const long v = std::atol(ov);
         if (v > 0) target = v;
@@ -260,9 +260,10 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     lc.lds_bytes = fixed + (size_t)lc.pool_slots * kSlotBytes;
     const int64_t g = std::gcd(upr, nt);
     // rows per work item: enough units to amortise the partly filled last round of an item,
-    // few enough that the grid has several items per compute unit; a multiple of the period
-    // after which rows fill whole rounds when that fits
-    int64_t target = std::min<int64_t>(16384, std::max<int64_t>(nt, total_units / 4096));
+    // few enough that the grid has dozens of items per compute unit (the last items of a launch
+    // run on a partly idle chip); a multiple of the period after which rows fill whole rounds
+    // when that fits
+    int64_t target = std::min<int64_t>(8192, std::max<int64_t>(nt, total_units / 16384));
     if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {   // tuning / test override
       const long v = std::atol(ov);
       if (v > 0) target = v;

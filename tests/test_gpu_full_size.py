@@ -67,8 +67,6 @@ def _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix, seed, what):
     checked = 0
     for cols, group in by_cols.items():
         print(f"[full-size] {what}: cols={cols}, {sum(len(pk) for _, pk in group)} sampled rows", flush=True)
-        G = p.group_size
-        upr = cols // G
         raws, got_u, got_s, got_z, got_out = [], [], [], [], []
         for k, pick in group:
             W, o = Ws[k], outs[k]
@@ -119,12 +117,18 @@ def test_config4_llama7b_bf16_whole_model():
 
 
 def test_config5_llama65b_whole_model():
+    """The benchmark's workload, and on the same resident weights the two secondary benchmark
+    configurations: one range per output channel, and no optimisation steps."""
     Ws, names, bits, dt = bench.build_workload("llama65b_f16_w4g128", -1, DEV)
     assert len(Ws) == 560 and sum(w.numel() for w in Ws) == 64760053760
-    p = eqo.Params(bits=4, group_size=128, iters=100)
-    outs = _quantize_all(Ws, p)
-    frac = _global_properties(Ws, outs, p, "c5")
-    n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=2, seed=5, what="c5")
-    print(f"c5: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
-    del Ws, outs
+    for what, p in (("c5", eqo.Params(bits=4, group_size=128, iters=100)),
+                    ("c5 per channel", eqo.Params(bits=4, group_size=0, iters=100)),
+                    ("c5 T=0", eqo.Params(bits=4, group_size=128, iters=0))):
+        outs = _quantize_all(Ws, p)
+        frac = _global_properties(Ws, outs, p, what)
+        n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=2 if p.group_size else 1, seed=5, what=what)
+        print(f"{what}: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
+        del outs
+        torch.cuda.empty_cache()
+    del Ws
     torch.cuda.empty_cache()
