@@ -269,7 +269,10 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       if (v > 0) target = v;
     }
     const int64_t period = nt / g;
-    int64_t rpi = std::max<int64_t>(1, target / upr);
+    // as many rows as fill a whole number of rounds as nearly as possible from below: the last
+    // round of an item runs with the lanes that are left
+    const int64_t rounds = std::max<int64_t>(1, (target + nt / 2) / nt);
+    int64_t rpi = std::max<int64_t>(1, rounds * nt / upr);
     if (rpi >= period) rpi -= rpi % period;
     lc.first_item = pl.work.size();
     for (size_t j = k; j < e; ++j) {

@@ -37,7 +37,8 @@ struct RowAcc {
 struct ChanScratch {
   RowAcc acc[kChanMaxRows];
   uint32_t inexact;                  // some row of the round cannot use the fixed-point form
-  uint32_t pad_[3];
+  uint32_t keep_bf16;                // some segment of the round has no exact fp16 form (slot_fits_f16)
+  uint32_t pad_[2];
   double part[kChanThreads];         // binary64 shares of the lanes (slow path only)
 };
 static_assert(kChanScratchOff + sizeof(ChanScratch) <= kChanHeader, "LDS header too small");
@@ -86,7 +87,10 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       z0.xc[0] = z0.xc[1] = z0.xc[2] = 0;
       cs->acc[tid] = z0;
     }
-    if (tid == 0) cs->inexact = 0;
+    if (tid == 0) {
+      cs->inexact = 0;
+      cs->keep_bf16 = 0;
+    }
     for (uint32_t b = 0; b < nr; b += RB)       // ends with a barrier, which also publishes the clears above
       stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, row0 + b, (int)min((uint32_t)RB, nr - b), pool, b * segs * 16u, sc);
 
@@ -114,118 +118,136 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
     int E = 0;
     (void)frexpf(fmaxf(-vmin, vmax), &E);
     const int q = 30 - E;
-    uint32_t H[kPairs], Lo[kPairs];
-    uint32_t frac_bits = 0;
-    const bool need_test = !(DT == EQ_F16 && __all(q >= 24));
-    if (need_test) build_planes<DT, true>(slot, q, H, Lo, frac_bits);
-    else build_planes<DT, false>(slot, q, H, Lo, frac_bits);
-    if (valid && (frac_bits << 1) != 0) cs->inexact = 1u;      // benign race: every writer stores 1
+    // bf16 rows take the fp16 form of their values when every segment of the round has one
+    // (see slot_fits_f16; the shift comes from the row's largest magnitude).  The choice is
+    // uniform over the workgroup because the code below synchronises.
+    const int shift_f16 = 15 - E;
+    bool as_f16 = false;
+    if (DT == EQ_BF16) {
+      if (valid && !slot_fits_f16(slot, shift_f16)) cs->keep_bf16 = 1u;     // benign race: every writer stores 1
+      __syncthreads();
+      as_f16 = cs->keep_bf16 == 0;
+      if (as_f16 && valid) slot_bf16_to_f16(slot, shift_f16);
+    }
+    auto rest = [&](auto dx, const int shift) {
+      constexpr int DX = decltype(dx)::value;
+      const float unshift = ldexpf(1.0f, -shift);            // exact power of two
+      uint32_t H[kPairs], Lo[kPairs];
+      uint32_t frac_bits = 0;
+      const bool need_test = !(DX == EQ_F16 && __all(q - shift >= 24));
+      if (need_test) build_planes<DX, true>(slot, q - shift, H, Lo, frac_bits);
+      else build_planes<DX, false>(slot, q - shift, H, Lo, frac_bits);
+      if (valid && (frac_bits << 1) != 0) cs->inexact = 1u;      // benign race: every writer stores 1
 
-    // How the lanes of a row combine their shares (all three choices give the same exact sums):
-    //  * a row that lies inside one wavefront in an aligned group of 16, 32 or 64 lanes needs no
-    //    LDS and no barrier: group sums by lane shifts, then every lane fetches its group's sums;
-    //  * otherwise the shares go to the row's LDS accumulators, one barrier per evaluation;
-    //    a wavefront whose 32-lane halves each hold lanes of one row only adds the two half sums
-    //    instead of 64 single shares (64 atomics on one address serialise).
-    // The 32-bit group sums need |level| <= 15, i.e. at most 4 bits.
-    const bool small_levels = kp.bits <= 4;
-    const bool in_wave = small_levels && (segs == 16u || segs == 32u || segs == 64u);     // uniform over the grid
-    const uint32_t half_row = (uint32_t)__shfl((int)my_row, (int)(lane & 32u));
-    const bool half_valid = __shfl((int)valid, (int)(lane & 32u)) != 0;
-    const bool halves_uniform = small_levels && __all(!valid || my_row == half_row);      // uniform over the wavefront
-    RowAcc* ha = &cs->acc[half_valid ? half_row : 0u];
+      // How the lanes of a row combine their shares (all three choices give the same exact sums):
+      //  * a row that lies inside one wavefront in an aligned group of 16, 32 or 64 lanes needs no
+      //    LDS and no barrier: group sums by lane shifts, then every lane fetches its group's sums;
+      //  * otherwise the shares go to the row's LDS accumulators, one barrier per evaluation;
+      //    a wavefront whose 32-lane halves each hold lanes of one row only adds the two half sums
+      //    instead of 64 single shares (64 atomics on one address serialise).
+      // The 32-bit group sums need |level| <= 15, i.e. at most 4 bits.
+      const bool small_levels = kp.bits <= 4;
+      const bool in_wave = small_levels && (segs == 16u || segs == 32u || segs == 64u);     // uniform over the grid
+      const uint32_t half_row = (uint32_t)__shfl((int)my_row, (int)(lane & 32u));
+      const bool half_valid = __shfl((int)valid, (int)(lane & 32u)) != 0;
+      const bool halves_uniform = small_levels && __all(!valid || my_row == half_row);      // uniform over the wavefront
+      RowAcc* ha = &cs->acc[half_valid ? half_row : 0u];
 
-    uint32_t pass = 0;                           // evaluations so far in this round (selects the accumulator set)
-    float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
-      int cc, hc, lc;
-      eval_sums<DT>(slot, H, Lo, inv, mlo, mhi, cc, hc, lc);
-      if (in_wave) {
-        if (!valid) cc = hc = lc = 0;
-        int tc, th, tl;
-        long long xq;
-        if (segs == 16u) {
-          cc = group_sum_dpp<false>(cc);
-          hc = group_sum_dpp<false>(hc);
-          lc = group_sum_dpp<false>(lc);
-          const int src = (int)(lane | 15u);
-          tc = __shfl(cc, src);
-          th = __shfl(hc, src);
-          tl = __shfl(lc, src);
-          xq = (long long)th * 65536 + (long long)tl;
-        } else {
+      uint32_t pass = 0;                           // evaluations so far in this round (selects the accumulator set)
+      float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
+        int cc, hc, lc;
+        eval_sums<DX>(slot, H, Lo, inv * unshift, mlo, mhi, cc, hc, lc);
+        if (in_wave) {
+          if (!valid) cc = hc = lc = 0;
+          int tc, th, tl;
+          long long xq;
+          if (segs == 16u) {
+            cc = group_sum_dpp<false>(cc);
+            hc = group_sum_dpp<false>(hc);
+            lc = group_sum_dpp<false>(lc);
+            const int src = (int)(lane | 15u);
+            tc = __shfl(cc, src);
+            th = __shfl(hc, src);
+            tl = __shfl(lc, src);
+            xq = (long long)th * 65536 + (long long)tl;
+          } else {
+            cc = group_sum_dpp<true>(cc);
+            hc = group_sum_dpp<true>(hc);
+            lc = group_sum_dpp<true>(lc);
+            const int c0 = __builtin_amdgcn_readlane(cc, 31), c1 = __builtin_amdgcn_readlane(cc, 63);
+            const long long x0 = (long long)__builtin_amdgcn_readlane(hc, 31) * 65536 + (long long)__builtin_amdgcn_readlane(lc, 31);
+            const long long x1 = (long long)__builtin_amdgcn_readlane(hc, 63) * 65536 + (long long)__builtin_amdgcn_readlane(lc, 63);
+            if (segs == 64u) {
+              tc = c0 + c1;
+              xq = x0 + x1;
+            } else {
+              tc = lane < 32u ? c0 : c1;
+              xq = lane < 32u ? x0 : x1;
+            }
+          }
+          A = (double)tc;
+          B = ldexp((double)xq, -q);
+          return;
+        }
+        const uint32_t set = pass % 3u;
+        if (halves_uniform) {
+          if (!valid) cc = hc = lc = 0;
           cc = group_sum_dpp<true>(cc);
           hc = group_sum_dpp<true>(hc);
           lc = group_sum_dpp<true>(lc);
-          const int c0 = __builtin_amdgcn_readlane(cc, 31), c1 = __builtin_amdgcn_readlane(cc, 63);
-          const long long x0 = (long long)__builtin_amdgcn_readlane(hc, 31) * 65536 + (long long)__builtin_amdgcn_readlane(lc, 31);
-          const long long x1 = (long long)__builtin_amdgcn_readlane(hc, 63) * 65536 + (long long)__builtin_amdgcn_readlane(lc, 63);
-          if (segs == 64u) {
-            tc = c0 + c1;
-            xq = x0 + x1;
-          } else {
-            tc = lane < 32u ? c0 : c1;
-            xq = lane < 32u ? x0 : x1;
+          if ((lane & 31u) == 31u && half_valid) {
+            atomicAdd(&ha->cc[set], (uint32_t)cc);
+            atomicAdd(&ha->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
           }
+        } else if (valid) {
+          atomicAdd(&ra->cc[set], (uint32_t)cc);
+          atomicAdd(&ra->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
         }
-        A = (double)tc;
-        B = ldexp((double)xq, -q);
-        return;
-      }
-      const uint32_t set = pass % 3u;
-      if (halves_uniform) {
-        if (!valid) cc = hc = lc = 0;
-        cc = group_sum_dpp<true>(cc);
-        hc = group_sum_dpp<true>(hc);
-        lc = group_sum_dpp<true>(lc);
-        if ((lane & 31u) == 31u && half_valid) {
-          atomicAdd(&ha->cc[set], (uint32_t)cc);
-          atomicAdd(&ha->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
-        }
-      } else if (valid) {
-        atomicAdd(&ra->cc[set], (uint32_t)cc);
-        atomicAdd(&ra->xc[set], (unsigned long long)((long long)hc * 65536 + (long long)lc));
-      }
-      __syncthreads();
-      A = (double)ra->cc[set];
-      B = ldexp((double)(long long)ra->xc[set], -q);            // the integer is exact; one rounding at most
-      if (valid && seg == 0) {
-        const uint32_t clr = (pass + 2u) % 3u;
-        ra->cc[clr] = 0;
-        ra->xc[clr] = 0;
-      }
-      ++pass;
-    });
-    __syncthreads();                             // the flag is complete (no evaluation ran when iters == 0)
-    if (cs->inexact) {
-      r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
-        double a_lane, b_lane;
-        eval_slot<DT>(slot, inv, clo, chi, a_lane, b_lane);
-        const uint32_t set = pass % 3u;
-        cs->part[tid] = valid ? b_lane : 0.0;
-        if (valid) atomicAdd(&ra->cc[set], (uint32_t)a_lane);
         __syncthreads();
         A = (double)ra->cc[set];
-        double b = 0.0;
-        const uint32_t first = (valid ? my_row : 0u) * segs;
-        for (uint32_t j = 0; j < segs; ++j) b += cs->part[first + j];
-        B = b;
-        if (valid && seg == 0) ra->cc[(pass + 2u) % 3u] = 0;
+        B = ldexp((double)(long long)ra->xc[set], -q);            // the integer is exact; one rounding at most
+        if (valid && seg == 0) {
+          const uint32_t clr = (pass + 2u) % 3u;
+          ra->cc[clr] = 0;
+          ra->xc[clr] = 0;
+        }
         ++pass;
-        __syncthreads();                         // part[] is rewritten by the next evaluation
       });
-    }
-
-    // ---- emit (Algorithm 1, third step) ----
-    float s32, inv;
-    scale_of(kp, r_sel, s32, inv);
-    __syncthreads();
-    if (valid) {
-      emit_codes_to_slot<DT>(kp, slot, inv, z, mlo, mhi);
-      if (seg == 0) {
-        md.scales[row0 + my_row] = s32;
-        md.zps[row0 + my_row] = (unsigned char)z;
+      __syncthreads();                             // the flag is complete (no evaluation ran when iters == 0)
+      if (cs->inexact) {
+        r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
+          double a_lane, b_lane;
+          eval_slot<DX>(slot, inv * unshift, clo, chi, a_lane, b_lane);
+          b_lane = ldexp(b_lane, -shift);
+          const uint32_t set = pass % 3u;
+          cs->part[tid] = valid ? b_lane : 0.0;
+          if (valid) atomicAdd(&ra->cc[set], (uint32_t)a_lane);
+          __syncthreads();
+          A = (double)ra->cc[set];
+          double b = 0.0;
+          const uint32_t first = (valid ? my_row : 0u) * segs;
+          for (uint32_t j = 0; j < segs; ++j) b += cs->part[first + j];
+          B = b;
+          if (valid && seg == 0) ra->cc[(pass + 2u) % 3u] = 0;
+          ++pass;
+          __syncthreads();                         // part[] is rewritten by the next evaluation
+        });
       }
-    }
+
+      // ---- emit (Algorithm 1, third step) ----
+      float s32, inv;
+      scale_of(kp, r_sel, s32, inv);
+      __syncthreads();
+      if (valid) {
+        emit_codes_to_slot<DX>(kp, slot, inv * unshift, z, mlo, mhi);
+        if (seg == 0) {
+          md.scales[row0 + my_row] = s32;
+          md.zps[row0 + my_row] = (unsigned char)z;
+        }
+      }
+    };
+    if (DT == EQ_BF16 && as_f16) rest(std::integral_constant<int, EQ_F16>{}, shift_f16);
+    else rest(std::integral_constant<int, DT>{}, 0);
     __syncthreads();
     copy_wave_codes(kp, md, pool, row0 * (int64_t)segs, wave * kWave, nr * segs, lane);
     __syncthreads();                             // the pool is overwritten by the next round's staging

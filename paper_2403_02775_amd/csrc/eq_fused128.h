@@ -1,13 +1,13 @@
 // Fast path for group_size 128: one LANE owns one unit.
 //
-// A workgroup walks a range of rows.  Rows are staged into an LDS pool (eq_rowstage.h: one
-// coalesced HBM read, statistics, outlier compaction); whenever the pool holds 256 units
-// every lane takes one and runs ALL range-optimisation iterations on it (Sec. 4.2 /
+// A workgroup walks a range of rows.  Rows are staged into an LDS pool (eq_rowbatch.h: one
+// coalesced HBM read, statistics, outlier compaction); whenever the pool holds a round of
+// units (one per lane) every lane takes one and runs ALL range-optimisation iterations on it (Sec. 4.2 /
 // Algorithm 1, second step) without touching HBM: the unit's fixed-point planes live in
 // registers, its 16-bit values are re-read from the lane's own LDS slot in each iteration
 // (conflict-free 128-bit reads, ~3 % of the instruction stream), there is no cross-lane
 // reduction, and the scalar Adam step is paid once per 128 elements.  Units left over
-// (< 256) are carried to the next fill, so lanes idle only at the end of a range.
+// (less than a round) are carried to the next fill, so lanes idle only at the end of a range.
 //
 // Exact sums without binary64 in the inner loop: x is held as a block fixed-point integer
 // xi = x * 2^q (|xi| < 2^30, q from the unit's largest magnitude), split into two signed
