@@ -133,6 +133,66 @@ def bench_dequantize(args):
                                                                            "1%": 0.117, "5%": 0.186, "10%": 0.212}}}), flush=True)
 
 
+def bench_matvec(args):
+    """Secondary measurement: eq_dequant_matvec (Eq. 4 fused with a matrix-vector product) on the
+    same BLOOM-176B FFN shape, 4-bit per-channel, 1 % outliers, against torch's fp16 matrix-vector
+    product on the dequantized matrix (which reads 2 bytes per weight)."""
+    import torch
+    import paper_2403_02775_amd as eqg
+    dev = "cuda:0"
+    rows, cols = 14336, 57344
+    gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=0)
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (rows, cols * 4 // 32), dtype=torch.int32, device=dev, generator=g)
+    scales = torch.rand((rows, 1), device=dev, generator=g) * 0.01 + 0.001
+    zps = torch.full((rows, 1), 7, dtype=torch.uint8, device=dev)
+    k = max(1, int(round(cols * args.outlier_pct / 100.0)))
+    stride = cols // k                              # one outlier in every stride-wide stretch: ascending, no duplicates
+    col = (torch.arange(k, device=dev, dtype=torch.int32) * stride).view(1, -1) + \
+        torch.randint(stride, (rows, k), device=dev, generator=g, dtype=torch.int32)
+    col = col.contiguous()
+    rp = (torch.arange(rows + 1, device=dev, dtype=torch.int64) * k).to(torch.int32)
+    # the format's invariant: an outlier's slot holds the zero level (code = zero-point)
+    by = codes.view(torch.uint8).view(rows, cols // 2)
+    rr = torch.arange(rows, device=dev).view(-1, 1).expand(-1, k)
+    cl = col.long()
+    for nib, keep, put in ((0, 0xF0, 0x07), (1, 0x0F, 0x70)):
+        m = (cl % 2) == nib
+        r_, b_ = rr[m], cl[m] // 2
+        by[r_, b_] = (by[r_, b_] & keep) | put
+    vals = (torch.randn(rows * k, device=dev, generator=g) * 0.3).half().view(torch.int16)
+    q = eqg.QMatrix(codes=codes, scales=scales, zero_points=zps, out_row_ptr=rp, out_col=col.view(-1),
+                    out_val=vals, status=torch.zeros(1, dtype=torch.int32, device=dev))
+    x = torch.randn(cols, device=dev, generator=g).half()
+    y = torch.empty(rows, dtype=torch.float32, device=dev)
+    W = torch.empty((rows, cols), dtype=torch.float16, device=dev)
+    eqg.eq_dequantize(q, rows, cols, gp, W)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    fused_ms = timed(lambda: eqg.eq_dequant_matvec(q, rows, cols, gp, x, y))
+    dense_ms = timed(lambda: torch.mv(W, x))
+    y_ref = torch.mv(W.float(), x.float())
+    rel = float((y - y_ref).abs().max() / y_ref.abs().max())
+    traffic = rows * cols * 0.5 + rows * (5 + 4) + rows * k * 6 + cols * 2
+    print(json.dumps({"metric": f"eq_dequant_matvec ms (14336x57344, int4 x fp16 vector, {args.outlier_pct:g} % outliers)", "value": fused_ms, "unit": "ms",
+                      "n_gpus": 1, "steps": args.steps, "higher_is_better": False, "data": "synthetic",
+                      "GBps": traffic / (fused_ms * 1e-3) / 1e9, "hbm_frac": traffic / (fused_ms * 1e-3) / HBM_PEAK,
+                      "torch_fp16_mv_on_dequantized_ms": dense_ms, "speedup_vs_fp16_mv": dense_ms / fused_ms,
+                      "max_rel_diff_vs_fp32_mv": rel}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,9 +209,13 @@ def main():
                     help="also run one plain 4 GiB device-to-device copy (torch's copy kernel) so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) has a kernel of known traffic to scale by")
     ap.add_argument("--dequant", action="store_true", help="measure eq_dequantize instead (secondary benchmark, own JSON line)")
+    ap.add_argument("--outlier-pct", type=float, default=1.0, help="outlier ratio in percent for --matvec")
+    ap.add_argument("--matvec", action="store_true", help="measure eq_dequant_matvec instead (secondary benchmark, own JSON line)")
     args = ap.parse_args()
     if args.dequant:
         return bench_dequantize(args)
+    if args.matvec:
+        return bench_matvec(args)
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path needs no communication; see DESIGN.md); run with --gpus 1")
 

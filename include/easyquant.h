@@ -149,6 +149,16 @@ EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* row
 EQ_API int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p,
                   void* W_out, int64_t ld_out, void* hip_stream);
 
+/* Eq. 4 fused with a matrix-vector product (the serving-time use of a quantized weight, the
+ * scenario of the paper's latency paragraph in Sec. 5 for one token): y = W^ x, where W^ is
+ * exactly what eq_dequantize would write (every element rounded to p->dtype, outliers verbatim),
+ * but W^ never reaches memory: bits/8 bytes are read per weight instead of 2.
+ *   x  DEVICE, cols elements of p->dtype, 16-byte aligned.    y  DEVICE, rows binary32 values.
+ * Products and sums are binary32 in an unspecified order: y agrees with the exact product to
+ * within 3e-5 * sum_j |W^_ij x_j| per row.  q as for eq_dequantize.  cols == 0 gives y = 0. */
+EQ_API int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p,
+                      const void* x, float* y, void* hip_stream);
+
 /* Bytes of workspace eq_quantize_batch needs for these shapes (HOST arrays of length n);
  * eq_quantize_matrix is the n == 1 case.  0 on invalid arguments. */
 EQ_API size_t eq_workspace_bytes(int32_t n, const int64_t* rows, const int64_t* cols,

@@ -348,6 +348,14 @@ def dequantize(q: Dict[str, np.ndarray], rows: int, cols: int, p: Params) -> np.
     return out
 
 
+def dequant_matvec(q: Dict[str, np.ndarray], rows: int, cols: int, p: Params, x_raw: np.ndarray) -> np.ndarray:
+    """The reconstruction of Eq. 4 applied to a vector: y = W^ x in binary64, W^ = dequantize(q)
+    (every element already rounded to the 16-bit type), x given as raw 16-bit patterns."""
+    W = widen(dequantize(q, rows, cols, p), p.dtype).astype(_f64)
+    x = widen(np.asarray(x_raw).reshape(cols), p.dtype).astype(_f64)
+    return W @ x
+
+
 def reconstruction_sse(raw: np.ndarray, deq_raw: np.ndarray, dtype: int) -> np.ndarray:
     """Per-row squared reconstruction error (the paper's r(W), Section 2), binary64."""
     d = widen(deq_raw, dtype).astype(_f64) - widen(raw, dtype).astype(_f64)

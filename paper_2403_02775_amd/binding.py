@@ -61,6 +61,9 @@ def lib() -> C.CDLL:
         L.eq_dequantize.restype = C.c_int
         L.eq_dequantize.argtypes = [C.POINTER(_CQMatrix), C.c_int64, C.c_int64, C.POINTER(_CParams), C.c_void_p,
                                     C.c_int64, C.c_void_p]
+        L.eq_dequant_matvec.restype = C.c_int
+        L.eq_dequant_matvec.argtypes = [C.POINTER(_CQMatrix), C.c_int64, C.c_int64, C.POINTER(_CParams), C.c_void_p,
+                                        C.c_void_p, C.c_void_p]
         L.eq_workspace_bytes.restype = C.c_size_t
         L.eq_workspace_bytes.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                          C.POINTER(_CParams)]
@@ -219,6 +222,19 @@ def eq_quantize_batch(Ws: List[torch.Tensor], p: Params, outs: List[QMatrix], wo
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if rc != 0:
         raise EasyQuantError(rc, "eq_quantize_batch")
+
+
+def eq_dequant_matvec(q: QMatrix, rows: int, cols: int, p: Params, x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    """y (rows, float32) = dequantized matrix times x (cols, the matrix's 16-bit type), fused."""
+    want = torch.float16 if p.dtype == EQ_F16 else torch.bfloat16
+    if x.dtype != want or x.dim() != 1 or not x.is_contiguous() or x.numel() != cols:
+        raise ValueError("x must be a contiguous vector of cols elements in the matrix's 16-bit type")
+    if y.dtype != torch.float32 or y.dim() != 1 or not y.is_contiguous() or y.numel() != rows:
+        raise ValueError("y must be a contiguous float32 vector of rows elements")
+    cp, cq = p.c(), q.c()
+    rc = lib().eq_dequant_matvec(C.byref(cq), rows, cols, C.byref(cp), x.data_ptr(), y.data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_dequant_matvec")
 
 
 def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tensor, stream=None) -> None:

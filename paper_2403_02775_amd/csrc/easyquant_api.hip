@@ -411,6 +411,35 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   return EQ_OK;
 }
 
+// Argument checks and the descriptor shared by the two consumers of a quantized matrix.
+int make_deq_desc(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p, DeqDesc* d) {
+  if (!q || !p) return EQ_E_NULL;
+  if (p->dtype != EQ_F16 && p->dtype != EQ_BF16) return EQ_E_PARAM;
+  if (p->bits < 2 || p->bits > 8 || p->group_size < 0) return EQ_E_PARAM;
+  if (rows < 0 || cols < 0 || rows > 0x7FFFFFFF || cols % 8) return EQ_E_SHAPE;
+  if (cols > EQ_MAX_COLS) return EQ_E_UNSUPPORTED;
+  if (p->group_size && (p->group_size % 32 || cols % p->group_size)) return EQ_E_SHAPE;
+  std::memset(d, 0, sizeof(*d));
+  if (rows == 0 || cols == 0) {
+    d->rows = (int32_t)rows;
+    d->cols = (int32_t)cols;
+    return EQ_OK;
+  }
+  if (!q->codes || !q->scales || !q->zero_points || !q->out_row_ptr) return EQ_E_NULL;
+  if ((uintptr_t)q->codes & 3) return EQ_E_ALIGN;
+  const bool sparse = q->out_col && q->out_val;
+  d->codes = dev(q->codes); d->scales = dev(q->scales); d->zps = dev(q->zero_points);
+  d->out_row_ptr = dev(q->out_row_ptr);
+  d->out_col = sparse ? dev(q->out_col) : nullptr;
+  d->out_val = sparse ? dev(q->out_val) : nullptr;
+  d->rows = (int32_t)rows; d->cols = (int32_t)cols;
+  d->G = p->group_size ? p->group_size : (int32_t)cols;
+  d->upr = d->cols / d->G;
+  d->words_per_row = (int32_t)eq_code_words_per_row(cols, p->bits);
+  d->bits = p->bits;
+  return EQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -566,32 +595,46 @@ int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld, co
 
 int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p, void* W_out, int64_t ld_out,
                   void* hip_stream) {
-  if (!q || !p) return EQ_E_NULL;
-  if (p->dtype != EQ_F16 && p->dtype != EQ_BF16) return EQ_E_PARAM;
-  if (p->bits < 2 || p->bits > 8 || p->group_size < 0) return EQ_E_PARAM;
-  if (rows < 0 || cols < 0 || rows > 0x7FFFFFFF || cols % 8 || ld_out < cols || ld_out % 8) return EQ_E_SHAPE;
-  if (cols > EQ_MAX_COLS) return EQ_E_UNSUPPORTED;
-  if (p->group_size && (p->group_size % 32 || cols % p->group_size)) return EQ_E_SHAPE;
-  if (rows == 0 || cols == 0) return EQ_OK;
-  if (!W_out || !q->codes || !q->scales || !q->zero_points || !q->out_row_ptr) return EQ_E_NULL;
-  if (((uintptr_t)W_out & 15) || ((uintptr_t)q->codes & 3)) return EQ_E_ALIGN;
   DeqDesc d;
-  const bool sparse = q->out_col && q->out_val;
-  d.codes = dev(q->codes); d.scales = dev(q->scales); d.zps = dev(q->zero_points);
-  d.out_row_ptr = dev(q->out_row_ptr);
-  d.out_col = sparse ? dev(q->out_col) : nullptr;
-  d.out_val = sparse ? dev(q->out_val) : nullptr;
+  const int rc = make_deq_desc(q, rows, cols, p, &d);
+  if (rc != EQ_OK) return rc;
+  if (ld_out < cols || ld_out % 8) return EQ_E_SHAPE;
+  if (rows == 0 || cols == 0) return EQ_OK;
+  if (!W_out) return EQ_E_NULL;
+  if ((uintptr_t)W_out & 15) return EQ_E_ALIGN;
   d.W = dev(static_cast<uint16_t*>(W_out));
-  d.ld = ld_out; d.rows = (int32_t)rows; d.cols = (int32_t)cols;
-  d.G = p->group_size ? p->group_size : (int32_t)cols;
-  d.upr = d.cols / d.G;
-  d.words_per_row = (int32_t)eq_code_words_per_row(cols, p->bits);
-  d.bits = p->bits;
+  d.ld = ld_out;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   {
     ScopedKernelTimer tm(st);
     if (p->dtype == EQ_F16) hipLaunchKernelGGL(dequantize_rows<EQ_F16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
     else hipLaunchKernelGGL(dequantize_rows<EQ_BF16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
+  }
+  EQ_HIP(hipGetLastError());
+  return EQ_OK;
+}
+
+int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p, const void* x, float* y,
+                      void* hip_stream) {
+  DeqDesc d;
+  const int rc = make_deq_desc(q, rows, cols, p, &d);
+  if (rc != EQ_OK) return rc;
+  if (rows == 0) return EQ_OK;
+  if (!y || (cols > 0 && !x)) return EQ_E_NULL;
+  if (((uintptr_t)x & 15) || ((uintptr_t)y & 3)) return EQ_E_ALIGN;
+  d.W = nullptr;
+  d.ld = 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const unsigned blocks = (unsigned)((rows + kMvRows - 1) / kMvRows);
+  {
+    ScopedKernelTimer tm(st);
+    const EQ_GLOBAL uint16_t* xd = dev(static_cast<const uint16_t*>(x));
+    EQ_GLOBAL float* yd = dev(y);
+    const dim3 grid(blocks), block(kThreads);
+    if (p->dtype == EQ_F16 && p->bits == 4) hipLaunchKernelGGL((dequant_matvec<EQ_F16, true>), grid, block, 0, st, d, xd, yd);
+    else if (p->dtype == EQ_F16) hipLaunchKernelGGL((dequant_matvec<EQ_F16, false>), grid, block, 0, st, d, xd, yd);
+    else if (p->bits == 4) hipLaunchKernelGGL((dequant_matvec<EQ_BF16, true>), grid, block, 0, st, d, xd, yd);
+    else hipLaunchKernelGGL((dequant_matvec<EQ_BF16, false>), grid, block, 0, st, d, xd, yd);
   }
   EQ_HIP(hipGetLastError());
   return EQ_OK;

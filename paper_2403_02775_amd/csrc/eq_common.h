@@ -106,6 +106,9 @@ typedef __amdgpu_buffer_rsrc_t BufferRsrc;
 __device__ __forceinline__ BufferRsrc make_buffer(const EQ_GLOBAL void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);   // untyped 32-bit data
 }
+__device__ __forceinline__ uint32_t buffer_load32(BufferRsrc rs, uint32_t byte_offset) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, (int)byte_offset, 0, 0);
+}
 __device__ __forceinline__ uint4 buffer_load_stream128(BufferRsrc rs, uint32_t byte_offset) {
   const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_offset, 0, 2);           // 2: non-temporal
   return make_uint4(v.x, v.y, v.z, v.w);

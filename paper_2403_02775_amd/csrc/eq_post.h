@@ -168,6 +168,36 @@ __device__ __forceinline__ uint4 dequantize_chunk(const DeqDesc& d, int64_t row,
   return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
 }
 
+// Byte N of a word as binary32 (v_cvt_f32_ubyteN; written out because the compiler, knowing that
+// only four bits of each byte can be set, otherwise takes a bit-field extract and a convert).
+template <int N>
+__device__ __forceinline__ float byte_to_float(uint32_t w) {
+  float f;
+  if (N == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(f) : "v"(w));
+  else if (N == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(f) : "v"(w));
+  else if (N == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(f) : "v"(w));
+  else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(f) : "v"(w));
+  return f;
+}
+
+// The same for 4-bit codes, from the chunk's one code word: nibbles to bytes, bytes to binary32,
+// then exactly the arithmetic above (subtract the zero-point, one binary32 product, one rounding
+// to the 16-bit type).
+template <int DT>
+__device__ __forceinline__ uint4 dequantize_chunk4(uint32_t w, float s, float zf) {
+  const uint32_t even = w & 0x0F0F0F0Fu, odd = (w >> 4) & 0x0F0F0F0Fu;      // elements 0 2 4 6 / 1 3 5 7
+  const float u[8] = {byte_to_float<0>(even), byte_to_float<0>(odd), byte_to_float<1>(even), byte_to_float<1>(odd),
+                      byte_to_float<2>(even), byte_to_float<2>(odd), byte_to_float<3>(even), byte_to_float<3>(odd)};
+  uint32_t h[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float prod = s * (u[k] - zf);
+    asm volatile("" : "+v"(prod));      // two roundings, as in dequantize_chunk
+    h[k] = narrow16<DT>(prod);
+  }
+  return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
 constexpr int kDeqChunks = 4;      // chunks per thread and segment: a segment is 4 * 256 * 8 = 8192 columns
 
 // Eq. 4, dense and sparse part in one pass over the output: one workgroup per row walks the
@@ -212,6 +242,148 @@ __global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
       const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
       if (ch < nchunks) global_store_stream128(orow + 8 * (size_t)ch, seg[j * kThreads + tid]);
     }
+  }
+}
+
+// ---- Eq. 4 fused with a matrix-vector product ----------------------------------------------
+// y = W^ x for the reconstruction W^ of Eq. 4 (every element rounded to the 16-bit type exactly
+// as dequantize_rows writes it), without W^ ever reaching HBM: the kernel reads bits/8 bytes per
+// weight instead of 2.  A workgroup takes kMvRows consecutive rows; a thread keeps its chunks
+// of x in registers for all of them, products and sums are binary32.  An outlier's slot holds
+// the zero level, so the dense part contributes 0 there and the row's sparse list is added on
+// top as val * x[col].
+constexpr int kMvRows = 8;
+constexpr int kMvChunks = 2;
+
+template <int DT>
+__device__ __forceinline__ float dot8(const uint4 w, const uint4 x, float acc) {
+  const uint32_t a[4] = {w.x, w.y, w.z, w.w}, b[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (DT == EQ_F16) {
+      typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a[k]), __builtin_bit_cast(half2_t, b[k]), acc, false);
+    } else {
+      acc = __builtin_fmaf(widen16<DT>(a[k] & 0xFFFFu), widen16<DT>(b[k] & 0xFFFFu), acc);
+      acc = __builtin_fmaf(widen16<DT>(a[k] >> 16), widen16<DT>(b[k] >> 16), acc);
+    }
+  }
+  return acc;
+}
+
+// FOUR: 4-bit codes (one code word per chunk).  One range per row (upr == 1) keeps the rows'
+// scales and zero-points in registers.
+template <int DT, bool FOUR>
+__global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_GLOBAL uint16_t* __restrict__ x,
+                                                            EQ_GLOBAL float* __restrict__ y) {
+  __shared__ float red[kMvRows][kWaves];
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int64_t row0 = (int64_t)blockIdx.x * kMvRows;
+  const int nrows = (int)min((int64_t)kMvRows, (int64_t)d.rows - row0);
+  const uint32_t nchunks = (uint32_t)d.cols >> 3;
+  const bool per_row = d.upr == 1;
+  uint32_t rp[kMvRows + 1];                              // the rows' sparse ranges (loaded early, used last)
+#pragma unroll
+  for (int r = 0; r <= kMvRows; ++r) rp[r] = d.out_col ? d.out_row_ptr[row0 + min(r, nrows)] : 0u;   // absent rows: empty
+  float acc[kMvRows], srow[kMvRows], zrow[kMvRows];
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r) {
+    acc[r] = 0.0f;
+    srow[r] = 0.0f;
+    zrow[r] = 0.0f;
+    if (FOUR && per_row && r < nrows) {
+      srow[r] = d.scales[row0 + r];
+      zrow[r] = (float)d.zps[row0 + r];
+    }
+  }
+  // range-checked views of the rows' code words: chunks past the end of a row and rows past the
+  // end of the matrix read as zero words without touching memory (their x chunk is zero too)
+  BufferRsrc crow[kMvRows];
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r)
+    crow[r] = make_buffer(d.codes + (r < nrows ? row0 + r : row0) * (int64_t)d.words_per_row,
+                          FOUR && r < nrows ? (uint32_t)d.words_per_row * 4u : 0u);
+  auto sparse_part = [&] {
+    if (!d.out_col) return;
+    // the sparse lists of the workgroup's rows are one contiguous stretch of the CSR arrays: one
+    // strided walk over it, each entry credited to the row whose range holds its index
+    const uint32_t b = rp[0], e = rp[kMvRows];
+    constexpr int kAhead = 4;                            // entries per thread in flight (two dependent loads each)
+    for (uint32_t i0 = b + tid; i0 < e; i0 += kAhead * kThreads) {
+      uint32_t col[kAhead];
+      float val[kAhead], xg[kAhead];
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        const uint32_t i = i0 + (uint32_t)a * kThreads;
+        col[a] = i < e ? d.out_col[i] : 0xFFFFFFFFu;
+        val[a] = i < e ? widen16<DT>(d.out_val[i]) : 0.0f;
+      }
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) xg[a] = col[a] < (uint32_t)d.cols ? widen16<DT>(x[col[a]]) : 0.0f;
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        const uint32_t i = i0 + (uint32_t)a * kThreads;
+        const float prod = val[a] * xg[a];
+#pragma unroll
+        for (int r = 0; r < kMvRows; ++r) acc[r] += (i >= rp[r] && i < rp[r + 1]) ? prod : 0.0f;
+      }
+    }
+  };
+  for (uint32_t ch0 = 0; ch0 < nchunks; ch0 += kMvChunks * kThreads) {
+    uint4 xv[kMvChunks];
+#pragma unroll
+    for (int j = 0; j < kMvChunks; ++j) {
+      const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
+      xv[j] = ch < nchunks ? global_load128(x + 8 * (size_t)ch) : make_uint4(0, 0, 0, 0);
+    }
+    if (FOUR) {
+      uint32_t wq[kMvRows][kMvChunks];                   // every code load of the segment in flight
+#pragma unroll
+      for (int r = 0; r < kMvRows; ++r)
+#pragma unroll
+        for (int j = 0; j < kMvChunks; ++j)
+          wq[r][j] = buffer_load32(crow[r], (ch0 + (uint32_t)j * kThreads + tid) * 4u);
+#pragma unroll
+      for (int r = 0; r < kMvRows; ++r) {
+#pragma unroll
+        for (int j = 0; j < kMvChunks; ++j) {
+          float s = srow[r], zf = zrow[r];
+          if (!per_row) {                                // uniform
+            const uint32_t ch = min(ch0 + (uint32_t)j * kThreads + tid, nchunks - 1u);
+            const int64_t unit = (r < nrows ? row0 + r : row0) * (int64_t)d.upr + (ch * 8u) / (uint32_t)d.G;
+            s = d.scales[unit];
+            zf = (float)d.zps[unit];
+          }
+          acc[r] = dot8<DT>(dequantize_chunk4<DT>(wq[r][j], s, zf), xv[j], acc[r]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < kMvRows; ++r) {
+        if (r < nrows) {                                 // uniform
+#pragma unroll
+          for (int j = 0; j < kMvChunks; ++j) {
+            const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
+            if (ch < nchunks) acc[r] = dot8<DT>(dequantize_chunk<DT>(d, row0 + r, ch), xv[j], acc[r]);
+          }
+        }
+      }
+    }
+  }
+  sparse_part();
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r) {
+    float v = acc[r];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (lane == 0) red[r][wave] = v;
+  }
+  __syncthreads();
+  if (tid < (uint32_t)nrows) {
+    float t = red[tid][0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) t += red[tid][w];
+    y[row0 + tid] = t;
   }
 }
 

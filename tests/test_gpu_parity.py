@@ -7,7 +7,7 @@ import torch
 import eq_inputs
 import paper_2403_02775_amd as eqg
 from oracle import easyquant_oracle as eqo
-from parity import compare, compare_sse, gpu_dequantize, raw_of, run_gpu
+from parity import compare, compare_sse, gpu_dequantize, raw_of, run_gpu, to_gpu_params
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -133,6 +133,44 @@ def test_exact_rounding_ties_go_to_the_even_level(iters):
         assert res["excused_elems"] == 0
     res = _check(W, eqo.Params(bits=4, group_size=0, iters=iters, lr=0.0), f"ties per-channel T={iters}")
     assert res["excused_elems"] == 0
+
+
+@pytest.mark.parametrize("rows,cols,bits,G,dtype", [(37, 4096, 4, 128, "f16"), (19, 8192, 4, 0, "f16"), (9, 22016, 3, 128, "f16"),
+                                                    (70, 1280, 8, 32, "bf16"), (5, 57344, 4, 0, "f16"), (8, 256, 2, 64, "bf16")])
+def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
+    """eq_dequant_matvec against the oracle's W^ x (binary64) on the GPU's own quantized output:
+    the weights are bit-identical by construction (the same Eq. 4 arithmetic as eq_dequantize), so
+    what is compared is a binary32 accumulation against the exact one; the bar is the one the
+    header states, 3e-5 of the sum of the absolute terms of each row."""
+    rec = eq_inputs.RECIPES["c2"] if dtype == "f16" else eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16")
+    W = eq_inputs.gen_matrix(rows, cols, rec, seed=rows + cols + bits, device=DEV)
+    p = eqo.Params(dtype=eqo.F16 if dtype == "f16" else eqo.BF16, bits=bits, group_size=G, iters=3)
+    print(f"[case] matvec shape={tuple(W.shape)} bits={bits} G={G} {dtype}", flush=True)
+    outs, got = run_gpu([W], p)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(rows * 31 + cols)
+    x = torch.randn(cols, device=DEV, generator=g).to(W.dtype)
+    y = torch.empty(rows, dtype=torch.float32, device=DEV)
+    eqg.eq_dequant_matvec(outs[0], rows, cols, to_gpu_params(p), x, y)
+    torch.cuda.synchronize()
+    x_raw = raw_of(x.view(1, -1)).reshape(-1)
+    want = eqo.dequant_matvec(got[0], rows, cols, p, x_raw)
+    Wd = np.abs(eqo.widen(eqo.dequantize(got[0], rows, cols, p), p.dtype).astype(np.float64))
+    bound = 3e-5 * (Wd @ np.abs(eqo.widen(x_raw, p.dtype).astype(np.float64))) + 1e-30
+    err = np.abs(y.cpu().numpy().astype(np.float64) - want)
+    assert (err <= bound).all(), (float((err / bound).max()), int(np.argmax(err / bound)))
+    # the same call without the sparse list leaves exactly the outliers' contribution out
+    import dataclasses
+    dense_only = dataclasses.replace(outs[0], out_col=outs[0].out_col[:0], out_val=outs[0].out_val[:0])
+    y2 = torch.empty_like(y)
+    eqg.eq_dequant_matvec(dense_only, rows, cols, to_gpu_params(p), x, y2)
+    torch.cuda.synchronize()
+    q2 = dict(got[0])
+    q2["out_row_ptr"] = np.zeros_like(got[0]["out_row_ptr"])
+    q2["out_col"] = got[0]["out_col"][:0]
+    q2["out_val"] = got[0]["out_val"][:0]
+    err2 = np.abs(y2.cpu().numpy().astype(np.float64) - eqo.dequant_matvec(q2, rows, cols, p, x_raw))
+    assert (err2 <= bound).all()
 
 
 def test_bf16_and_student_t_inputs():

@@ -436,3 +436,23 @@ def test_exact_dot_falls_back_to_exact_summation():
     prod = np.array([[big, tiny, -big, tiny]], np.float32)
     got = eq._exact_dot(prod, np.array([2.0 ** -47]))
     assert got[0] == 2.0 ** -39
+
+
+def test_dequant_matvec_is_the_reconstruction_times_the_vector():
+    """Unit vectors pick out the columns of the (already pinned) reconstruction, and a hand-worked
+    2 x 8 case: codes 0..7 at zero-point 3 and scale 0.5 give (-1.5 .. 2), one outlier replaces
+    column 6 by 10; with x = (1, ..., 1) the first row sums to 2 - 1.5 + 10 = 10.5."""
+    p = eq.Params(bits=4, group_size=0)
+    u = np.stack([np.arange(8), np.full(8, 3)]).astype(np.int64)
+    u[0, 6] = 3                                                   # an outlier's slot holds the zero level
+    q = {"codes": eq.pack_codes(u, 4), "scales": np.full((2, 1), 0.5, np.float32),
+         "zero_points": np.full((2, 1), 3, np.uint8), "out_row_ptr": np.array([0, 1, 1], np.uint32),
+         "out_col": np.array([6], np.uint32), "out_val": eq.narrow(np.array([10.0], np.float32), eq.F16)}
+    ones = eq.narrow(np.ones(8, np.float32), eq.F16)
+    y = eq.dequant_matvec(q, 2, 8, p, ones)
+    assert y.tolist() == [10.5, 0.0]
+    W = eq.widen(eq.dequantize(q, 2, 8, p), eq.F16).astype(np.float64)
+    for j in range(8):
+        e = np.zeros(8, np.float32)
+        e[j] = 2.0
+        assert np.array_equal(eq.dequant_matvec(q, 2, 8, p, eq.narrow(e, eq.F16)), 2.0 * W[:, j])
