@@ -173,6 +173,19 @@ def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     assert (err2 <= bound).all()
 
 
+def test_longest_supported_rows():
+    # EQ_MAX_COLS = 65536: beyond the lane kernels' 32768, so the general kernel with the whole row in LDS
+    W = eq_inputs.gen_matrix(3, 65536, eq_inputs.RECIPES["c5"], seed=65, device=DEV)
+    _check(W, eqo.Params(bits=4, group_size=128, iters=8), "65536 columns, group 128")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=8), "65536 columns, per channel")
+    gp = eqg.Params(group_size=128)
+    too_long = torch.zeros((1, 65536 + 128), dtype=torch.float16, device=DEV)
+    with pytest.raises(eqg.EasyQuantError) as e:
+        eqg.eq_quantize_matrix(too_long, gp, eqg.alloc_outputs(1, 65536 + 128, gp, 0, DEV),
+                               torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -6
+
+
 def test_bf16_and_student_t_inputs():
     W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
