@@ -631,10 +631,14 @@ int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_
     const EQ_GLOBAL uint16_t* xd = dev(static_cast<const uint16_t*>(x));
     EQ_GLOBAL float* yd = dev(y);
     const dim3 grid(blocks), block(kThreads);
-    if (p->dtype == EQ_F16 && p->bits == 4) hipLaunchKernelGGL((dequant_matvec<EQ_F16, true>), grid, block, 0, st, d, xd, yd);
-    else if (p->dtype == EQ_F16) hipLaunchKernelGGL((dequant_matvec<EQ_F16, false>), grid, block, 0, st, d, xd, yd);
-    else if (p->bits == 4) hipLaunchKernelGGL((dequant_matvec<EQ_BF16, true>), grid, block, 0, st, d, xd, yd);
-    else hipLaunchKernelGGL((dequant_matvec<EQ_BF16, false>), grid, block, 0, st, d, xd, yd);
+    const int mode = p->bits != 4 ? 0 : d.upr == 1 ? 2 : 1;
+#define EQ_MV(DT_, MODE_) hipLaunchKernelGGL((dequant_matvec<DT_, MODE_>), grid, block, 0, st, d, xd, yd)
+    if (p->dtype == EQ_F16) {
+      if (mode == 2) EQ_MV(EQ_F16, 2); else if (mode == 1) EQ_MV(EQ_F16, 1); else EQ_MV(EQ_F16, 0);
+    } else {
+      if (mode == 2) EQ_MV(EQ_BF16, 2); else if (mode == 1) EQ_MV(EQ_BF16, 1); else EQ_MV(EQ_BF16, 0);
+    }
+#undef EQ_MV
   }
   EQ_HIP(hipGetLastError());
   return EQ_OK;

@@ -271,12 +271,16 @@ __device__ __forceinline__ float dot8(const uint4 w, const uint4 x, float acc) {
   return acc;
 }
 
-// FOUR: 4-bit codes (one code word per chunk).  One range per row (upr == 1) keeps the rows'
-// scales and zero-points in registers.
-template <int DT, bool FOUR>
+// MODE 0: any code width (dequantize_chunk).  MODE 1: 4-bit codes, one code word per chunk
+// (dequantize_chunk4).  MODE 2: 4-bit codes and one range per row: the 16 values a weight of a row
+// can take, fl16(fl32(s (u - z))) for u = 0..15, are tabulated in LDS once and every weight is
+// one 16-bit LDS read (two address instructions) instead of five arithmetic instructions.
+template <int DT, int MODE>
 __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_GLOBAL uint16_t* __restrict__ x,
                                                             EQ_GLOBAL float* __restrict__ y) {
+  constexpr bool FOUR = MODE != 0;
   __shared__ float red[kMvRows][kWaves];
+  __shared__ uint16_t lut[kMvRows][16];
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int64_t row0 = (int64_t)blockIdx.x * kMvRows;
   const int nrows = (int)min((int64_t)kMvRows, (int64_t)d.rows - row0);
@@ -291,10 +295,20 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
     acc[r] = 0.0f;
     srow[r] = 0.0f;
     zrow[r] = 0.0f;
-    if (FOUR && per_row && r < nrows) {
+    if (MODE == 1 && per_row && r < nrows) {
       srow[r] = d.scales[row0 + r];
       zrow[r] = (float)d.zps[row0 + r];
     }
+  }
+  if (MODE == 2) {
+    if (tid < (uint32_t)(kMvRows * 16)) {
+      const int r = (int)(tid >> 4), u = (int)(tid & 15u);
+      const int64_t row = row0 + (r < nrows ? r : 0);
+      float prod = d.scales[row] * ((float)u - (float)d.zps[row]);
+      asm volatile("" : "+v"(prod));      // two roundings, as in dequantize_chunk
+      lut[r][u] = (uint16_t)narrow16<DT>(prod);
+    }
+    __syncthreads();
   }
   // range-checked views of the rows' code words: chunks past the end of a row and rows past the
   // end of the matrix read as zero words without touching memory (their x chunk is zero too)
@@ -354,7 +368,17 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
             s = d.scales[unit];
             zf = (float)d.zps[unit];
           }
-          acc[r] = dot8<DT>(dequantize_chunk4<DT>(wq[r][j], s, zf), xv[j], acc[r]);
+          uint4 wv;
+          if (MODE == 2) {
+            const uint32_t w = wq[r][j];
+            uint32_t h[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) h[k] = lut[r][(w >> (4 * k)) & 15u];
+            wv = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+          } else {
+            wv = dequantize_chunk4<DT>(wq[r][j], s, zf);
+          }
+          acc[r] = dot8<DT>(wv, xv[j], acc[r]);
         }
       }
     } else {

@@ -136,7 +136,8 @@ def test_exact_rounding_ties_go_to_the_even_level(iters):
 
 
 @pytest.mark.parametrize("rows,cols,bits,G,dtype", [(37, 4096, 4, 128, "f16"), (19, 8192, 4, 0, "f16"), (9, 22016, 3, 128, "f16"),
-                                                    (70, 1280, 8, 32, "bf16"), (5, 57344, 4, 0, "f16"), (8, 256, 2, 64, "bf16")])
+                                                    (70, 1280, 8, 32, "bf16"), (5, 57344, 4, 0, "f16"), (8, 256, 2, 64, "bf16"),
+                                                    (17, 4096, 4, 0, "bf16"), (33, 2048, 4, 128, "bf16")])
 def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     """eq_dequant_matvec against the oracle's W^ x (binary64) on the GPU's own quantized output:
     the weights are bit-identical by construction (the same Eq. 4 arithmetic as eq_dequantize), so
