@@ -607,8 +607,11 @@ int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_para
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   {
     ScopedKernelTimer tm(st);
-    if (p->dtype == EQ_F16) hipLaunchKernelGGL(dequantize_rows<EQ_F16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
-    else hipLaunchKernelGGL(dequantize_rows<EQ_BF16>, dim3((unsigned)rows), dim3(kThreads), 0, st, d);
+    const dim3 grid((unsigned)rows), block(kThreads);
+    if (p->dtype == EQ_F16 && p->bits == 4) hipLaunchKernelGGL((dequantize_rows<EQ_F16, true>), grid, block, 0, st, d);
+    else if (p->dtype == EQ_F16) hipLaunchKernelGGL((dequantize_rows<EQ_F16, false>), grid, block, 0, st, d);
+    else if (p->bits == 4) hipLaunchKernelGGL((dequantize_rows<EQ_BF16, true>), grid, block, 0, st, d);
+    else hipLaunchKernelGGL((dequantize_rows<EQ_BF16, false>), grid, block, 0, st, d);
   }
   EQ_HIP(hipGetLastError());
   return EQ_OK;

@@ -205,42 +205,91 @@ constexpr int kDeqChunks = 4;      // chunks per thread and segment: a segment i
 // the segment (the list is sorted by column, so they are the next entries of the row's run)
 // overwrite their 16-bit slots there, and the segment leaves with coalesced 128-bit stores.
 // Each output byte is written to HBM once; there is no read-modify-write of cache lines.
-template <int DT>
+// Without an outlier list the results go straight from registers to HBM.
+// FOUR: 4-bit codes, one code word per chunk, all of a segment's words in flight together.
+template <int DT, bool FOUR>
 __global__ __launch_bounds__(kThreads) void dequantize_rows(DeqDesc d) {
   __shared__ uint4 seg[kDeqChunks * kThreads];
   const int64_t row = blockIdx.x;
   const uint32_t tid = threadIdx.x;
   const uint32_t nchunks = (uint32_t)d.cols >> 3;
+  const bool sparse = d.out_col != nullptr;
   uint32_t next = 0, end = 0;                  // the row's outliers not yet written
-  if (d.out_col) {
+  if (sparse) {
     next = d.out_row_ptr[row];
     end = d.out_row_ptr[row + 1];
   }
+  const bool per_row = d.upr == 1;
+  float s_row = 0.0f, z_row = 0.0f;
+  if (FOUR && per_row) {
+    s_row = d.scales[row];
+    z_row = (float)d.zps[row];
+  }
+  const BufferRsrc crow = make_buffer(d.codes + row * (int64_t)d.words_per_row, FOUR ? (uint32_t)d.words_per_row * 4u : 0u);
   EQ_GLOBAL uint16_t* orow = d.W + row * d.ld;
   for (uint32_t ch0 = 0; ch0 < nchunks; ch0 += kDeqChunks * kThreads) {
+    // the next entries of the row's list, loaded ahead of the dense work
+    const uint32_t i_first = next + tid;
+    uint32_t col_first = 0xFFFFFFFFu;
+    uint16_t val_first = 0;
+    if (sparse && i_first < end) {
+      col_first = d.out_col[i_first];
+      val_first = d.out_val[i_first];
+    }
+    uint4 res[kDeqChunks];
+    if (FOUR) {
+      uint32_t wq[kDeqChunks];
+#pragma unroll
+      for (int j = 0; j < kDeqChunks; ++j) wq[j] = buffer_load32(crow, (ch0 + (uint32_t)j * kThreads + tid) * 4u);
+#pragma unroll
+      for (int j = 0; j < kDeqChunks; ++j) {
+        float s = s_row, zf = z_row;
+        if (!per_row) {                          // uniform
+          const uint32_t ch = min(ch0 + (uint32_t)j * kThreads + tid, nchunks - 1u);
+          const int64_t unit = row * (int64_t)d.upr + (ch * 8u) / (uint32_t)d.G;
+          s = d.scales[unit];
+          zf = (float)d.zps[unit];
+        }
+        res[j] = dequantize_chunk4<DT>(wq[j], s, zf);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kDeqChunks; ++j) {
+        const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
+        res[j] = ch < nchunks ? dequantize_chunk<DT>(d, row, ch) : make_uint4(0, 0, 0, 0);
+      }
+    }
+    if (sparse) {                                // uniform
+#pragma unroll
+      for (int j = 0; j < kDeqChunks; ++j) seg[j * kThreads + tid] = res[j];
+      const uint32_t col0 = ch0 * 8u, col1 = min(col0 + kDeqChunks * kThreads * 8u, (uint32_t)d.cols);
+      uint32_t taken;
+      bool first = true;
+      do {                                       // uniform: every thread sees the same counts
+        __syncthreads();                         // dense results (or the previous patches) are in place
+        uint32_t col = col_first;
+        uint16_t val = val_first;
+        if (!first) {
+          const uint32_t i = next + tid;
+          col = 0xFFFFFFFFu;
+          if (i < end) {
+            col = d.out_col[i];
+            val = d.out_val[i];
+          }
+        }
+        first = false;
+        const bool mine = col >= col0 && col < col1;
+        if (mine) reinterpret_cast<uint16_t*>(seg)[col - col0] = val;
+        taken = (uint32_t)__syncthreads_count(mine);
+        next += taken;
+      } while (taken == (uint32_t)kThreads);     // all of this batch fell into the segment: there may be more
+#pragma unroll
+      for (int j = 0; j < kDeqChunks; ++j) res[j] = seg[j * kThreads + tid];   // the entries this thread wrote itself
+    }
 #pragma unroll
     for (int j = 0; j < kDeqChunks; ++j) {
       const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
-      if (ch < nchunks) seg[j * kThreads + tid] = dequantize_chunk<DT>(d, row, ch);
-    }
-    const uint32_t col0 = ch0 * 8u, col1 = min(col0 + kDeqChunks * kThreads * 8u, (uint32_t)d.cols);
-    uint32_t taken;
-    do {                                       // uniform: every thread sees the same counts
-      __syncthreads();                         // dense results (or the previous patches) are in place
-      const uint32_t i = next + tid;
-      bool mine = false;
-      if (i < end) {
-        const uint32_t col = d.out_col[i];
-        mine = col >= col0 && col < col1;
-        if (mine) reinterpret_cast<uint16_t*>(seg)[col - col0] = d.out_val[i];
-      }
-      taken = (uint32_t)__syncthreads_count(mine);
-      next += taken;
-    } while (taken == (uint32_t)kThreads);     // all of this batch fell into the segment: there may be more
-#pragma unroll
-    for (int j = 0; j < kDeqChunks; ++j) {     // every thread reads back the entries it wrote itself
-      const uint32_t ch = ch0 + (uint32_t)j * kThreads + tid;
-      if (ch < nchunks) global_store_stream128(orow + 8 * (size_t)ch, seg[j * kThreads + tid]);
+      if (ch < nchunks) global_store_stream128(orow + 8 * (size_t)ch, res[j]);
     }
   }
 }
