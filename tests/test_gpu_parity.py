@@ -207,6 +207,8 @@ def test_last_iterate_and_llama_learning_rate():
     _check(W, eqo.Params(bits=4, group_size=128, iters=100, select=eqo.SELECT_LAST), "select=last")
     _check(W, eqo.Params(bits=4, group_size=128, iters=500, lr=1e-4), "T=500 lr=1e-4")
     _check(W, eqo.Params(bits=4, group_size=128, iters=0), "T=0")
+    _check(W, eqo.Params(bits=4, group_size=128, iters=0, stat_scope=eqo.STAT_MATRIX), "T=0, matrix scope")
+    _check(W, eqo.Params(bits=8, group_size=128, iters=0, mode=eqo.ASYMMETRIC), "T=0, 8-bit asymmetric")
     _check(W, eqo.Params(bits=4, group_size=128, iters=1), "T=1")
     _check(W, eqo.Params(bits=4, group_size=128, iters=30, n_sigma=float("inf")), "no outliers")
     _check(W, eqo.Params(bits=4, group_size=128, iters=30, n_sigma=1.0), "n=1 (many outliers)")
@@ -248,6 +250,20 @@ def test_batch_of_mixed_shapes_matches_single_calls_and_is_deterministic():
             _, single = run_gpu([W], p, batch=False)
             for k in a:
                 assert np.array_equal(a[k], single[0][k]), k
+
+
+def test_per_channel_batch_spans_three_kernels():
+    # one call, one range per row: rows for the per-channel lane kernel (two row lengths, i.e. two
+    # launches), rows too short for it (general kernel), and an empty matrix
+    rec = eq_inputs.RECIPES["c5"]
+    Ws = [eq_inputs.gen_matrix(r, c, rec, seed=70 + i, device=DEV) for i, (r, c) in
+          enumerate([(16, 4096), (8, 256), (5, 11008), (0, 128), (9, 4096), (6, 1000 * 8)])]
+    p = eqo.Params(bits=4, group_size=0, iters=15)
+    _, got = run_gpu(Ws, p)
+    for W, a in zip(Ws, got):
+        if W.shape[0]:
+            res = compare(raw_of(W), a, eqo.quantize_matrix(raw_of(W), p), p, f"per-channel batch {tuple(W.shape)}")
+            assert res["excused_elems"] == 0
 
 
 def test_outlier_overflow_and_nonfinite_are_reported():
