@@ -187,6 +187,34 @@ def test_longest_supported_rows():
     assert e.value.code == -6
 
 
+@pytest.mark.parametrize("G,iters", [(128, 6), (0, 6), (128, 0)])
+def test_extreme_magnitudes_and_degenerate_rows(G, iters):
+    # the three lane kernels on rows that leave the fast statistics: magnitudes whose squares overflow
+    # binary32 (bf16), the largest fp16 values, constant rows, an all-zero row, a row of tiny values
+    cols = 4096
+    g = torch.Generator(device=DEV)
+    g.manual_seed(11)
+    W = (torch.randn((12, cols), device=DEV, generator=g) * 0.02).to(torch.bfloat16)
+    W[0] = W[0] * 1e30                      # squares overflow: the sums are not finite, the values are
+    W[1] = 0.5                              # constant: sigma = 0, no outliers, one level
+    W[2] = 0
+    W[3] = W[3] * 1e-30
+    W[4, 7] = 3e38
+    W[5, ::2] = -2.0
+    W[5, 1::2] = 2.0                        # mean 0, every element exactly one sigma away
+    res = _check(W, eqo.Params(dtype=eqo.BF16, bits=4, group_size=G, iters=iters), f"bf16 extremes G={G} T={iters}")
+    assert res["excused_elems"] == 0
+    Wh = (torch.randn((8, cols), device=DEV, generator=g) * 0.02).to(torch.float16)
+    Wh[0] = Wh[0].sign() * 65504.0          # the largest fp16 magnitude everywhere
+    Wh[1, 100] = 65504.0
+    Wh[2] = 6e-8                            # the smallest subnormal
+    Wh[3, :128] = 0
+    res = _check(Wh, eqo.Params(bits=4, group_size=G, iters=iters), f"fp16 extremes G={G} T={iters}")
+    assert res["excused_elems"] == 0
+    res = _check(Wh, eqo.Params(bits=4, group_size=G, iters=iters, n_sigma=1.0), f"fp16 extremes, n = 1, G={G} T={iters}")
+    assert res["excused_elems"] == 0
+
+
 def test_bf16_and_student_t_inputs():
     W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
