@@ -264,6 +264,9 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     // run on a partly idle chip); a multiple of the period after which rows fill whole rounds
     // when that fits
     int64_t target = std::min<int64_t>(8192, std::max<int64_t>(nt, total_units / 16384));
+    // an item's last round is partly filled when rows do not tile the rounds: at least four
+    // rounds per item as long as that still leaves a thousand items
+    if (target < 4 * nt && total_units / (4 * nt) >= 1024) target = 4 * nt;
     if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {   // tuning / test override
       const long v = std::atol(ov);
       if (v > 0) target = v;
