@@ -456,3 +456,17 @@ def test_dequant_matvec_is_the_reconstruction_times_the_vector():
         e = np.zeros(8, np.float32)
         e[j] = 2.0
         assert np.array_equal(eq.dequant_matvec(q, 2, 8, p, eq.narrow(e, eq.F16)), 2.0 * W[:, j])
+
+
+def test_rounding_ties_go_to_the_even_level():
+    """Eq. 1 rounds to nearest; an exact tie goes to the even level (the reading taken for the
+    rounding operator).  Scale 2^-7 exactly (largest magnitude 7 * 2^-7, 4-bit symmetric), values
+    at every half level -7.0, -6.5, ..., 7.0: worked by hand, level + zero-point 7."""
+    half_levels = np.arange(-14, 15) / 2.0
+    x = np.zeros((1, 128), np.float32)
+    x[0, :29] = half_levels * 2.0 ** -7
+    q = eq.quantize_matrix(eq.narrow(x, eq.F16), eq.Params(bits=4, group_size=0, iters=0, n_sigma=float("inf")))
+    assert q["scales"][0, 0] == np.float32(2.0 ** -7)
+    expect = [0, 1, 1, 1, 2, 3, 3, 3, 4, 5, 5, 5, 6, 7, 7, 7, 8, 9, 9, 9, 10, 11, 11, 11, 12, 13, 13, 13, 14]
+    assert q["u"][0, :29].tolist() == expect
+    assert (q["u"][0, 29:] == 7).all()
