@@ -408,7 +408,8 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   hipLaunchKernelGGL(scan_row_counts, dim3(n), dim3(kThreads), 0, st, dmats);
   EQ_HIP(hipGetLastError());
   if (max_rows > 0) {
-    hipLaunchKernelGGL(gather_outliers, dim3((max_rows + kWaves - 1) / kWaves, n), dim3(kThreads), 0, st, dmats);
+    const int rows_per_block = kWaves * kGatherRows;
+    hipLaunchKernelGGL(gather_outliers, dim3((max_rows + rows_per_block - 1) / rows_per_block, n), dim3(kThreads), 0, st, dmats);
     EQ_HIP(hipGetLastError());
   }
   return EQ_OK;

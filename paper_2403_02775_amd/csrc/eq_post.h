@@ -50,19 +50,13 @@ __global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __res
   if (threadIdx.x == 0) md.out_row_ptr[md.rows] = running;
 }
 
-// Moves each row's run of outliers from the staging area (rows in arrival order, entries
-// within a run in any order) to its CSR position, sorted by column.  One wavefront per row;
-// blockIdx.y = matrix.  Columns are distinct, so the rank of an entry (the number of entries
-// of the run with a smaller column) is its position; a run has a few dozen entries.
-__global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats) {
-  const MatDesc md = mats[blockIdx.y];
-  const int64_t row = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
-  if (row >= md.rows || md.cols == 0) return;
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t cnt = md.row_count[row];
-  const uint32_t src = md.row_stage[row];
-  const uint32_t dst = md.out_row_ptr[row];
-  if (src == 0xFFFFFFFFu || (unsigned long long)dst + cnt > (unsigned long long)md.capacity) return;
+// Moves each row's staged run (arrival order) to its CSR position, sorted by column: the rank of
+// an entry is the number of entries of its row with a smaller column.  One wavefront takes
+// kGatherRows consecutive rows at a time with all their loads in flight together (a row's
+// bookkeeping, then its entries: two dependent round trips to memory per row otherwise).
+constexpr int kGatherRows = 4;
+
+__device__ __forceinline__ void gather_row_general(const MatDesc& md, uint32_t cnt, uint32_t src, uint32_t dst, uint32_t lane) {
   for (uint32_t e0 = 0; e0 < cnt; e0 += kWave) {
     const uint32_t e = e0 + lane;
     const bool have = e < cnt;
@@ -78,6 +72,44 @@ __global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __res
     if (have) {
       md.out_col[dst + rank] = col;
       md.out_val[dst + rank] = val;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats) {
+  const MatDesc md = mats[blockIdx.y];
+  const int64_t row0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kGatherRows;
+  if (row0 >= md.rows || md.cols == 0) return;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  uint32_t cnt[kGatherRows], src[kGatherRows], dst[kGatherRows];
+#pragma unroll
+  for (int r = 0; r < kGatherRows; ++r) {
+    const bool in = row0 + r < md.rows;
+    cnt[r] = in ? md.row_count[row0 + r] : 0u;
+    src[r] = in ? md.row_stage[row0 + r] : 0u;
+    dst[r] = in ? md.out_row_ptr[row0 + r] : 0u;
+    // a row that was not staged, or whose run does not fit the output arrays, is left out
+    if (src[r] == 0xFFFFFFFFu || (unsigned long long)dst[r] + cnt[r] > (unsigned long long)md.capacity) cnt[r] = 0;
+  }
+  uint32_t col[kGatherRows];
+  uint16_t val[kGatherRows];
+#pragma unroll
+  for (int r = 0; r < kGatherRows; ++r) {                 // rows of at most 64 entries: one entry per lane
+    const bool have = cnt[r] <= (uint32_t)kWave && lane < cnt[r];
+    col[r] = have ? md.st_col[src[r] + lane] : 0xFFFFFFFFu;
+    val[r] = have ? md.st_val[src[r] + lane] : (uint16_t)0;
+  }
+#pragma unroll
+  for (int r = 0; r < kGatherRows; ++r) {
+    if (cnt[r] > (uint32_t)kWave) {                        // uniform over the wavefront
+      gather_row_general(md, cnt[r], src[r], dst[r], lane);
+    } else if (cnt[r]) {
+      uint32_t rank = 0;
+      for (uint32_t j = 0; j < cnt[r]; ++j) rank += (uint32_t)__shfl((int)col[r], (int)j) < col[r] ? 1u : 0u;
+      if (lane < cnt[r]) {
+        md.out_col[dst[r] + rank] = col[r];
+        md.out_val[dst[r] + rank] = val[r];
+      }
     }
   }
 }
