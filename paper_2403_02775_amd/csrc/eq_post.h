@@ -67,7 +67,7 @@ __device__ __forceinline__ void gather_row_general(const MatDesc& md, uint32_t c
       const uint32_t f = f0 + lane;
       const uint32_t cf = f < cnt ? md.st_col[src + f] : 0xFFFFFFFFu;
       const int m = (int)min((uint32_t)kWave, cnt - f0);
-      for (int j = 0; j < m; ++j) rank += __shfl(cf, j) < col ? 1u : 0u;
+      for (int j = 0; j < m; ++j) rank += (uint32_t)__builtin_amdgcn_readlane((int)cf, j) < col ? 1u : 0u;
     }
     if (have) {
       md.out_col[dst + rank] = col;
@@ -91,24 +91,44 @@ __global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __res
     // a row that was not staged, or whose run does not fit the output arrays, is left out
     if (src[r] == 0xFFFFFFFFu || (unsigned long long)dst[r] + cnt[r] > (unsigned long long)md.capacity) cnt[r] = 0;
   }
-  uint32_t col[kGatherRows];
-  uint16_t val[kGatherRows];
+  // rows of at most 128 entries (two per lane): all loads of all rows first, then the ranks
+  constexpr uint32_t kFast = 2 * kWave;
+  uint32_t col[kGatherRows][2];
+  uint16_t val[kGatherRows][2];
 #pragma unroll
-  for (int r = 0; r < kGatherRows; ++r) {                 // rows of at most 64 entries: one entry per lane
-    const bool have = cnt[r] <= (uint32_t)kWave && lane < cnt[r];
-    col[r] = have ? md.st_col[src[r] + lane] : 0xFFFFFFFFu;
-    val[r] = have ? md.st_val[src[r] + lane] : (uint16_t)0;
+  for (int r = 0; r < kGatherRows; ++r) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t e = lane + (uint32_t)h * kWave;
+      const bool have = cnt[r] <= kFast && e < cnt[r];
+      col[r][h] = have ? md.st_col[src[r] + e] : 0xFFFFFFFFu;
+      val[r][h] = have ? md.st_val[src[r] + e] : (uint16_t)0;
+    }
   }
 #pragma unroll
   for (int r = 0; r < kGatherRows; ++r) {
-    if (cnt[r] > (uint32_t)kWave) {                        // uniform over the wavefront
+    if (cnt[r] > kFast) {                                  // uniform over the wavefront
       gather_row_general(md, cnt[r], src[r], dst[r], lane);
     } else if (cnt[r]) {
-      uint32_t rank = 0;
-      for (uint32_t j = 0; j < cnt[r]; ++j) rank += (uint32_t)__shfl((int)col[r], (int)j) < col[r] ? 1u : 0u;
+      uint32_t rank0 = 0, rank1 = 0;
+      const uint32_t n0 = min(cnt[r], (uint32_t)kWave);
+      for (uint32_t j = 0; j < n0; ++j) {
+        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)col[r][0], (int)j);     // j is uniform: no LDS traffic
+        rank0 += c < col[r][0] ? 1u : 0u;
+        rank1 += c < col[r][1] ? 1u : 0u;
+      }
+      for (uint32_t j = kWave; j < cnt[r]; ++j) {
+        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)col[r][1], (int)(j - kWave));
+        rank0 += c < col[r][0] ? 1u : 0u;
+        rank1 += c < col[r][1] ? 1u : 0u;
+      }
       if (lane < cnt[r]) {
-        md.out_col[dst[r] + rank] = col[r];
-        md.out_val[dst[r] + rank] = val[r];
+        md.out_col[dst[r] + rank0] = col[r][0];
+        md.out_val[dst[r] + rank0] = val[r][0];
+      }
+      if (lane + kWave < cnt[r]) {
+        md.out_col[dst[r] + rank1] = col[r][1];
+        md.out_val[dst[r] + rank1] = val[r][1];
       }
     }
   }
