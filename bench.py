@@ -202,6 +202,7 @@ def main():
     ap.add_argument("--layers", type=int, default=-1, help="limit the number of layers (debugging; changes the workload)")
     ap.add_argument("--iters", type=int, default=100, help="Adam steps T on the range")
     ap.add_argument("--lr", type=float, default=1e-3)
+    ap.add_argument("--bits", type=int, default=0, help="code width (default: the workload's, 4)")
     ap.add_argument("--group-size", type=int, default=128, help="0 = one range per output channel (secondary measurement)")
     ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
     ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the first matrix given to the CPU oracle (0 = skip)")
@@ -226,6 +227,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     Ws, names, bits, dt = build_workload(args.workload, args.layers, dev)
+    if args.bits:
+        bits = args.bits
     gp = eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=args.group_size, mode=eqg.EQ_SYMMETRIC,
                     stat_scope=eqg.EQ_STAT_ROW, n_sigma=3.0, iters=args.iters, lr=args.lr, select=eqg.EQ_SELECT_BEST)
     caps = [int(w.numel() * args.capacity_frac) for w in Ws]
