@@ -18,8 +18,8 @@
 //           threshold (<= 90 roundings of 2^-24 on quantities that are bounded through the
 //           guard mean^2 < variance, n >= 0.5), so those decisions equal the exact ones.
 //   exact : a row with an element inside that band, or that fails the guard (which also
-//           covers constant rows), is redone with the two-pass binary64 sums and decided
-//           element by element in binary64.
+//           covers constant rows), is redone from its pool copy with the two-pass binary64 sums
+//           and decided element by element in binary64.
 #pragma once
 
 #include "eq_common.h"
@@ -68,7 +68,8 @@ __device__ __forceinline__ void batch_issue_loads(const MatDesc& md, int64_t row
   }
 }
 
-// Everything after the loads (v = what batch_issue_loads returned for the same rows).
+// Everything after the loads (v = what batch_issue_loads returned for the same rows).  v is read
+// up to the per-chunk outlier test; everything after that works on the pool copy.
 template <int DT, int NT, int RB, int K, class Layout>
 __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
                                                   unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc,
@@ -217,10 +218,13 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
         double s = 0.0;
 #pragma unroll
         for (int i = 0; i < K; ++i) {
-          float x[8];
-          chunk_floats<DT>(v[r][i], x);
+          const uint32_t ch = (uint32_t)i * NT + tid;
+          if (ch < nchunks) {
+            float x[8];
+            chunk_floats<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), x);
 #pragma unroll
-          for (int k = 0; k < 8; ++k) s += (double)x[k];     // absent chunks hold zeros
+            for (int k = 0; k < 8; ++k) s += (double)x[k];
+          }
         }
         mu = block_sum(s, sc->dred) / cnt;
         double q = 0.0;
@@ -229,7 +233,7 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
           const uint32_t ch = (uint32_t)i * NT + tid;
           if (ch < nchunks) {
             float x[8];
-            chunk_floats<DT>(v[r][i], x);
+            chunk_floats<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), x);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
               const double dd = (double)x[k] - mu;
@@ -250,7 +254,9 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
 #pragma unroll
       for (int i = 0; i < K; ++i) {
         const uint32_t ch = (uint32_t)i * NT + tid;
-        const uint32_t mm = (ch < nchunks && sigma > 0.0) ? chunk_mask<DT>(v[r][i], mu, thr) : 0u;
+        const uint32_t mm = (ch < nchunks && sigma > 0.0)
+                                ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), mu, thr)
+                                : 0u;
         n_out += __popc(mm);
         if (mm) cand |= 1u << (r * K + i);
         else cand &= ~(1u << (r * K + i));
