@@ -180,19 +180,17 @@ __device__ __forceinline__ void slot_min_max(const unsigned char* slot, float& v
   vmax = 0.0f;
   if (DT == EQ_F16) {
     // packed fp16 min / max over the pairs (exact: they only select), widened once at the end
-    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-    half2_t mn = {(_Float16)0.0f, (_Float16)0.0f}, mx = mn;
+    uint32_t mnb = 0u, mxb = 0u;
 #pragma unroll
     for (int ch = 0; ch < 16; ++ch) {
       const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const half2_t h = __builtin_bit_cast(half2_t, w[j]);
-        mn = __builtin_elementwise_min(mn, h);
-        mx = __builtin_elementwise_max(mx, h);
-      }
+      const uint32_t lo4 = pk_min_f16(pk_min_f16(v.x, v.y), pk_min_f16(v.z, v.w));
+      const uint32_t hi4 = pk_max_f16(pk_max_f16(v.x, v.y), pk_max_f16(v.z, v.w));
+      mnb = pk_min_f16(mnb, lo4);
+      mxb = pk_max_f16(mxb, hi4);
     }
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    const half2_t mn = __builtin_bit_cast(half2_t, mnb), mx = __builtin_bit_cast(half2_t, mxb);
     vmin = fminf((float)mn.x, (float)mn.y);
     vmax = fmaxf((float)mx.x, (float)mx.y);
   } else {

@@ -22,6 +22,8 @@
 //           and decided element by element in binary64.
 #pragma once
 
+#include <type_traits>
+
 #include "eq_common.h"
 #include "eq_rowstage.h"
 
@@ -39,6 +41,68 @@ struct BatchScratch {
   uint32_t rowpos[RB];               // next free entry of the row's run while it is written
   uint32_t slow[RB];                 // row takes the exact path
 };
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bfloat2_t __attribute__((ext_vector_type(2)));
+
+// Packed 16-bit floating-point minimum / maximum as single instructions (the generic minimum
+// of the language first quiets a signalling NaN of each operand, one more instruction apiece;
+// rows with a NaN are flagged and their results are unspecified anyway).
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// s1 += x0 + x1, s2 += x0^2 + x1^2 for the two 16-bit values of w, one packed dot-product
+// instruction each, accumulating in binary32.  Measured on gfx950 against exact sums: the
+// result is within 3 * 2^-24 of the largest of its three terms; a subnormal binary16 operand
+// is not flushed, its product carries a relative error of up to 2^-18 of that product.
+template <int DT>
+__device__ __forceinline__ void pair_sums(uint32_t w, float& s1, float& s2) {
+  if (DT == EQ_F16) {
+    const half2_t h = __builtin_bit_cast(half2_t, w);
+    const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+    s1 = __builtin_amdgcn_fdot2(h, ones, s1, false);
+    s2 = __builtin_amdgcn_fdot2(h, h, s2, false);
+  } else {
+    const bfloat2_t h = __builtin_bit_cast(bfloat2_t, w);
+    const bfloat2_t ones = __builtin_bit_cast(bfloat2_t, 0x3F803F80u);
+    s1 = __builtin_amdgcn_fdot2_f32_bf16(h, ones, s1, false);
+    s2 = __builtin_amdgcn_fdot2_f32_bf16(h, h, s2, false);
+  }
+}
+
+// Sum over the wavefront by data-parallel primitives; lane 63 holds the total.
+__device__ __forceinline__ float wave_sum_to_last(float v) {
+  auto step = [&](auto ctrl, auto rows) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                                                 decltype(rows)::value, 0xF, true));
+  };
+  step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xF>{});   // row_shr:1
+  step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xF>{});   // row_shr:2
+  step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xF>{});   // row_shr:4
+  step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xF>{});   // row_shr:8
+  step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});   // row_bcast:15 -> rows 1, 3
+  step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});   // row_bcast:31 -> rows 2, 3
+  return v;
+}
+
+// Largest binary16 value strictly below the binary32 value b, and smallest strictly above.
+__device__ __forceinline__ uint32_t f16_below(float b) {
+  uint32_t h = (uint32_t)__half_as_ushort(__float2half_rn(b));
+  if (!(__half2float(__ushort_as_half((unsigned short)h)) < b)) {
+    if ((h & 0x7FFFu) == 0u) h = 0x8001u;           // below zero: the smallest negative subnormal
+    else h = (h & 0x8000u) ? h + 1u : h - 1u;
+  }
+  return h;
+}
+__device__ __forceinline__ uint32_t f16_above(float b) { return f16_below(-b) ^ 0x8000u; }
 
 template <int DT>
 __device__ __forceinline__ void chunk_floats(const uint4 v, float (&x)[8]) {
@@ -89,22 +153,19 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   bool bad = false;
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
-    float s1 = 0.0f, s2 = 0.0f;
+    float s1 = 0.0f, s2 = 0.0f, t1 = 0.0f, t2 = 0.0f;   // two chains each
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      float x[8];
-      chunk_floats<DT>(v[r][i], x);
-      // pairwise within the chunk: short dependency chains (a dependent instruction cannot issue
-      // back to back), and fewer roundings along any path than a running sum
-      const float a01 = x[0] + x[1], a23 = x[2] + x[3], a45 = x[4] + x[5], a67 = x[6] + x[7];
-      const float q01 = __builtin_fmaf(x[1], x[1], x[0] * x[0]), q23 = __builtin_fmaf(x[3], x[3], x[2] * x[2]);
-      const float q45 = __builtin_fmaf(x[5], x[5], x[4] * x[4]), q67 = __builtin_fmaf(x[7], x[7], x[6] * x[6]);
-      s1 += (a01 + a23) + (a45 + a67);
-      s2 += (q01 + q23) + (q45 + q67);
+      pair_sums<DT>(v[r][i].x, s1, s2);
+      pair_sums<DT>(v[r][i].y, t1, t2);
+      pair_sums<DT>(v[r][i].z, s1, s2);
+      pair_sums<DT>(v[r][i].w, t1, t2);
       const uint32_t ch = (uint32_t)i * NT + tid;
       if (r < nrows && ch < nchunks)
         *reinterpret_cast<uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)) = v[r][i];
     }
+    s1 += t1;
+    s2 += t2;
     // An Inf or NaN makes the sum of squares non-finite; only then look at the elements (for
     // bf16 a huge finite value can overflow the square too, so the sum alone does not decide).
     if (!(s2 < __builtin_inff())) {
@@ -115,12 +176,9 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
         for (int k = 0; k < 4; ++k) bad = bad || nonfinite16<DT>(w[k] & 0xFFFFu) || nonfinite16<DT>(w[k] >> 16);
       }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      s1 += __shfl_xor(s1, o);
-      s2 += __shfl_xor(s2, o);
-    }
-    if (lane == 0) {
+    s1 = wave_sum_to_last(s1);
+    s2 = wave_sum_to_last(s2);
+    if (lane == kWave - 1) {
       sc->part[r][wave][0] = s1;
       sc->part[r][wave][1] = s2;
     }
@@ -128,13 +186,13 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   if (__any(bad) && lane == 0) global_atomic_or(md.status, EQ_S_NONFINITE);
   __syncthreads();
 
-  // ---- thresholds; one test per chunk: can any of its elements be an outlier? ----
+  // ---- thresholds: lane r of every wavefront works out row r, all lanes get them as scalars ----
   const double cnt = (double)md.cols;
-  const float rcnt = 1.0f / (float)md.cols;
   float mu_f[RB], thr_lo[RB], thr_hi[RB];
-  uint32_t cand = 0;                      // bit r * K + i: chunk i of row r needs a look
-#pragma unroll
-  for (int r = 0; r < RB; ++r) {
+  uint32_t cand_hi[RB], cand_lo[RB];      // binary16 pairs: a value beyond one of them may be an outlier
+  uint32_t slow_rows;                     // bit r: row r takes the exact path
+  {
+    const uint32_t r = lane < (uint32_t)RB ? lane : 0u;
     float S1 = 0.0f, S2 = 0.0f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
@@ -149,28 +207,58 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
       slow = true;                        // the matrix-wide statistics are exact: decide every element exactly
     } else {
       // binary32 throughout: a dozen more roundings of 2^-24 on top of those of the sums
+      const float rcnt = 1.0f / (float)md.cols;
       mu = S1 * rcnt;
       const float ms = S2 * rcnt;         // mean square = variance + mean^2
       const float var = ms - mu * mu;
-      slow = !(var + var > ms) || kp.n < 0.5;   // mean^2 >= variance, a constant row, NaN; or a threshold so
-                                                 // small that the error of the mean is not negligible against it
+      // exact path: mean^2 >= variance, a constant row, NaN; a threshold so small that the error of
+      // the mean is not negligible against it; a row of (mostly) subnormal binary16 values
+      slow = !(var + var > ms) || kp.n < 0.5 || !(ms >= 1.0e-8f);
       thr = (float)kp.n * __builtin_sqrtf(fmaxf(var, 0.0f));
     }
-    mu_f[r] = mu;
-    thr_lo[r] = thr * (1.0f - kBand);
-    thr_hi[r] = thr * (1.0f + kBand);
-    if (slow) {
-      if (r < nrows) sc->slow[r] = 1u;    // benign race: every writer stores 1
-    } else {
+    const float lo = thr * (1.0f - kBand), hi = thr * (1.0f + kBand);
+    // chunk test for binary16 rows: bounds strictly inside mean +- lo * (1 - 2^-10), the margin
+    // covering the roundings of this sum and of |x - mean| in the candidate loop
+    const float inner = lo * (1.0f - 0x1p-10f);
+    const uint32_t bh = DT == EQ_F16 ? f16_below(mu + inner) : 0u, bl = DT == EQ_F16 ? f16_above(mu - inner) : 0u;
+    const uint32_t sb = (uint32_t)__ballot(slow && lane < (uint32_t)nrows);
+    slow_rows = sb & ((1u << RB) - 1u);
+#pragma unroll
+    for (int rr = 0; rr < RB; ++rr) {
+      mu_f[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mu), rr));
+      thr_lo[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lo), rr));
+      thr_hi[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hi), rr));
+      if (DT == EQ_F16) {
+        cand_hi[rr] = (uint32_t)__builtin_amdgcn_readlane((int)(bh | (bh << 16)), rr);
+        cand_lo[rr] = (uint32_t)__builtin_amdgcn_readlane((int)(bl | (bl << 16)), rr);
+      }
+    }
+  }
+  if (lane < (uint32_t)RB && ((slow_rows >> lane) & 1u)) sc->slow[lane] = 1u;   // benign race: every writer stores 1
+
+  // ---- one test per chunk: can any of its elements be an outlier? ----
+  uint32_t cand = 0;                      // bit r * K + i: chunk i of row r needs a look
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    if (!((slow_rows >> r) & 1u)) {
 #pragma unroll
       for (int i = 0; i < K; ++i) {
-        float x[8];
-        chunk_floats<DT>(v[r][i], x);
-        float dmax = 0.0f;
+        bool maybe;
+        if (DT == EQ_F16) {
+          const uint32_t mx = pk_max_f16(pk_max_f16(v[r][i].x, v[r][i].y), pk_max_f16(v[r][i].z, v[r][i].w));
+          const uint32_t mn = pk_min_f16(pk_min_f16(v[r][i].x, v[r][i].y), pk_min_f16(v[r][i].z, v[r][i].w));
+          // max(mx, bound) differs from the bound exactly when a half of mx lies above it
+          maybe = ((pk_max_f16(mx, cand_hi[r]) ^ cand_hi[r]) | (pk_min_f16(mn, cand_lo[r]) ^ cand_lo[r])) != 0u;
+        } else {
+          float x[8];
+          chunk_floats<DT>(v[r][i], x);
+          float dmax = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) dmax = fmaxf(dmax, fabsf(x[k] - mu_f[r]));
+          for (int k = 0; k < 8; ++k) dmax = fmaxf(dmax, fabsf(x[k] - mu_f[r]));
+          maybe = dmax >= thr_lo[r];
+        }
         const uint32_t ch = (uint32_t)i * NT + tid;
-        if (r < nrows && ch < nchunks && dmax >= thr_lo[r]) cand |= 1u << (r * K + i);
+        if (r < nrows && ch < nchunks && maybe) cand |= 1u << (r * K + i);
       }
     }
   }

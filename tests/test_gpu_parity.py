@@ -209,6 +209,11 @@ def test_extreme_magnitudes_and_degenerate_rows(G, iters):
     Wh[1, 100] = 65504.0
     Wh[2] = 6e-8                            # the smallest subnormal
     Wh[3, :128] = 0
+    # rows at and around the subnormal range of fp16 (below 6.1e-5), with outliers: mostly subnormal
+    # (exact statistics), a mixture on the fast statistics, and just above
+    for r, sigma in ((4, 3e-5), (5, 1.5e-4), (6, 6e-4)):
+        Wh[r] = (torch.randn((cols,), device=DEV, generator=g) * sigma).to(torch.float16)
+        Wh[r, 17::500] = 9.0 * sigma
     res = _check(Wh, eqo.Params(bits=4, group_size=G, iters=iters), f"fp16 extremes G={G} T={iters}")
     assert res["excused_elems"] == 0
     res = _check(Wh, eqo.Params(bits=4, group_size=G, iters=iters, n_sigma=1.0), f"fp16 extremes, n = 1, G={G} T={iters}")
