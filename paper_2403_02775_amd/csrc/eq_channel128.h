@@ -25,8 +25,8 @@ namespace eq {
 
 constexpr int kChanThreads = 256;
 constexpr int kChanMaxRows = 16;     // rows per round (rows shorter than 2048 go to the general kernel)
-constexpr int kChanHeader = 5120;    // LDS in front of the pool: staging scratch, then ChanScratch
-constexpr int kChanScratchOff = 2048;
+constexpr int kChanHeader = 7168;    // LDS in front of the pool: staging scratch, then ChanScratch
+constexpr int kChanScratchOff = 4096;
 
 struct RowAcc {
   uint32_t max_bits, negmin_bits;    // bit patterns of max(x, 0) and max(-x, 0) over the row
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
     const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
   constexpr int NT = kChanThreads;
   constexpr int RB = 16 / K;
-  typedef BatchScratch<RB> Scratch;
+  typedef BatchScratch<RB, NT / kWave> Scratch;
   static_assert(sizeof(Scratch) <= kChanScratchOff, "staging scratch overlaps the row accumulators");
   extern __shared__ __align__(16) unsigned char smem[];
   Scratch* sc = reinterpret_cast<Scratch*>(smem);

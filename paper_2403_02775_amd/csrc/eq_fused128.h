@@ -32,7 +32,7 @@ constexpr int kPairs = kG / 2;
 constexpr int kSlotBytes = 272;       // 256 B of data + 16 B of padding (bank spread)
 constexpr int kSlotChunks = 17;
 constexpr int kCodeOff = 128;         // packed codes are assembled in the upper half of the slot
-constexpr int kLdsHeader = 2560;      // scratch of the row staging, in front of the pool
+constexpr int kLdsHeader = 6144;      // scratch of the row staging, in front of the pool
 
 struct WorkItem {
   int32_t mat, row0, nrows, pad_;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                                                               const WorkItem* __restrict__ items, KParams kp,
                                                               uint32_t pool_slots) {
   constexpr int RB = 16 / K;
-  typedef BatchScratch<RB> Scratch;
+  typedef BatchScratch<RB, NT / kWave> Scratch;
   static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
   extern __shared__ __align__(16) unsigned char smem[];
   Scratch* sc = reinterpret_cast<Scratch*>(smem);

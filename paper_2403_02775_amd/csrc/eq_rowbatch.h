@@ -31,15 +31,19 @@ namespace eq {
 
 constexpr float kBand = 1.0e-4f;
 
-template <int RB>
+constexpr int kQueue = 128;          // candidate chunks a wavefront can queue per batch
+
+template <int RB, int NW>
 struct BatchScratch {
-  float part[RB][kMaxWaves][2];      // per wavefront: sum x, sum x^2 of each row
+  float part[RB][NW][2];             // per wavefront: sum x, sum x^2 of each row
   double dred[kMaxWaves];
   double mu[RB], thr[RB];            // exact mean and n*sigma of the rows that were redone
   unsigned long long rowbase[RB];    // staging position of the row, ~0 when it does not fit
+  float4 fast[RB];                   // fast mean, lower and upper end of the band around n*sigma
   uint32_t rowcnt[RB];               // outliers of the row
   uint32_t rowpos[RB];               // next free entry of the row's run while it is written
   uint32_t slow[RB];                 // row takes the exact path
+  uint32_t queue[NW][kQueue];        // per wavefront: row << 16 | chunk of its candidate chunks
 };
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -93,6 +97,20 @@ __device__ __forceinline__ float wave_sum_to_last(float v) {
   return v;
 }
 
+// Inclusive prefix sum over the wavefront (same steps as above: they form a scan).
+__device__ __forceinline__ uint32_t wave_scan_inclusive(uint32_t v) {
+  auto step = [&](auto ctrl, auto rows) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, decltype(ctrl)::value, decltype(rows)::value, 0xF, true);
+  };
+  step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xF>{});
+  step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xF>{});
+  step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xF>{});
+  step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xF>{});
+  step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});
+  step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});
+  return v;
+}
+
 // Largest binary16 value strictly below the binary32 value b, and smallest strictly above.
 __device__ __forceinline__ uint32_t f16_below(float b) {
   uint32_t h = (uint32_t)__half_as_ushort(__float2half_rn(b));
@@ -136,7 +154,7 @@ __device__ __forceinline__ void batch_issue_loads(const MatDesc& md, int64_t row
 // up to the per-chunk outlier test; everything after that works on the pool copy.
 template <int DT, int NT, int RB, int K, class Layout>
 __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
-                                                  unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc,
+                                                  unsigned char* pool, uint32_t ch0, BatchScratch<RB, NT / kWave>* sc,
                                                   const uint4 (&v)[RB][K]) {
   static_assert(RB * K <= 32, "candidate flags are one 32-bit word");
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
@@ -188,8 +206,8 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
 
   // ---- thresholds: lane r of every wavefront works out row r, all lanes get them as scalars ----
   const double cnt = (double)md.cols;
-  float mu_f[RB], thr_lo[RB], thr_hi[RB];
-  uint32_t cand_hi[RB], cand_lo[RB];      // binary16 pairs: a value beyond one of them may be an outlier
+  float mu_f[RB], thr_lo[RB];             // bf16 rows: fast mean and lower end of the band
+  uint32_t cand_hi[RB], cand_lo[RB];      // fp16 rows: binary16 pairs, a value beyond one of them may be an outlier
   uint32_t slow_rows;                     // bit r: row r takes the exact path
   {
     const uint32_t r = lane < (uint32_t)RB ? lane : 0u;
@@ -217,20 +235,22 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
       thr = (float)kp.n * __builtin_sqrtf(fmaxf(var, 0.0f));
     }
     const float lo = thr * (1.0f - kBand), hi = thr * (1.0f + kBand);
+    // every wavefront stores the same bits, and reads them back itself: no barrier needed
+    if (lane < (uint32_t)RB) sc->fast[lane] = make_float4(mu, lo, hi, 0.0f);
     // chunk test for binary16 rows: bounds strictly inside mean +- lo * (1 - 2^-10), the margin
-    // covering the roundings of this sum and of |x - mean| in the candidate loop
+    // covering the roundings of this sum and of |x - mean| in the candidate pass
     const float inner = lo * (1.0f - 0x1p-10f);
     const uint32_t bh = DT == EQ_F16 ? f16_below(mu + inner) : 0u, bl = DT == EQ_F16 ? f16_above(mu - inner) : 0u;
     const uint32_t sb = (uint32_t)__ballot(slow && lane < (uint32_t)nrows);
     slow_rows = sb & ((1u << RB) - 1u);
 #pragma unroll
     for (int rr = 0; rr < RB; ++rr) {
-      mu_f[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mu), rr));
-      thr_lo[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lo), rr));
-      thr_hi[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, hi), rr));
       if (DT == EQ_F16) {
         cand_hi[rr] = (uint32_t)__builtin_amdgcn_readlane((int)(bh | (bh << 16)), rr);
         cand_lo[rr] = (uint32_t)__builtin_amdgcn_readlane((int)(bl | (bl << 16)), rr);
+      } else {
+        mu_f[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mu), rr));
+        thr_lo[rr] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lo), rr));
       }
     }
   }
@@ -263,35 +283,59 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
     }
   }
 
-  // ---- candidates, one per iteration: count the outliers, notice borderline elements ----
-  {
-    uint32_t todo = cand;
-    while (__any(todo != 0)) {
-      if (todo) {
+  // Runs body(row, chunk) once for every candidate chunk of the wavefront.  The lanes that found
+  // candidates found different numbers of them, so the chunks are first queued (row << 16 | chunk,
+  // in lane order) and then dealt out evenly, one per lane and pass over the queue.  A wavefront
+  // with more candidates than the queue holds lets every lane work through its own instead.
+  auto for_each_candidate = [&](auto&& body) {
+    const uint32_t mine = (uint32_t)__popc(cand);
+    const uint32_t upto = wave_scan_inclusive(mine);
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)upto, kWave - 1);
+    if (total <= (uint32_t)kQueue) {
+      uint32_t todo = cand, k = upto - mine;
+      while (todo) {
         const int slot = __ffs((int)todo) - 1;
         todo &= todo - 1;
         const int r = slot / K, i = slot - r * K;
-        const uint32_t ch = (uint32_t)i * NT + tid;
-        const uint4 c = *reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch));
-        float x[8];
-        chunk_floats<DT>(c, x);
-        float mf = 0.0f, lo = 0.0f, hi = 0.0f;
-#pragma unroll
-        for (int rr = 0; rr < RB; ++rr)
-          if (rr == r) { mf = mu_f[rr]; lo = thr_lo[rr]; hi = thr_hi[rr]; }
-        uint32_t n_out = 0;
-        bool border = false;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const float d = fabsf(x[k] - mf);
-          n_out += d >= hi ? 1u : 0u;
-          border = border || (d >= lo && d < hi);
+        sc->queue[wave][k++] = ((uint32_t)r << 16) | ((uint32_t)i * NT + tid);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      for (uint32_t e = lane; e < total; e += kWave) {
+        const uint32_t id = sc->queue[wave][e];
+        body(id >> 16, id & 0xFFFFu);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    } else {
+      uint32_t todo = cand;
+      while (__any(todo != 0)) {
+        if (todo) {
+          const int slot = __ffs((int)todo) - 1;
+          todo &= todo - 1;
+          const int r = slot / K, i = slot - r * K;
+          body((uint32_t)r, (uint32_t)i * NT + tid);
         }
-        if (border) sc->slow[r] = 1u;
-        if (n_out) atomicAdd(&sc->rowcnt[r], n_out);
       }
     }
-  }
+  };
+
+  // ---- candidates: count the outliers, notice borderline elements ----
+  for_each_candidate([&](uint32_t r, uint32_t ch) {
+    const uint4 c = *reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + r * nchunks + ch));
+    const float4 f = sc->fast[r];         // mean, lower and upper end of the band
+    float x[8];
+    chunk_floats<DT>(c, x);
+    uint32_t n_lo = 0, n_hi = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float d = fabsf(x[k] - f.x);
+      n_lo += d >= f.y ? 1u : 0u;
+      n_hi += d >= f.z ? 1u : 0u;
+    }
+    if (n_lo != n_hi) sc->slow[r] = 1u;   // an element inside the band
+    if (n_hi) atomicAdd(&sc->rowcnt[r], n_hi);
+  });
   __syncthreads();
 
   // ---- exact statistics and counts of the rows that asked for them (uniform branch per row) ----
@@ -373,53 +417,41 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   __syncthreads();
 
   // ---- candidates again: write (column, raw value), zero the pool copy ----
-  {
-    uint32_t todo = cand;
-    while (__any(todo != 0)) {
-      if (todo) {
-        const int slot = __ffs((int)todo) - 1;
-        todo &= todo - 1;
-        const int r = slot / K, i = slot - r * K;
-        const uint32_t ch = (uint32_t)i * NT + tid;
-        unsigned char* cp = pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch);
-        const uint4 c = *reinterpret_cast<const uint4*>(cp);
-        uint32_t mm = 0;
-        if (sc->slow[r]) {
-          mm = chunk_mask<DT>(c, sc->mu[r], sc->thr[r]);
-        } else {
-          float x[8];
-          chunk_floats<DT>(c, x);
-          float mf = 0.0f, hi = 0.0f;
+  for_each_candidate([&](uint32_t r, uint32_t ch) {
+    unsigned char* cp = pool + Layout::off(ch0 + r * nchunks + ch);
+    const uint4 c = *reinterpret_cast<const uint4*>(cp);
+    uint32_t mm = 0;
+    if (sc->slow[r]) {
+      mm = chunk_mask<DT>(c, sc->mu[r], sc->thr[r]);
+    } else {
+      const float4 f = sc->fast[r];
+      float x[8];
+      chunk_floats<DT>(c, x);
 #pragma unroll
-          for (int rr = 0; rr < RB; ++rr)
-            if (rr == r) { mf = mu_f[rr]; hi = thr_hi[rr]; }
-#pragma unroll
-          for (int k = 0; k < 8; ++k) mm |= (fabsf(x[k] - mf) >= hi ? 1u : 0u) << k;
+      for (int k = 0; k < 8; ++k) mm |= (fabsf(x[k] - f.x) >= f.z ? 1u : 0u) << k;
+    }
+    if (mm) {
+      const unsigned long long base = sc->rowbase[r];
+      unsigned long long pos = base + atomicAdd(&sc->rowpos[r], (uint32_t)__popc(mm));
+      unsigned short* e = reinterpret_cast<unsigned short*>(cp);
+      while (mm) {
+        const int j = __ffs((int)mm) - 1;
+        mm &= mm - 1;
+        if (base != ~0ull) {
+          md.st_col[pos] = ch * 8u + (uint32_t)j;
+          md.st_val[pos] = e[j];
         }
-        if (mm) {
-          const unsigned long long base = sc->rowbase[r];
-          unsigned long long pos = base + atomicAdd(&sc->rowpos[r], (uint32_t)__popc(mm));
-          unsigned short* e = reinterpret_cast<unsigned short*>(cp);
-          while (mm) {
-            const int j = __ffs((int)mm) - 1;
-            mm &= mm - 1;
-            if (base != ~0ull) {
-              md.st_col[pos] = ch * 8u + (uint32_t)j;
-              md.st_val[pos] = e[j];
-            }
-            ++pos;
-            e[j] = 0;
-          }
-        }
+        ++pos;
+        e[j] = 0;
       }
     }
-  }
+  });
   __syncthreads();
 }
 
 template <int DT, int NT, int RB, int K, class Layout>
 __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
-                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB>* sc) {
+                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB, NT / kWave>* sc) {
   uint4 v[RB][K];
   batch_issue_loads<NT, RB, K>(md, row0, nrows, v);     // every load of the batch in flight
   stage_loaded_rows<DT, NT, RB, K, Layout>(md, kp, row0, nrows, pool, ch0, sc, v);

@@ -20,7 +20,7 @@ template <int DT, int NT, int K>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_rtn128(
     const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
   constexpr int RB = 16 / K;
-  typedef BatchScratch<RB> Scratch;
+  typedef BatchScratch<RB, NT / kWave> Scratch;
   static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
   extern __shared__ __align__(16) unsigned char smem[];
   Scratch* sc = reinterpret_cast<Scratch*>(smem);

@@ -220,6 +220,17 @@ def test_extreme_magnitudes_and_degenerate_rows(G, iters):
     assert res["excused_elems"] == 0
 
 
+@pytest.mark.parametrize("n_sigma", [2.6, 2.2, 1.5])
+def test_candidate_queue_fill_levels(n_sigma):
+    # the staging deals a wavefront's candidate chunks out over its lanes through a queue of 128
+    # entries: thresholds that give roughly 110 (two passes over the queue), 250 and 700 (more than
+    # it holds: every lane works through its own) candidate chunks per wavefront and batch
+    W = eq_inputs.gen_matrix(20, 8192, eq_inputs.RECIPES["c5"], seed=41, device=DEV)
+    for G, iters in ((128, 0), (128, 3), (0, 3)):
+        res = _check(W, eqo.Params(bits=4, group_size=G, iters=iters, n_sigma=n_sigma), f"queue n={n_sigma} G={G} T={iters}")
+        assert res["excused_elems"] == 0
+
+
 def test_bf16_and_student_t_inputs():
     W = eq_inputs.gen_matrix(40, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c3"], "bf16"), seed=3, device=DEV)
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=50)
