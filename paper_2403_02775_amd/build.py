@@ -14,6 +14,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                      # the arithmetic contract: no fused multiply-add is formed
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # atomics are issued by single lanes here; the compiler's wave-level rewrite of them would
+    # wait for the returned value at once instead of where it is used
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-fvisibility=hidden", "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -211,6 +211,9 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
       lc.kind = 3;
       lc.threads = c > 8192 ? 512 : 256;
+      if (const char* ov = std::getenv("EASYQUANT_RTN_THREADS")) {
+        if (std::atol(ov) == 128 && c <= 8192) lc.threads = 128;
+      }
       const int64_t per_thread = (c / 8 + lc.threads - 1) / lc.threads;
       lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : 8;
       if (lc.threads == 512 && lc.chunks_per_thread < 4) lc.chunks_per_thread = 4;
@@ -375,6 +378,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
     };                                                                                                          \
   }
     if (lc.kind == 3) {
+      EQ_RTN_VARIANT(128, 1) EQ_RTN_VARIANT(128, 2) EQ_RTN_VARIANT(128, 4) EQ_RTN_VARIANT(128, 8)
       EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
     } else if (lc.kind == 2) {
       EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)

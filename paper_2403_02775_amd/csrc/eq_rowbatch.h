@@ -151,11 +151,13 @@ __device__ __forceinline__ void batch_issue_loads(const MatDesc& md, int64_t row
 }
 
 // Everything after the loads (v = what batch_issue_loads returned for the same rows).  v is read
-// up to the per-chunk outlier test; everything after that works on the pool copy.
-template <int DT, int NT, int RB, int K, class Layout>
+// up to the per-chunk outlier test; everything after that works on the pool copy, and
+// `after_reservation_issued()` (called once by every thread, later than the last use of v) may
+// overwrite v.
+template <int DT, int NT, int RB, int K, class Layout, class Hook>
 __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
                                                   unsigned char* pool, uint32_t ch0, BatchScratch<RB, NT / kWave>* sc,
-                                                  const uint4 (&v)[RB][K]) {
+                                                  const uint4 (&v)[RB][K], Hook&& after_reservation_issued) {
   static_assert(RB * K <= 32, "candidate flags are one 32-bit word");
   const uint32_t nchunks = (uint32_t)md.cols >> 3;
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -399,22 +401,36 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   __syncthreads();
 
   // ---- one reservation for the batch ----
+  // Thread 0 issues the atomic, the caller's hook runs (the T = 0 kernel starts the loads of its
+  // next batch there: v is dead by now, and loads issued after the atomic do not delay its
+  // return, which is awaited by count), then thread 0 hands out the rows' positions.
+  uint32_t total = 0;
+  unsigned long long b = 0;
   if (tid == 0) {
-    uint32_t total = 0;
     for (int r = 0; r < nrows; ++r) total += sc->rowcnt[r];
-    unsigned long long b = 0;
     if (total) b = global_atomic_add(md.cursor, (unsigned long long)total);
-    for (int r = 0; r < nrows; ++r) {
-      const uint32_t t = sc->rowcnt[r];
-      const bool fits = b + t <= (unsigned long long)md.capacity;
-      md.row_count[row0 + r] = t;
-      md.row_stage[row0 + r] = fits ? (uint32_t)b : 0xFFFFFFFFu;
-      if (!fits) global_atomic_or(md.status, EQ_S_OUTLIER_OVERFLOW);
-      sc->rowbase[r] = fits ? b : ~0ull;
-      b += t;
+  }
+  after_reservation_issued();
+  if (tid == 0) {
+    // unrolled on purpose (in front of a loop the compiler would wait for every outstanding load),
+    // and nothing but LDS stores after the first use of b (each later global store would move the
+    // count that the wait for b is expressed in)
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      if (r < nrows) {
+        const uint32_t t = sc->rowcnt[r];
+        sc->rowbase[r] = b + t <= (unsigned long long)md.capacity ? b : ~0ull;
+        b += t;
+      }
     }
   }
   __syncthreads();
+  if (tid < (uint32_t)nrows) {
+    const unsigned long long base = sc->rowbase[tid];
+    md.row_count[row0 + tid] = sc->rowcnt[tid];
+    md.row_stage[row0 + tid] = base != ~0ull ? (uint32_t)base : 0xFFFFFFFFu;
+    if (base == ~0ull) global_atomic_or(md.status, EQ_S_OUTLIER_OVERFLOW);
+  }
 
   // ---- candidates again: write (column, raw value), zero the pool copy ----
   for_each_candidate([&](uint32_t r, uint32_t ch) {
@@ -454,7 +470,7 @@ __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParam
                                                  unsigned char* pool, uint32_t ch0, BatchScratch<RB, NT / kWave>* sc) {
   uint4 v[RB][K];
   batch_issue_loads<NT, RB, K>(md, row0, nrows, v);     // every load of the batch in flight
-  stage_loaded_rows<DT, NT, RB, K, Layout>(md, kp, row0, nrows, pool, ch0, sc, v);
+  stage_loaded_rows<DT, NT, RB, K, Layout>(md, kp, row0, nrows, pool, ch0, sc, v, [] {});
 }
 
 }  // namespace eq

@@ -1,12 +1,11 @@
 // Zero optimisation steps (iters = 0): outlier isolation followed by round-to-nearest at the
 // initial range (Algorithm 1 without its second step), group size 128.
 //
-// This end of the path is bound by HBM, not by arithmetic, so the kernel is organised around
-// keeping loads in flight: while a workgroup takes one batch of rows through statistics,
-// outlier compaction (eq_rowbatch.h) and code emission, the 128-bit loads of its next batch
-// are already under way into a second set of registers.  Emission is the unit-per-lane scheme
-// of eq_fused128.h (the transposition through the padded LDS slots makes both the HBM reads
-// and the code writes fully coalesced), one round per batch, nothing carried over.
+// A workgroup takes one batch of rows at a time through statistics, outlier compaction
+// (eq_rowbatch.h) and code emission; the 128-bit loads of its next batch start as soon as the
+// registers that held this one are free.  Emission is the unit-per-lane scheme of
+// eq_fused128.h (the transposition through the padded LDS slots makes both the HBM reads and
+// the code writes fully coalesced), one round per batch, nothing carried over.
 #pragma once
 
 #include "eq_fused128.h"
@@ -32,8 +31,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   const int64_t row_end = (int64_t)it.row0 + it.nrows;
 
   auto rows_at = [&](int64_t row) { return (int)max((int64_t)0, min((int64_t)RB, row_end - row)); };
-  auto finish_batch = [&](int64_t row0, int nb, const uint4 (&v)[RB][K]) {
-    stage_loaded_rows<DT, NT, RB, K, Padded128Layout>(md, kp, row0, nb, pool, 0u, sc, v);
+
+  uint4 v[RB][K];
+  int nb = rows_at(it.row0);
+  batch_issue_loads<NT, RB, K>(md, it.row0, nb, v);
+  for (int64_t row0 = it.row0; row0 < row_end; row0 += RB) {
+    // the next batch's loads start half-way through this one (past the end: zero-sized buffers,
+    // no traffic), so that they fly under the compaction and the emission
+    const int nb_next = rows_at(row0 + RB);
+    stage_loaded_rows<DT, NT, RB, K, Padded128Layout>(md, kp, row0, nb, pool, 0u, sc, v, [&] {
+      batch_issue_loads<NT, RB, K>(md, row0 + RB, nb_next, v);
+    });
     const uint32_t take = (uint32_t)nb * upr;              // <= NT
     const bool valid = tid < take;
     unsigned char* slot = pool + (size_t)(valid ? tid : 0u) * kSlotBytes;
@@ -54,13 +62,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     __syncthreads();
     copy_wave_codes(kp, md, pool, row0 * (int64_t)upr, wave * kWave, take, lane);
     __syncthreads();                                       // the pool is refilled by the next batch
-  };
-
-  for (int64_t row = it.row0; row < row_end; row += RB) {
-    const int nb = rows_at(row);
-    uint4 v[RB][K];
-    batch_issue_loads<NT, RB, K>(md, row, nb, v);
-    finish_batch(row, nb, v);
+    nb = nb_next;
   }
 }
 
