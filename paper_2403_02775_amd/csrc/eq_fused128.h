@@ -209,6 +209,72 @@ __device__ __forceinline__ void slot_min_max(const unsigned char* slot, float& v
   }
 }
 
+// Code widths other than 4: the unit's 128 codes as a bit stream (code e at bits [BITS e,
+// BITS e + BITS), least significant first) of 4 BITS words, built in registers with constant
+// shifts and written over the upper part of the slot once every value has been read.  A chunk
+// of 8 values yields BITS whole bytes.  The zero-point rides in the rounding constant as in the
+// 4-bit form (an odd one as z + 1 so that exact ties still go to the even level; the 1 comes
+// off the gathered bytes, or off each pattern for 8 bits, where code + 1 can reach 256).
+template <int DT, int BITS>
+__device__ __forceinline__ void emit_codes_bits(const KParams& kp, unsigned char* slot, float inv, int z) {
+  const int zodd = z & 1;
+  const uint32_t unfold = zodd ? 0x01010101u : 0u;
+  const float mz = kMagic + (float)(z + zodd), ulo = kMagic + (float)zodd, uhi = kMagic + (float)(kp.L + zodd);
+  constexpr int NWORDS = 4 * BITS;
+  constexpr uint32_t kPairMask = (((1u << BITS) - 1u) << BITS) * 0x00010001u;
+  uint32_t o[NWORDS];
+#pragma unroll
+  for (int i = 0; i < NWORDS; ++i) o[i] = 0u;
+#pragma unroll
+  for (int ch = 0; ch < 16; ++ch) {
+    const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t f[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float x0, x1;
+      if (DT == EQ_F16) {
+        x0 = __half2float(__ushort_as_half((unsigned short)(w[j] & 0xFFFFu)));
+        x1 = __half2float(__ushort_as_half((unsigned short)(w[j] >> 16)));
+      } else {
+        x0 = __uint_as_float(w[j] << 16);
+        x1 = __uint_as_float(w[j] & 0xFFFF0000u);
+      }
+      f[2 * j] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
+      f[2 * j + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
+      if (BITS == 8) {
+        f[2 * j] -= (uint32_t)zodd;
+        f[2 * j + 1] -= (uint32_t)zodd;
+      }
+    }
+    // the low bytes of four patterns, in element order
+    uint32_t b[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      b[h] = __builtin_amdgcn_perm(f[4 * h + 1], f[4 * h], 0x0C0C0400u) | __builtin_amdgcn_perm(f[4 * h + 3], f[4 * h + 2], 0x04000C0Cu);
+      if (BITS != 8) b[h] -= unfold;
+      // four bytes -> two fields of 2 BITS bits -> one of 4 BITS bits
+      const uint32_t pr = (b[h] & 0x00FF00FFu) | ((b[h] >> (8 - BITS)) & kPairMask);
+      b[h] = (pr & 0xFFFFu) | ((pr >> 16) << (2 * BITS));
+    }
+    const unsigned long long r = (unsigned long long)b[0] | ((unsigned long long)b[1] << (4 * BITS));
+    const uint32_t lo = (uint32_t)r, hi = (uint32_t)(r >> 32);
+    constexpr int kChunkBits = 8 * BITS;
+    const int off = ch * kChunkBits, wd = off >> 5, sh = off & 31;
+    o[wd] |= lo << sh;
+    if (sh) {
+      if (wd + 1 < NWORDS) o[wd + 1] |= (lo >> (32 - sh)) | (hi << sh);
+      if (kChunkBits + sh > 64 && wd + 2 < NWORDS) o[wd + 2] |= hi >> (32 - sh);
+    } else if (kChunkBits > 32) {
+      if (wd + 1 < NWORDS) o[wd + 1] |= hi;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  uint4* dst = reinterpret_cast<uint4*>(slot + kCodeOff);
+#pragma unroll
+  for (int wd = 0; wd < BITS; ++wd) dst[wd] = make_uint4(o[4 * wd], o[4 * wd + 1], o[4 * wd + 2], o[4 * wd + 3]);
+}
+
 // Packed codes of the unit in `slot` at reciprocal scale `inv` (Eq. 1), assembled in the upper
 // half of the slot (the values in the lower half stay intact for 4-bit codes only).
 template <int DT>
@@ -251,32 +317,13 @@ __device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned c
 #pragma unroll
     for (int wd = 0; wd < 4; ++wd) dst[wd] = make_uint4(o[4 * wd], o[4 * wd + 1], o[4 * wd + 2], o[4 * wd + 3]);
   } else {
-    // unsigned codes as bytes over the front of the slot (chunk ch yields bytes 8 ch .. 8 ch + 7,
-    // never ahead of the values still to be read), then a bit-stream pack into the upper half
-    for (int ch = 0; ch < 16; ++ch) {
-      const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-      uint32_t f0, f1, f2, f3, f4, f5, f6, f7;
-      pair_levels<DT>(v.x, inv, mlo, mhi, f0, f1);
-      pair_levels<DT>(v.y, inv, mlo, mhi, f2, f3);
-      pair_levels<DT>(v.z, inv, mlo, mhi, f4, f5);
-      pair_levels<DT>(v.w, inv, mlo, mhi, f6, f7);
-      const uint32_t zz = (uint32_t)z;
-      const uint32_t b0 = ((f0 + zz) & 0xFFu) | (((f1 + zz) & 0xFFu) << 8) | (((f2 + zz) & 0xFFu) << 16) | (((f3 + zz) & 0xFFu) << 24);
-      const uint32_t b1 = ((f4 + zz) & 0xFFu) | (((f5 + zz) & 0xFFu) << 8) | (((f6 + zz) & 0xFFu) << 16) | (((f7 + zz) & 0xFFu) << 24);
-      *reinterpret_cast<uint2*>(slot + ch * 8) = make_uint2(b0, b1);
-    }
-    const unsigned char* ub = slot;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(slot + kCodeOff);
-    unsigned long long acc = 0;
-    int nb = 0, wi = 0;
-    for (int e = 0; e < kG; ++e) {
-      acc |= (unsigned long long)ub[e] << nb;
-      nb += kp.bits;
-      if (nb >= 32) {
-        dst[wi++] = (uint32_t)acc;
-        acc >>= 32;
-        nb -= 32;
-      }
+    switch (kp.bits) {
+      case 2: emit_codes_bits<DT, 2>(kp, slot, inv, z); break;
+      case 3: emit_codes_bits<DT, 3>(kp, slot, inv, z); break;
+      case 5: emit_codes_bits<DT, 5>(kp, slot, inv, z); break;
+      case 6: emit_codes_bits<DT, 6>(kp, slot, inv, z); break;
+      case 7: emit_codes_bits<DT, 7>(kp, slot, inv, z); break;
+      default: emit_codes_bits<DT, 8>(kp, slot, inv, z); break;
     }
   }
 }
