@@ -332,10 +332,11 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
 template <int DT>
 int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const std::vector<MatDesc>& h, const Plan& pl,
                const KParams& kp, hipStream_t st) {
-  int32_t max_rows = 0, gen_rows = 0, gen_cols = 0;
+  int32_t max_rows = 0, max_cols = 0, gen_rows = 0, gen_cols = 0;
   for (const MatDesc& m : h) {
     if (m.cols == 0 || m.rows == 0) continue;
     max_rows = std::max(max_rows, m.rows);
+    max_cols = std::max(max_cols, m.cols);
     if (m.path == 0) {
       gen_rows = std::max(gen_rows, m.rows);
       gen_cols = std::max(gen_cols, m.cols);
@@ -415,7 +416,11 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   EQ_HIP(hipGetLastError());
   if (max_rows > 0) {
     const int rows_per_block = kWaves * kGatherRows;
-    hipLaunchKernelGGL(gather_outliers, dim3((max_rows + rows_per_block - 1) / rows_per_block, n), dim3(kThreads), 0, st, dmats);
+    const uint32_t wmax = (uint32_t)((max_cols + 31) / 32);
+    const size_t lds = (size_t)kWaves * 2 * wmax * sizeof(uint32_t);
+    if (lds > 65536)
+      EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_outliers), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(gather_outliers, dim3((max_rows + rows_per_block - 1) / rows_per_block, n), dim3(kThreads), lds, st, dmats, wmax);
     EQ_HIP(hipGetLastError());
   }
   return EQ_OK;

@@ -3,6 +3,7 @@
 #pragma once
 
 #include "eq_common.h"
+#include "eq_rowbatch.h"
 
 namespace eq {
 
@@ -51,36 +52,25 @@ __global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __res
 }
 
 // Moves each row's staged run (arrival order) to its CSR position, sorted by column: the rank of
-// an entry is the number of entries of its row with a smaller column.  One wavefront takes
-// kGatherRows consecutive rows at a time with all their loads in flight together (a row's
-// bookkeeping, then its entries: two dependent round trips to memory per row otherwise).
+// an entry is the number of entries of its row with a smaller column.  Columns of a row are
+// distinct, so the wavefront marks them in a bitmap of the row's columns in LDS, takes a prefix
+// sum of the population counts of its words, and an entry's rank is the prefix of its word plus
+// the marked bits below its own: linear in the row's entries and words, whatever the order they
+// arrived in.  One wavefront takes kGatherRows consecutive rows with all their loads in flight
+// together (a row's bookkeeping, then its entries: two dependent round trips to memory per row
+// otherwise); rows of more than 128 entries re-read theirs in passes of 64.
+// `wmax` = words of the widest matrix's bitmap; LDS: 2 * wmax words per wavefront.
 constexpr int kGatherRows = 4;
 
-__device__ __forceinline__ void gather_row_general(const MatDesc& md, uint32_t cnt, uint32_t src, uint32_t dst, uint32_t lane) {
-  for (uint32_t e0 = 0; e0 < cnt; e0 += kWave) {
-    const uint32_t e = e0 + lane;
-    const bool have = e < cnt;
-    const uint32_t col = have ? md.st_col[src + e] : 0xFFFFFFFFu;
-    const uint16_t val = have ? md.st_val[src + e] : (uint16_t)0;
-    uint32_t rank = 0;
-    for (uint32_t f0 = 0; f0 < cnt; f0 += kWave) {
-      const uint32_t f = f0 + lane;
-      const uint32_t cf = f < cnt ? md.st_col[src + f] : 0xFFFFFFFFu;
-      const int m = (int)min((uint32_t)kWave, cnt - f0);
-      for (int j = 0; j < m; ++j) rank += (uint32_t)__builtin_amdgcn_readlane((int)cf, j) < col ? 1u : 0u;
-    }
-    if (have) {
-      md.out_col[dst + rank] = col;
-      md.out_val[dst + rank] = val;
-    }
-  }
-}
-
-__global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats) {
+__global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats, uint32_t wmax) {
+  extern __shared__ uint32_t gather_lds[];
   const MatDesc md = mats[blockIdx.y];
   const int64_t row0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kGatherRows;
   if (row0 >= md.rows || md.cols == 0) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
+  uint32_t* bm = gather_lds + (threadIdx.x / kWave) * 2u * wmax;   // marked columns
+  uint32_t* pre = bm + wmax;                                       // marked columns in the words before
+  const uint32_t W = ((uint32_t)md.cols + 31u) >> 5, wpl = (W + kWave - 1) / kWave;
   uint32_t cnt[kGatherRows], src[kGatherRows], dst[kGatherRows];
 #pragma unroll
   for (int r = 0; r < kGatherRows; ++r) {
@@ -91,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __res
     // a row that was not staged, or whose run does not fit the output arrays, is left out
     if (src[r] == 0xFFFFFFFFu || (unsigned long long)dst[r] + cnt[r] > (unsigned long long)md.capacity) cnt[r] = 0;
   }
-  // rows of at most 128 entries (two per lane): all loads of all rows first, then the ranks
+  // rows of at most 128 entries (two per lane): all loads of all rows first
   constexpr uint32_t kFast = 2 * kWave;
   uint32_t col[kGatherRows][2];
   uint16_t val[kGatherRows][2];
@@ -105,32 +95,61 @@ __global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __res
       val[r][h] = have ? md.st_val[src[r] + e] : (uint16_t)0;
     }
   }
+  auto wave_sync = [] {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  auto rank_of = [&](uint32_t c) { return pre[c >> 5] + (uint32_t)__popc(bm[c >> 5] & ((1u << (c & 31u)) - 1u)); };
 #pragma unroll
   for (int r = 0; r < kGatherRows; ++r) {
-    if (cnt[r] > kFast) {                                  // uniform over the wavefront
-      gather_row_general(md, cnt[r], src[r], dst[r], lane);
-    } else if (cnt[r]) {
-      uint32_t rank0 = 0, rank1 = 0;
-      const uint32_t n0 = min(cnt[r], (uint32_t)kWave);
-      for (uint32_t j = 0; j < n0; ++j) {
-        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)col[r][0], (int)j);     // j is uniform: no LDS traffic
-        rank0 += c < col[r][0] ? 1u : 0u;
-        rank1 += c < col[r][1] ? 1u : 0u;
-      }
-      for (uint32_t j = kWave; j < cnt[r]; ++j) {
-        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)col[r][1], (int)(j - kWave));
-        rank0 += c < col[r][0] ? 1u : 0u;
-        rank1 += c < col[r][1] ? 1u : 0u;
-      }
-      if (lane < cnt[r]) {
-        md.out_col[dst[r] + rank0] = col[r][0];
-        md.out_val[dst[r] + rank0] = val[r][0];
-      }
-      if (lane + kWave < cnt[r]) {
-        md.out_col[dst[r] + rank1] = col[r][1];
-        md.out_val[dst[r] + rank1] = val[r][1];
+    if (cnt[r] == 0) continue;                             // uniform over the wavefront
+    const bool fast = cnt[r] <= kFast;
+    for (uint32_t w = lane; w < W; w += kWave) bm[w] = 0u;
+    wave_sync();
+    if (fast) {
+      if (col[r][0] != 0xFFFFFFFFu) atomicOr(&bm[col[r][0] >> 5], 1u << (col[r][0] & 31u));
+      if (col[r][1] != 0xFFFFFFFFu) atomicOr(&bm[col[r][1] >> 5], 1u << (col[r][1] & 31u));
+    } else {
+      for (uint32_t e = lane; e < cnt[r]; e += kWave) {
+        const uint32_t c = md.st_col[src[r] + e];
+        atomicOr(&bm[c >> 5], 1u << (c & 31u));
       }
     }
+    wave_sync();
+    // lane l owns words [l * wpl, (l + 1) * wpl)
+    uint32_t mine = 0;
+    for (uint32_t k = 0; k < wpl; ++k) {
+      const uint32_t w = lane * wpl + k;
+      if (w < W) mine += (uint32_t)__popc(bm[w]);
+    }
+    uint32_t run = wave_scan_inclusive(mine) - mine;
+    for (uint32_t k = 0; k < wpl; ++k) {
+      const uint32_t w = lane * wpl + k;
+      if (w < W) {
+        pre[w] = run;
+        run += (uint32_t)__popc(bm[w]);
+      }
+    }
+    wave_sync();
+    if (fast) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        if (col[r][h] != 0xFFFFFFFFu) {
+          const uint32_t rank = rank_of(col[r][h]);
+          md.out_col[dst[r] + rank] = col[r][h];
+          md.out_val[dst[r] + rank] = val[r][h];
+        }
+      }
+    } else {
+      for (uint32_t e = lane; e < cnt[r]; e += kWave) {
+        const uint32_t c = md.st_col[src[r] + e];
+        const uint16_t v = md.st_val[src[r] + e];
+        const uint32_t rank = rank_of(c);
+        md.out_col[dst[r] + rank] = c;
+        md.out_val[dst[r] + rank] = v;
+      }
+    }
+    wave_sync();                                           // the next row clears the bitmap
   }
 }
 
