@@ -184,6 +184,10 @@ def test_longest_supported_rows():
     W = eq_inputs.gen_matrix(3, 65536, eq_inputs.RECIPES["c5"], seed=65, device=DEV)
     _check(W, eqo.Params(bits=4, group_size=128, iters=8), "65536 columns, group 128")
     _check(W, eqo.Params(bits=4, group_size=0, iters=8), "65536 columns, per channel")
+    # a third of every row is an outlier: the CSR finish sorts runs of ~20000 entries (a bitmap of 2048 words)
+    _check(W, eqo.Params(bits=4, group_size=128, iters=2, n_sigma=1.0), "65536 columns, n = 1")
+    W2 = eq_inputs.gen_matrix(5, 32768, eq_inputs.RECIPES["c5"], seed=66, device=DEV)
+    _check(W2, eqo.Params(bits=4, group_size=128, iters=0, n_sigma=1.0), "32768 columns, n = 1, T = 0")
     gp = eqg.Params(group_size=128)
     too_long = torch.zeros((1, 65536 + 128), dtype=torch.float16, device=DEV)
     with pytest.raises(eqg.EasyQuantError) as e:
