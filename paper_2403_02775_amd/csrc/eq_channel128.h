@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       scale_of(kp, r_sel, s32, inv);
       __syncthreads();
       if (valid) {
-        emit_codes_to_slot<DX>(kp, slot, inv * unshift, z, mlo, mhi);
+        emit_codes_to_slot<DX>(kp, slot, inv * unshift, z);
         if (seg == 0) {
           md.scales[row0 + my_row] = s32;
           md.zps[row0 + my_row] = (unsigned char)z;

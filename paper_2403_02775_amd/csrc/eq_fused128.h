@@ -40,24 +40,10 @@ struct WorkItem {
 
 typedef short short2_t __attribute__((ext_vector_type(2)));
 
-// Bit patterns of kMagic + level for the two elements of a packed pair (see level_of): the low
-// 16 bits of each pattern are the signed level c in two's complement.  mlo / mhi are the
-// level bounds plus kMagic.  For fp16 the widening folds into the multiply-add (v_fma_mix_f32).
-template <int DT>
-__device__ __forceinline__ void pair_levels(uint32_t w, float inv, float mlo, float mhi, uint32_t& f0, uint32_t& f1) {
-  float x0, x1;
-  if (DT == EQ_F16) {
-    x0 = __half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu)));
-    x1 = __half2float(__ushort_as_half((unsigned short)(w >> 16)));
-  } else {
-    x0 = __uint_as_float(w << 16);
-    x1 = __uint_as_float(w & 0xFFFF0000u);
-  }
-  f0 = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, kMagic), mlo, mhi));
-  f1 = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, kMagic), mlo, mhi));
-}
-
-// Levels of the 8 elements of one 16-byte chunk as four packed int16 pairs.  Written stage by
+// Levels of the 8 elements of one 16-byte chunk as four packed int16 pairs: the low 16 bits of the
+// bit pattern of kMagic + level (see level_of) are the signed level in two's complement; mlo / mhi
+// are the level bounds plus kMagic; for fp16 the widening folds into the multiply-add
+// (v_fma_mix_f32).  Written stage by
 // stage (8 multiply-adds, 8 clamps, 4 packs) so that neighbouring instructions are independent:
 // a dependent instruction cannot issue back to back, and only two wavefronts share a SIMD.
 template <int DT>
@@ -278,7 +264,7 @@ __device__ __forceinline__ void emit_codes_bits(const KParams& kp, unsigned char
 // Packed codes of the unit in `slot` at reciprocal scale `inv` (Eq. 1), assembled in the upper
 // half of the slot (the values in the lower half stay intact for 4-bit codes only).
 template <int DT>
-__device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned char* slot, float inv, int z, float mlo, float mhi) {
+__device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned char* slot, float inv, int z) {
   if (kp.bits == 4) {
     // all 16 words first (they overwrite the upper half of the values), then one store burst
     // The zero-point goes into the magic constant, so the low byte of each pattern is the
@@ -499,7 +485,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         scale_of(kp, r_sel, s32, inv);
         __syncthreads();              // every lane has finished reading slots that are not its own
         if (valid) {
-          emit_codes_to_slot<DX>(kp, slot, inv * unshift, z, mlo, mhi);
+          emit_codes_to_slot<DX>(kp, slot, inv * unshift, z);
           const int64_t gu = unit_base + slot_i;
           md.scales[gu] = s32;
           md.zps[gu] = (unsigned char)z;

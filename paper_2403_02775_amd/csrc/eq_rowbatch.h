@@ -7,19 +7,21 @@
 // Outliers are rare (< 1 % of the elements, Sec. 5), so only a few 16-byte chunks per thread
 // hold one.  The bulk pass therefore does the minimum per element (the sums, and one test per
 // chunk: can anything in it reach the threshold?), and the chunks that pass the test
-// ("candidates") are handled one per loop iteration by the lanes that have one.  Within a
-// row the outliers are written in arrival order; gather_outliers sorts each row's run by
-// column when it moves it to its final place, so the result does not depend on timing.
+// ("candidates") are queued per wavefront and dealt out evenly over its lanes, twice: to count,
+// and, once the batch's run of the staging list is reserved, to write.  Within a row the
+// outliers are written in arrival order; gather_outliers sorts each row's run by column when
+// it moves it to its final place, so the result does not depend on timing.
 //
 // Statistics (Eq. 3) take a fast path and an exact path with identical results:
-//   fast  : sum x and sum x^2, mean and sigma in binary32.  The outlier
+//   fast  : sum x and sum x^2 by packed dot products, mean and sigma in binary32.  The outlier
 //           test is decided only for elements whose |x - mean| is farther than a relative
 //           1e-4 from n*sigma; the error of the fast mean and threshold is below 2.7e-5 of the
 //           threshold (<= 90 roundings of 2^-24 on quantities that are bounded through the
 //           guard mean^2 < variance, n >= 0.5), so those decisions equal the exact ones.
 //   exact : a row with an element inside that band, or that fails the guard (which also
-//           covers constant rows), is redone from its pool copy with the two-pass binary64 sums
-//           and decided element by element in binary64.
+//           covers constant rows and rows of mostly subnormal binary16 values), is redone from
+//           its pool copy with the two-pass binary64 sums and decided element by element in
+//           binary64.
 #pragma once
 
 #include <type_traits>

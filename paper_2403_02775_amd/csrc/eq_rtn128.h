@@ -50,11 +50,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     float r0;
     int z;
     const bool active = init_unit(kp, vmin, vmax, r0, z);
-    const float mlo = (float)(-z) + kMagic, mhi = (float)(kp.L - z) + kMagic;
     float s32, inv;
     scale_of(kp, active ? r0 : kp.D, s32, inv);            // an all-zero unit keeps s = 1
     if (valid) {
-      emit_codes_to_slot<DT>(kp, slot, inv, z, mlo, mhi);
+      emit_codes_to_slot<DT>(kp, slot, inv, z);
       const int64_t gu = row0 * (int64_t)upr + tid;
       md.scales[gu] = s32;
       md.zps[gu] = (unsigned char)z;
