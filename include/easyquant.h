@@ -146,7 +146,10 @@ EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* row
  * and group_size of p are read.  q->status is not touched.  The outlier list must be in the
  * form eq_quantize_* writes it: columns ascending within each row (an entry out of order, or
  * with a column >= cols, ends the row's list: it and the entries after it are not applied;
- * nothing outside W_out is ever written).  q->out_col / q->out_val NULL: no outliers. */
+ * nothing outside W_out is ever written).  q->out_col / q->out_val NULL: no outliers.
+ * One kernel launch on hip_stream, every argument passed by value, no device memory
+ * allocated or copied: the call (like eq_dequant_matvec) may be recorded into a HIP graph;
+ * the eq_quantize_* calls may not, they upload descriptors from host memory. */
 EQ_API int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p,
                   void* W_out, int64_t ld_out, void* hip_stream);
 

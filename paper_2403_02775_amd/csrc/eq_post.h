@@ -7,8 +7,8 @@
 
 namespace eq {
 
-// Reset of the per-matrix cursor and status word (a kernel rather than a memset, so the
-// whole call can be recorded into a HIP graph).
+// Reset of the per-matrix cursor and status word (a kernel: the descriptors that hold the
+// addresses live in device memory).
 __global__ void reset_state(const MatDesc* __restrict__ mats, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;

@@ -179,6 +179,47 @@ def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     assert (err2 <= bound).all()
 
 
+def test_consumers_replay_from_a_hip_graph():
+    """eq_dequantize and eq_dequant_matvec are single kernel launches that take everything by value
+    and allocate nothing, so a serving loop can record them into a HIP graph: every replay, with
+    eager work and synchronisations in between and fresh inputs in the same buffers, must give
+    the bits of the eager call."""
+    rows, cols = 48, 4096
+    W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c2"], seed=321, device=DEV)
+    p = eqo.Params(bits=4, group_size=128, iters=3)
+    gp = to_gpu_params(p)
+    outs, _ = run_gpu([W], p)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    x = torch.randn(cols, device=DEV, generator=g).to(torch.float16)
+    y = torch.zeros(rows, dtype=torch.float32, device=DEV)
+    Wd = torch.zeros((rows, cols), dtype=torch.float16, device=DEV)
+    # eager results first (this also warms everything up outside the capture)
+    eqg.eq_dequant_matvec(outs[0], rows, cols, gp, x, y)
+    eqg.eq_dequantize(outs[0], rows, cols, gp, Wd)
+    torch.cuda.synchronize()
+    Wd_eager = Wd.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            eqg.eq_dequant_matvec(outs[0], rows, cols, gp, x, y)
+            eqg.eq_dequantize(outs[0], rows, cols, gp, Wd)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        x.copy_(torch.randn(cols, device=DEV, generator=g).to(torch.float16))
+        y_eager = torch.empty_like(y)
+        eqg.eq_dequant_matvec(outs[0], rows, cols, gp, x, y_eager)
+        y.fill_(-1.0)
+        Wd.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int32), y_eager.view(torch.int32)), rep
+        assert torch.equal(Wd.view(torch.int16), Wd_eager.view(torch.int16)), rep
+
+
 def test_longest_supported_rows():
     # EQ_MAX_COLS = 65536: beyond the lane kernels' 32768, so the general kernel with the whole row in LDS
     W = eq_inputs.gen_matrix(3, 65536, eq_inputs.RECIPES["c5"], seed=65, device=DEV)
