@@ -270,6 +270,18 @@ def test_extreme_magnitudes_and_degenerate_rows(G, iters):
     assert res["excused_elems"] == 0
 
 
+@pytest.mark.parametrize("bits", [2, 3, 5, 6, 7, 8])
+def test_every_code_width_on_the_lane_kernels(bits):
+    # the three lane kernels build the bit stream of a unit in registers, one instantiation per width;
+    # asymmetric mode gives odd and even zero-points (an odd one takes the tie-preserving detour)
+    W = eq_inputs.gen_matrix(12, 2048, eq_inputs.RECIPES["c5"], seed=50 + bits, device=DEV)
+    for G, iters, mode in ((128, 0, eqo.SYMMETRIC), (128, 4, eqo.ASYMMETRIC), (0, 4, eqo.SYMMETRIC), (128, 0, eqo.ASYMMETRIC)):
+        res = _check(W, eqo.Params(bits=bits, group_size=G, iters=iters, mode=mode), f"{bits}-bit G={G} T={iters} mode={mode}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+    Wb = eq_inputs.gen_matrix(12, 2048, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=60 + bits, device=DEV)
+    _check(Wb, eqo.Params(dtype=eqo.BF16, bits=bits, group_size=128, iters=3, mode=eqo.ASYMMETRIC), f"{bits}-bit bf16")
+
+
 @pytest.mark.parametrize("n_sigma", [2.6, 2.2, 1.5])
 def test_candidate_queue_fill_levels(n_sigma):
     # the staging deals a wavefront's candidate chunks out over its lanes through a queue of 128
