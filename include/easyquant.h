@@ -127,8 +127,9 @@ typedef struct eq_qmatrix {
  * wavefront per unit).  Three environment variables, read at every call, exist for tests and
  * measurements: EASYQUANT_UNITS_PER_ITEM=<n> sets the number of units a workgroup walks
  * through (changes only how the work is cut up), EASYQUANT_FORCE_GENERAL=1 sends every
- * matrix to the general kernel, EASYQUANT_RTN_THREADS=256 runs the iters == 0 variant with
- * workgroups of 256 instead of 128 threads for rows of up to 8192. */
+ * matrix to the general kernel, EASYQUANT_RTN_THREADS=256 | 512 runs the iters == 0 variant
+ * with workgroups of 256 threads for every row length (default: 128 up to 8192 columns, 256
+ * beyond) or of 512 threads for rows longer than 8192. */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,
                        const eq_params* p, const eq_qmatrix* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -211,13 +211,16 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
       lc.kind = 3;
       // two-wavefront workgroups (four per compute unit) for rows of up to 8192: measured 4 % faster
-      // than four-wavefront ones, whose barriers hold more wavefronts; longer rows need 512 threads
-      lc.threads = c > 8192 ? 512 : 128;
+      // than four-wavefront ones, whose barriers hold more wavefronts; longer rows take four
+      // wavefronts (two workgroups per compute unit, 15 % faster on rows of 22016 than one of eight)
+      lc.threads = c > 8192 ? 256 : 128;
       if (const char* ov = std::getenv("EASYQUANT_RTN_THREADS")) {
-        if (std::atol(ov) == 256 && c <= 8192) lc.threads = 256;
+        const long t = std::atol(ov);
+        if (t == 256) lc.threads = 256;
+        if (t == 512 && c > 8192) lc.threads = 512;
       }
       const int64_t per_thread = (c / 8 + lc.threads - 1) / lc.threads;
-      lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : 8;
+      lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : per_thread <= 8 ? 8 : 16;
       if (lc.threads == 512 && lc.chunks_per_thread < 4) lc.chunks_per_thread = 4;
       const int64_t rpb = 16 / lc.chunks_per_thread;
       lc.pool_slots = (uint32_t)(rpb * upr);
@@ -382,7 +385,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   }
     if (lc.kind == 3) {
       EQ_RTN_VARIANT(128, 1) EQ_RTN_VARIANT(128, 2) EQ_RTN_VARIANT(128, 4) EQ_RTN_VARIANT(128, 8)
-      EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
+      EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(256, 8) EQ_RTN_VARIANT(256, 16) EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
     } else if (lc.kind == 2) {
       EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
     } else {

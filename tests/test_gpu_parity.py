@@ -115,11 +115,11 @@ def test_no_optimisation_steps_kernel_row_shapes(rows, cols, units_per_item, mon
     for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
         res = _check(W, eqo.Params(bits=bits, group_size=128, mode=mode, iters=0), f"rtn kernel {rows}x{cols}")
         assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
-    if cols <= 8192:                                     # the same with four-wavefront workgroups
-        monkeypatch.setenv("EASYQUANT_RTN_THREADS", "256")
-        res = _check(W, eqo.Params(bits=4, group_size=128, iters=0), f"rtn kernel, 256 threads, {rows}x{cols}")
-        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
-        monkeypatch.delenv("EASYQUANT_RTN_THREADS")
+    # the same with the other workgroup sizes: four wavefronts for short rows, eight for long ones
+    monkeypatch.setenv("EASYQUANT_RTN_THREADS", "256" if cols <= 8192 else "512")
+    res = _check(W, eqo.Params(bits=4, group_size=128, iters=0), f"rtn kernel, other workgroup size, {rows}x{cols}")
+    assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+    monkeypatch.delenv("EASYQUANT_RTN_THREADS")
     Wb = eq_inputs.gen_matrix(rows, cols, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=rows, device=DEV)
     _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=0, n_sigma=2.0), f"rtn kernel bf16 {rows}x{cols}")
 
