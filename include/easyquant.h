@@ -124,12 +124,13 @@ typedef struct eq_qmatrix {
  * one unit per lane (without optimisation steps, iters == 0, a load-pipelined variant of it);
  * one range per row with cols a multiple of 128 in 2048..32768 spreads the row over
  * cols / 128 lanes; everything else goes to a general kernel (one workgroup per row, one
- * wavefront per unit).  Three environment variables, read at every call, exist for tests and
+ * wavefront per unit).  Four environment variables, read at every call, exist for tests and
  * measurements: EASYQUANT_UNITS_PER_ITEM=<n> sets the number of units a workgroup walks
  * through (changes only how the work is cut up), EASYQUANT_FORCE_GENERAL=1 sends every
  * matrix to the general kernel, EASYQUANT_RTN_THREADS=256 | 512 runs the iters == 0 variant
  * with workgroups of 256 threads for every row length (default: 128 up to 8192 columns, 256
- * beyond) or of 512 threads for rows longer than 8192. */
+ * beyond) or of 512 threads for rows longer than 8192, EASYQUANT_CHANNEL_KERNEL=128 keeps
+ * per-channel rows of 11008, 13824, 17920 and 22016 columns on the 128-element segments. */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,
                        const eq_params* p, const eq_qmatrix* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -13,6 +13,7 @@
 #include "easyquant.h"
 #include "eq_common.h"
 #include "eq_channel128.h"
+#include "eq_channel_split.h"
 #include "eq_fused128.h"
 #include "eq_generic.h"
 #include "eq_post.h"
@@ -96,7 +97,8 @@ KParams make_kparams(const eq_params* p) {
 // One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
 struct LaneClass {
   int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes,
-                                        // 3: group of 128 without optimisation steps (load-pipelined kernel)
+                                        // 3: group of 128 without optimisation steps (load-pipelined kernel),
+                                        // 5: per-channel rows cut into equal pieces over all lanes
   int32_t cols = 0, upr = 0;
   int32_t threads = kThreads;           // workgroup size = units per round
   int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
@@ -188,7 +190,18 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : per_thread <= 8 ? 8 : 16;
       lc.pool_slots = kChanThreads;
       lc.lds_bytes = (size_t)kChanHeader + (size_t)kChanThreads * kSlotBytes;
-      const int64_t rpr = std::min<int64_t>(kChanThreads / upr, kChanMaxRows);
+      int64_t rpr = std::min<int64_t>(kChanThreads / upr, kChanMaxRows);
+      // fp16 rows with 4-bit codes whose 128-element segments would leave many of the 256 lanes
+      // idle (the MLP down-projections of the LLaMA shapes): equal pieces over all lanes instead
+      // (eq_channel_split.h).  chunks_per_thread selects the instantiation.
+      const char* which = std::getenv("EASYQUANT_CHANNEL_KERNEL");
+      const int split = c == 86 * 256 ? 1 : c == 86 * 128 ? 2 : c == 54 * 256 ? 3 : c == 70 * 256 ? 4 : 0;
+      if (split && p->dtype == EQ_F16 && p->bits == 4 && !(which && std::strcmp(which, "128") == 0)) {
+        lc.kind = 5;
+        rpr = split == 2 ? 2 : 1;
+        lc.chunks_per_thread = split;
+        lc.lds_bytes = (size_t)kChanHeader + (size_t)rpr * (size_t)c * 2;
+      }
       int64_t target = std::min<int64_t>(8192, std::max<int64_t>(kChanThreads, total_units / 16384));
       if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
         const long v = std::atol(ov);
@@ -386,6 +399,17 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
     if (lc.kind == 3) {
       EQ_RTN_VARIANT(128, 1) EQ_RTN_VARIANT(128, 2) EQ_RTN_VARIANT(128, 4) EQ_RTN_VARIANT(128, 8)
       EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(256, 8) EQ_RTN_VARIANT(256, 16) EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
+    } else if (lc.kind == 5) {
+#define EQ_SPLIT_VARIANT(ID_, P_, LPR_)                                                                         \
+  if (DT == EQ_F16 && lc.chunks_per_thread == ID_) {                                                            \
+    fn = reinterpret_cast<const void*>(&quantize_channels_split<P_, LPR_>);                                     \
+    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
+      hipLaunchKernelGGL((quantize_channels_split<P_, LPR_>), dim3((unsigned)c.n_items), dim3(kChanThreads),    \
+                         c.lds_bytes, s, dm, di + c.first_item, k);                                             \
+    };                                                                                                          \
+  }
+      EQ_SPLIT_VARIANT(1, 43, 256) EQ_SPLIT_VARIANT(2, 43, 128) EQ_SPLIT_VARIANT(3, 27, 256) EQ_SPLIT_VARIANT(4, 35, 256)
+#undef EQ_SPLIT_VARIANT
     } else if (lc.kind == 2) {
       EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
     } else {

@@ -64,7 +64,8 @@ def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_it
 
 
 @pytest.mark.parametrize("rows,cols,units_per_item", [(37, 4096, 0), (21, 8192, 300), (5, 22016, 0), (11, 11008, 0),
-                                                      (13, 5120, 0), (40, 2048, 512), (3, 32768, 0)])
+                                                      (13, 5120, 0), (40, 2048, 512), (3, 32768, 0), (4, 13824, 0),
+                                                      (3, 17920, 0), (7, 11008, 200)])
 def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, monkeypatch):
     # one range per row, the row spread over cols / 128 lanes: rounds of 8, 4, 1, 2, 6, 16 and 1
     # rows, a ragged last round, several rounds per work item, staging in one or several batches
@@ -74,6 +75,32 @@ def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, monkeypa
     for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
         res = _check(W, eqo.Params(bits=bits, group_size=0, mode=mode, iters=12), f"channel kernel {rows}x{cols}")
         assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+
+
+@pytest.mark.parametrize("cols", [22016, 11008])
+def test_per_channel_rows_cut_into_equal_pieces(cols, monkeypatch):
+    # fp16 rows of 86 * 256 or 86 * 128 values with 4-bit codes take the kernel that cuts a row into
+    # equal pieces over all 256 lanes: its variants, its binary64 fallback, and the 128-element
+    # kernel it replaces on the same input
+    W = eq_inputs.gen_matrix(7, cols, eq_inputs.RECIPES["c5"], seed=cols, device=DEV)
+    _check(W, eqo.Params(bits=4, group_size=0, iters=20, mode=eqo.ASYMMETRIC), f"split {cols} asymmetric")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=0), f"split {cols} T=0")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=1), f"split {cols} T=1")
+    _check(W, eqo.Params(bits=4, group_size=cols, iters=30, select=eqo.SELECT_LAST), f"split {cols} select=last, G=cols")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=6, stat_scope=eqo.STAT_MATRIX), f"split {cols} matrix scope")
+    _check(W, eqo.Params(bits=4, group_size=0, iters=6, n_sigma=1.0), f"split {cols} n=1")
+    Wz = W.clone()
+    Wz[2] = 0                                            # an all-zero row keeps scale 1
+    Wz[3, 50:] = 0
+    Wz[4] = Wz[4] * 3000.0                               # magnitudes beyond 64: values below the fixed-point
+    Wz[4, 11] = 6e-8                                     # resolution of the row send the round to binary64 sums
+    Wz[5, ::2] = 0.25
+    Wz[5, 1::2] = -0.25                                  # every element exactly one sigma from the mean
+    res = _check(Wz, eqo.Params(bits=4, group_size=0, iters=8), f"split {cols} degenerate rows")
+    assert res["excused_elems"] == 0
+    monkeypatch.setenv("EASYQUANT_CHANNEL_KERNEL", "128")
+    res = _check(W, eqo.Params(bits=4, group_size=0, iters=8), f"128-element kernel on {cols}")
+    assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
 
 def test_per_channel_lane_kernel_variants():
