@@ -287,7 +287,7 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": alg_bytes / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": hbm_frac, "traffic": None}
-    kernel = "quantize_rtn128" if args.group_size == 128 and args.iters == 0 else "quantize_units128" if args.group_size == 128 else "quantize_channels128" if args.group_size == 0 else "quantize_rows_generic"
+    kernel = "quantize_rtn128" if args.group_size == 128 and args.iters == 0 else "quantize_units128" if args.group_size == 128 else "quantize_channels" if args.group_size == 0 else "quantize_rows_generic"
     roof["traffic"] = measured_traffic(args.workload if args.layers < 0 else None, args.iters, kernel)
     roof.update({"kernel": kernel, "launches_per_step": launches / args.steps,
                  "kernel_ms_per_step": kern_ms / args.steps, "avg_launch_ms": kern_ms / max(launches, 1),
