@@ -13,12 +13,11 @@
 #include "easyquant.h"
 #include "eq_common.h"
 #include "eq_channel128.h"
-#include "eq_channel_split.h"
 #include "eq_fused128.h"
 #include "eq_generic.h"
+#include "eq_launch.h"
 #include "eq_post.h"
 #include "eq_rowstage.h"
-#include "eq_rtn128.h"
 
 namespace {
 
@@ -93,19 +92,6 @@ KParams make_kparams(const eq_params* p) {
   k.adam_tab = nullptr;
   return k;
 }
-
-// One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
-struct LaneClass {
-  int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes,
-                                        // 3: group of 128 without optimisation steps (load-pipelined kernel),
-                                        // 5: per-channel rows cut into equal pieces over all lanes
-  int32_t cols = 0, upr = 0;
-  int32_t threads = kThreads;           // workgroup size = units per round
-  int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
-  uint32_t pool_slots = 0;
-  size_t lds_bytes = 0;
-  size_t first_item = 0, n_items = 0;
-};
 
 // Bias corrections of Adam for steps 1..T and their correctly rounded reciprocals, in the
 // order the kernels read them (Adam::step).  The running products are formed exactly as the
@@ -370,55 +356,11 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   }
   for (const LaneClass& lc : pl.classes) {
     if (lc.n_items == 0) continue;
-    const void* fn = nullptr;
-    void (*launch)(const LaneClass&, const MatDesc*, const WorkItem*, const KParams&, hipStream_t) = nullptr;
-#define EQ_VARIANT(NT_, K_)                                                                                     \
-  if (lc.threads == NT_ && lc.chunks_per_thread == K_) {                                                        \
-    fn = reinterpret_cast<const void*>(&quantize_units128<DT, NT_, K_>);                                        \
-    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
-      hipLaunchKernelGGL((quantize_units128<DT, NT_, K_>), dim3((unsigned)c.n_items), dim3(NT_), c.lds_bytes, s, \
-                         dm, di + c.first_item, k, c.pool_slots);                                              \
-    };                                                                                                          \
-  }
-#define EQ_CHAN_VARIANT(K_)                                                                                     \
-  if (lc.chunks_per_thread == K_) {                                                                             \
-    fn = reinterpret_cast<const void*>(&quantize_channels128<DT, K_>);                                          \
-    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
-      hipLaunchKernelGGL((quantize_channels128<DT, K_>), dim3((unsigned)c.n_items), dim3(kChanThreads),         \
-                         c.lds_bytes, s, dm, di + c.first_item, k);                                             \
-    };                                                                                                          \
-  }
-#define EQ_RTN_VARIANT(NT_, K_)                                                                                 \
-  if (lc.threads == NT_ && lc.chunks_per_thread == K_) {                                                        \
-    fn = reinterpret_cast<const void*>(&quantize_rtn128<DT, NT_, K_>);                                          \
-    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
-      hipLaunchKernelGGL((quantize_rtn128<DT, NT_, K_>), dim3((unsigned)c.n_items), dim3(NT_), c.lds_bytes, s,  \
-                         dm, di + c.first_item, k);                                                             \
-    };                                                                                                          \
-  }
-    if (lc.kind == 3) {
-      EQ_RTN_VARIANT(128, 1) EQ_RTN_VARIANT(128, 2) EQ_RTN_VARIANT(128, 4) EQ_RTN_VARIANT(128, 8)
-      EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(256, 8) EQ_RTN_VARIANT(256, 16) EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
-    } else if (lc.kind == 5) {
-#define EQ_SPLIT_VARIANT(ID_, P_, LPR_)                                                                         \
-  if (DT == EQ_F16 && lc.chunks_per_thread == ID_) {                                                            \
-    fn = reinterpret_cast<const void*>(&quantize_channels_split<P_, LPR_>);                                     \
-    launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& k, hipStream_t s) {   \
-      hipLaunchKernelGGL((quantize_channels_split<P_, LPR_>), dim3((unsigned)c.n_items), dim3(kChanThreads),    \
-                         c.lds_bytes, s, dm, di + c.first_item, k);                                             \
-    };                                                                                                          \
-  }
-      EQ_SPLIT_VARIANT(1, 43, 256) EQ_SPLIT_VARIANT(2, 43, 128) EQ_SPLIT_VARIANT(3, 27, 256) EQ_SPLIT_VARIANT(4, 35, 256)
-#undef EQ_SPLIT_VARIANT
-    } else if (lc.kind == 2) {
-      EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
-    } else {
-      EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4)
-      EQ_VARIANT(512, 2) EQ_VARIANT(512, 4) EQ_VARIANT(512, 8)
-    }
-#undef EQ_VARIANT
-#undef EQ_CHAN_VARIANT
-#undef EQ_RTN_VARIANT
+    // the kernels of each family are instantiated in a translation unit of their own (eq_launch.h)
+    const LaneKernel lk = lc.kind == 3 ? pick_rtn_kernel<DT>(lc)
+                          : (lc.kind == 2 || lc.kind == 5) ? pick_channel_kernel<DT>(lc) : pick_units_kernel<DT>(lc);
+    const void* fn = lk.fn;
+    const LaneLaunch launch = lk.launch;
     if (!fn) return EQ_E_UNSUPPORTED;
     if (lc.lds_bytes > 65536)
       EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));

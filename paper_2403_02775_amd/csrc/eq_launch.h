@@ -1,0 +1,42 @@
+// What the host side and the translation units that hold the lane kernels share: the description
+// of one launch, and one selector per kernel family.  Each family is compiled in a file of its
+// own (eq_tu_units.hip, eq_tu_channels.hip, eq_tu_rtn.hip), once per input type, so that the
+// library builds in parallel; a selector returns the instantiation that serves a launch, or
+// nothing if there is none.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "eq_common.h"
+
+namespace eq {
+
+struct WorkItem;
+
+// One launch of the unit-per-lane kernel: all matrices of a batch that share a row length.
+struct LaneClass {
+  int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes,
+                                        // 3: group of 128 without optimisation steps (load-pipelined kernel),
+                                        // 5: per-channel rows cut into equal pieces over all lanes
+  int32_t cols = 0, upr = 0;
+  int32_t threads = kThreads;           // workgroup size = units per round
+  int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
+  uint32_t pool_slots = 0;
+  size_t lds_bytes = 0;
+  size_t first_item = 0, n_items = 0;
+};
+
+typedef void (*LaneLaunch)(const LaneClass&, const MatDesc*, const WorkItem*, const KParams&, hipStream_t);
+struct LaneKernel {
+  const void* fn = nullptr;       // for hipFuncSetAttribute
+  LaneLaunch launch = nullptr;
+};
+
+template <int DT> LaneKernel pick_units_kernel(const LaneClass& lc);     // kind 1
+template <int DT> LaneKernel pick_channel_kernel(const LaneClass& lc);   // kinds 2 and 5
+template <int DT> LaneKernel pick_rtn_kernel(const LaneClass& lc);       // kind 3
+
+}  // namespace eq

@@ -1,0 +1,42 @@
+// Instantiations of the per-channel lane kernels for one input type, EQ_TU_DT.
+#include "eq_channel128.h"
+#include "eq_channel_split.h"
+#include "eq_launch.h"
+
+namespace eq {
+
+template <int DT>
+LaneKernel pick_channel_kernel(const LaneClass& lc) {
+  LaneKernel k;
+  if (lc.kind == 5) {
+    // rows cut into equal pieces (fp16 only); chunks_per_thread carries the variant chosen by the plan
+#define EQ_SPLIT_VARIANT(ID_, P_, LPR_)                                                                         \
+  if (DT == EQ_F16 && lc.chunks_per_thread == ID_) {                                                            \
+    k.fn = reinterpret_cast<const void*>(&quantize_channels_split<P_, LPR_>);                                   \
+    k.launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& kp, hipStream_t s) { \
+      hipLaunchKernelGGL((quantize_channels_split<P_, LPR_>), dim3((unsigned)c.n_items), dim3(kChanThreads),    \
+                         c.lds_bytes, s, dm, di + c.first_item, kp);                                            \
+    };                                                                                                          \
+  }
+#if EQ_TU_DT == 0   // EQ_F16
+    EQ_SPLIT_VARIANT(1, 43, 256) EQ_SPLIT_VARIANT(2, 43, 128) EQ_SPLIT_VARIANT(3, 27, 256) EQ_SPLIT_VARIANT(4, 35, 256)
+#endif
+#undef EQ_SPLIT_VARIANT
+    return k;
+  }
+#define EQ_CHAN_VARIANT(K_)                                                                                     \
+  if (lc.chunks_per_thread == K_) {                                                                             \
+    k.fn = reinterpret_cast<const void*>(&quantize_channels128<DT, K_>);                                        \
+    k.launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& kp, hipStream_t s) { \
+      hipLaunchKernelGGL((quantize_channels128<DT, K_>), dim3((unsigned)c.n_items), dim3(kChanThreads),         \
+                         c.lds_bytes, s, dm, di + c.first_item, kp);                                            \
+    };                                                                                                          \
+  }
+  EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
+#undef EQ_CHAN_VARIANT
+  return k;
+}
+
+template LaneKernel pick_channel_kernel<EQ_TU_DT>(const LaneClass&);
+
+}  // namespace eq
