@@ -168,7 +168,9 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     LaneClass lc;
     lc.cols = (int32_t)c;
     lc.upr = (int32_t)upr;
-    if (pl.path[(size_t)order[k]] == 2) {
+    const char* chan_which = std::getenv("EASYQUANT_CHANNEL_KERNEL");
+    const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && p->iters == 0 && !(chan_which && std::strcmp(chan_which, "128") == 0);
+    if (pl.path[(size_t)order[k]] == 2 && !chan_rtn) {
       // per-channel: a round is floor(256 / segments) whole rows; items are multiples of that
       lc.kind = 2;
       lc.threads = kChanThreads;
@@ -208,7 +210,8 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     }
     if (p->iters == 0) {
       // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
-      lc.kind = 3;
+      // (per-channel rows: the same kernel with one range per row)
+      lc.kind = chan_rtn ? 6 : 3;
       // two-wavefront workgroups (four per compute unit) for rows of up to 8192: measured 4 % faster
       // than four-wavefront ones, whose barriers hold more wavefronts; longer rows take four
       // wavefronts (two workgroups per compute unit, 15 % faster on rows of 22016 than one of eight)
@@ -357,7 +360,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   for (const LaneClass& lc : pl.classes) {
     if (lc.n_items == 0) continue;
     // the kernels of each family are instantiated in a translation unit of their own (eq_launch.h)
-    const LaneKernel lk = lc.kind == 3 ? pick_rtn_kernel<DT>(lc)
+    const LaneKernel lk = (lc.kind == 3 || lc.kind == 6) ? pick_rtn_kernel<DT>(lc)
                           : (lc.kind == 2 || lc.kind == 5) ? pick_channel_kernel<DT>(lc) : pick_units_kernel<DT>(lc);
     const void* fn = lk.fn;
     const LaneLaunch launch = lk.launch;

@@ -45,6 +45,8 @@ struct BatchScratch {
   uint32_t rowcnt[RB];               // outliers of the row
   uint32_t rowpos[RB];               // next free entry of the row's run while it is written
   uint32_t slow[RB];                 // row takes the exact path
+  uint32_t rowmax_bits[RB];          // for kernels with one range per row: bit patterns of max(x, 0) and
+  uint32_t rownegmin_bits[RB];       // max(-x, 0) over the row's normal values
   uint32_t queue[NW][kQueue];        // per wavefront: row << 16 | chunk of its candidate chunks
 };
 

@@ -103,6 +103,21 @@ def test_per_channel_rows_cut_into_equal_pieces(cols, monkeypatch):
     assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
 
+@pytest.mark.parametrize("rows,cols", [(37, 4096), (9, 22016), (21, 8192), (40, 2048), (3, 32768), (11, 11008)])
+def test_per_channel_without_optimisation_steps(rows, cols, monkeypatch):
+    # iters = 0 with one range per row: the load-pipelined kernel in its per-row form
+    W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows * 3 + cols, device=DEV)
+    W[rows // 2] = 0                                     # an all-zero row keeps scale 1
+    for bits, mode in ((4, eqo.SYMMETRIC), (4, eqo.ASYMMETRIC), (3, eqo.ASYMMETRIC), (8, eqo.SYMMETRIC)):
+        res = _check(W, eqo.Params(bits=bits, group_size=0, mode=mode, iters=0), f"per-row rtn {rows}x{cols} {bits}-bit")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+    Wb = eq_inputs.gen_matrix(rows, cols, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=rows, device=DEV)
+    _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=cols, iters=0, stat_scope=eqo.STAT_MATRIX), f"per-row rtn bf16 {rows}x{cols}")
+    monkeypatch.setenv("EASYQUANT_CHANNEL_KERNEL", "128")  # the same through the kernel that optimises
+    res = _check(W, eqo.Params(bits=4, group_size=0, iters=0), f"channel kernel at T=0 {rows}x{cols}")
+    assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+
+
 def test_per_channel_lane_kernel_variants():
     W = eq_inputs.gen_matrix(19, 4096, eq_inputs.RECIPES["c5"], seed=77, device=DEV)
     _check(W, eqo.Params(bits=4, group_size=0, iters=0), "channel T=0")
