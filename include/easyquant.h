@@ -123,7 +123,7 @@ typedef struct eq_qmatrix {
  * depend on the choice): group_size 128 with row or matrix statistics and cols <= 32768 runs
  * one unit per lane (without optimisation steps, iters == 0, a load-pipelined variant of it);
  * one range per row with cols a multiple of 128 in 2048..32768 spreads the row over
- * cols / 128 lanes (fp16 rows of 11008, 13824, 17920 or 22016 columns with 4-bit codes: in
+ * cols / 128 lanes (rows of 11008, 13824, 17920 or 22016 columns with 4-bit codes: in
  * equal pieces over 128 or 256 lanes); everything else goes to a general kernel (one
  * workgroup per row, one wavefront per unit).  Four environment variables, read at every call, exist for tests and
  * measurements: EASYQUANT_UNITS_PER_ITEM=<n> sets the number of units a workgroup walks

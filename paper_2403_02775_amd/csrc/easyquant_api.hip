@@ -179,12 +179,12 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       lc.pool_slots = kChanThreads;
       lc.lds_bytes = (size_t)kChanHeader + (size_t)kChanThreads * kSlotBytes;
       int64_t rpr = std::min<int64_t>(kChanThreads / upr, kChanMaxRows);
-      // fp16 rows with 4-bit codes whose 128-element segments would leave many of the 256 lanes
+      // rows with 4-bit codes whose 128-element segments would leave many of the 256 lanes
       // idle (the MLP down-projections of the LLaMA shapes): equal pieces over all lanes instead
       // (eq_channel_split.h).  chunks_per_thread selects the instantiation.
       const char* which = std::getenv("EASYQUANT_CHANNEL_KERNEL");
       const int split = c == 86 * 256 ? 1 : c == 86 * 128 ? 2 : c == 54 * 256 ? 3 : c == 70 * 256 ? 4 : 0;
-      if (split && p->dtype == EQ_F16 && p->bits == 4 && !(which && std::strcmp(which, "128") == 0)) {
+      if (split && p->bits == 4 && !(which && std::strcmp(which, "128") == 0)) {
         lc.kind = 5;
         rpr = split == 2 ? 2 : 1;
         lc.chunks_per_thread = split;

@@ -10,18 +10,19 @@
 // their exact combination over the row (integer LDS atomics on rotating sets, 32-lane half sums
 // first) and the Adam step are those of eq_channel128.h.
 //
-// fp16 rows and 4-bit codes only (a pair of codes is then one byte of the row's stream, so the
-// lanes' P-byte pieces need no bit shifting); everything else keeps the 128-element kernel.
+// 4-bit codes only (a pair of codes is then one byte of the row's stream, so the lanes' P-byte
+// pieces need no bit shifting); other widths keep the 128-element kernel.  bf16 rows are served as
+// they are (the values sit widened in registers either way); one whose values span more than the
+// fixed-point planes hold takes the binary64 sums.
 #pragma once
 
 #include "eq_channel128.h"
 
 namespace eq {
 
-template <int P, int LPR>
+template <int DT, int P, int LPR>
 __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_channels_split(
     const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
-  constexpr int DT = EQ_F16;
   constexpr int NT = kChanThreads;
   constexpr int R = NT / LPR;                  // rows per round
   constexpr int EPL = 2 * P;                   // elements per lane
@@ -62,15 +63,27 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
     uint32_t x[P];
     {
       const uint32_t* src = reinterpret_cast<const uint32_t*>(pool + ((size_t)(valid ? my_row : 0u) * cols + (size_t)seg * EPL) * 2u);
-      uint32_t mnb = 0u, mxb = 0u;
+      float lmin = 0.0f, lmax = 0.0f;
+      if (DT == EQ_F16) {
+        uint32_t mnb = 0u, mxb = 0u;
 #pragma unroll
-      for (int j = 0; j < P; ++j) {
-        x[j] = src[j];
-        mnb = pk_min_f16(mnb, x[j]);
-        mxb = pk_max_f16(mxb, x[j]);
+        for (int j = 0; j < P; ++j) {
+          x[j] = src[j];
+          mnb = pk_min_f16(mnb, x[j]);
+          mxb = pk_max_f16(mxb, x[j]);
+        }
+        const half2_t mn = __builtin_bit_cast(half2_t, mnb), mx = __builtin_bit_cast(half2_t, mxb);
+        lmin = fminf((float)mn.x, (float)mn.y);
+        lmax = fmaxf((float)mx.x, (float)mx.y);
+      } else {
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+          x[j] = src[j];
+          const float x0 = widen16<DT>(x[j] & 0xFFFFu), x1 = widen16<DT>(x[j] >> 16);
+          lmin = fminf(lmin, fminf(x0, x1));
+          lmax = fmaxf(lmax, fmaxf(x0, x1));
+        }
       }
-      const half2_t mn = __builtin_bit_cast(half2_t, mnb), mx = __builtin_bit_cast(half2_t, mxb);
-      const float lmin = fminf((float)mn.x, (float)mn.y), lmax = fmaxf((float)mx.x, (float)mx.y);
       if (valid) {                               // non-negative floats order like their bit patterns
         atomicMax(&ra->max_bits, __float_as_uint(lmax));
         atomicMax(&ra->negmin_bits, __float_as_uint(0.0f - lmin));
@@ -109,8 +122,7 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       int a[4] = {0, 0, 0, 0}, bh[4] = {0, 0, 0, 0}, bl[4] = {0, 0, 0, 0};
 #pragma unroll
       for (int j = 0; j < P; ++j) {
-        const float x0 = __half2float(__ushort_as_half((unsigned short)(x[j] & 0xFFFFu)));
-        const float x1 = __half2float(__ushort_as_half((unsigned short)(x[j] >> 16)));
+        const float x0 = widen16<DT>(x[j] & 0xFFFFu), x1 = widen16<DT>(x[j] >> 16);
         const float t0 = __builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, kMagic), mlo, mhi);
         const float t1 = __builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, kMagic), mlo, mhi);
         const short2_t c = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm(__float_as_uint(t1), __float_as_uint(t0), 0x05040100u));
@@ -181,8 +193,7 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       unsigned char* dst = pool + (size_t)my_row * (cols / 2u) + (size_t)seg * P;
 #pragma unroll
       for (int j = 0; j < P; ++j) {
-        const float x0 = __half2float(__ushort_as_half((unsigned short)(x[j] & 0xFFFFu)));
-        const float x1 = __half2float(__ushort_as_half((unsigned short)(x[j] >> 16)));
+        const float x0 = widen16<DT>(x[j] & 0xFFFFu), x1 = widen16<DT>(x[j] >> 16);
         const uint32_t f0 = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi)) - (uint32_t)zodd;
         const uint32_t f1 = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi)) - (uint32_t)zodd;
         dst[j] = (unsigned char)((f0 & 0xFu) | ((f1 & 0xFu) << 4));

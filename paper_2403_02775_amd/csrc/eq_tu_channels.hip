@@ -9,18 +9,16 @@ template <int DT>
 LaneKernel pick_channel_kernel(const LaneClass& lc) {
   LaneKernel k;
   if (lc.kind == 5) {
-    // rows cut into equal pieces (fp16 only); chunks_per_thread carries the variant chosen by the plan
+    // rows cut into equal pieces; chunks_per_thread carries the variant chosen by the plan
 #define EQ_SPLIT_VARIANT(ID_, P_, LPR_)                                                                         \
-  if (DT == EQ_F16 && lc.chunks_per_thread == ID_) {                                                            \
-    k.fn = reinterpret_cast<const void*>(&quantize_channels_split<P_, LPR_>);                                   \
+  if (lc.chunks_per_thread == ID_) {                                                                            \
+    k.fn = reinterpret_cast<const void*>(&quantize_channels_split<DT, P_, LPR_>);                               \
     k.launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& kp, hipStream_t s) { \
-      hipLaunchKernelGGL((quantize_channels_split<P_, LPR_>), dim3((unsigned)c.n_items), dim3(kChanThreads),    \
+      hipLaunchKernelGGL((quantize_channels_split<DT, P_, LPR_>), dim3((unsigned)c.n_items), dim3(kChanThreads), \
                          c.lds_bytes, s, dm, di + c.first_item, kp);                                            \
     };                                                                                                          \
   }
-#if EQ_TU_DT == 0   // EQ_F16
     EQ_SPLIT_VARIANT(1, 43, 256) EQ_SPLIT_VARIANT(2, 43, 128) EQ_SPLIT_VARIANT(3, 27, 256) EQ_SPLIT_VARIANT(4, 35, 256)
-#endif
 #undef EQ_SPLIT_VARIANT
     return k;
   }

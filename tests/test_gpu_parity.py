@@ -79,7 +79,7 @@ def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, monkeypa
 
 @pytest.mark.parametrize("cols", [22016, 11008])
 def test_per_channel_rows_cut_into_equal_pieces(cols, monkeypatch):
-    # fp16 rows of 86 * 256 or 86 * 128 values with 4-bit codes take the kernel that cuts a row into
+    # rows of 86 * 256 or 86 * 128 values with 4-bit codes take the kernel that cuts a row into
     # equal pieces over all 256 lanes: its variants, its binary64 fallback, and the 128-element
     # kernel it replaces on the same input
     W = eq_inputs.gen_matrix(7, cols, eq_inputs.RECIPES["c5"], seed=cols, device=DEV)
@@ -97,6 +97,16 @@ def test_per_channel_rows_cut_into_equal_pieces(cols, monkeypatch):
     Wz[5, ::2] = 0.25
     Wz[5, 1::2] = -0.25                                  # every element exactly one sigma from the mean
     res = _check(Wz, eqo.Params(bits=4, group_size=0, iters=8), f"split {cols} degenerate rows")
+    assert res["excused_elems"] == 0
+    # bf16 rows: served as they are; a row with values far below the resolution of its planes
+    # sends the round to the binary64 sums
+    Wb = eq_inputs.gen_matrix(6, cols, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=cols + 1, device=DEV)
+    res = _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=0, iters=10, mode=eqo.ASYMMETRIC), f"split {cols} bf16")
+    assert res["excused_elems"] == 0
+    Wb[1, 5] = 1e-12
+    Wb[4, cols - 1] = -3e-20
+    Wb[2] = Wb[2] * 1e30
+    res = _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=0, iters=10), f"split {cols} bf16 wide span")
     assert res["excused_elems"] == 0
     monkeypatch.setenv("EASYQUANT_CHANNEL_KERNEL", "128")
     res = _check(W, eqo.Params(bits=4, group_size=0, iters=8), f"128-element kernel on {cols}")
