@@ -218,7 +218,7 @@ def main():
     if args.matvec:
         return bench_matvec(args)
     if args.gpus != 1:
-        sys.exit("bench.py: this build measures one GPU only (the path needs no communication; see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build measures one GPU only (matrices, rows and groups are independent: the path needs no communication between GPUs); run with --gpus 1")
 
     import torch
     import paper_2403_02775_amd as eqg
