@@ -56,3 +56,14 @@ def test_work_split_env_override_does_not_change_workspace_contract(lib, monkeyp
     monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", "256")
     c = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
     assert a > 0 and b > 0 and c >= a
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    # every box has one GPU; the benchmark says so instead of pretending to scale
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert res.returncode != 0
+    assert "one GPU only" in (res.stderr + res.stdout)
