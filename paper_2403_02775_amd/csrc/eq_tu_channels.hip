@@ -1,4 +1,7 @@
 // Instantiations of the per-channel lane kernels for one input type, EQ_TU_DT.
+#ifndef EQ_TU_DT
+#define EQ_TU_DT 0   // the build compiles this file once per input type (0: fp16, 1: bf16)
+#endif
 #include "eq_channel128.h"
 #include "eq_channel_split.h"
 #include "eq_launch.h"
