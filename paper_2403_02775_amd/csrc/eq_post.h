@@ -490,11 +490,21 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
           }
           uint4 wv;
           if (MODE == 2) {
+            // byte offsets into the row's table, four at a time: even elements, odd elements
             const uint32_t w = wq[r][j];
-            uint32_t h[8];
+            uint32_t ev = (w << 1) & 0x1E1E1E1Eu, od = (w >> 3) & 0x1E1E1E1Eu;
+            asm("" : "+v"(ev), "+v"(od));     // keep the two words: a byte of them is one bit-field extract away
+            const unsigned char* tab = reinterpret_cast<const unsigned char*>(&lut[r][0]);
+            typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+            uint32_t pr[4];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) h[k] = lut[r][(w >> (4 * k)) & 15u];
-            wv = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            for (int k = 0; k < 4; ++k) {
+              ushort2_t h;
+              h.x = *reinterpret_cast<const unsigned short*>(tab + ((ev >> (8 * k)) & 0xFFu));
+              h.y = *reinterpret_cast<const unsigned short*>(tab + ((od >> (8 * k)) & 0xFFu));
+              pr[k] = __builtin_bit_cast(uint32_t, h);
+            }
+            wv = make_uint4(pr[0], pr[1], pr[2], pr[3]);
           } else {
             wv = dequantize_chunk4<DT>(wq[r][j], s, zf);
           }
