@@ -474,3 +474,34 @@ def test_config2_llama7b_attention_projection():
     compare_sse(raw, dg, eqo.dequantize(want, 4096, 4096, p), p, res["rows_ok"], "c2")
     frac = got[0]["out_row_ptr"][-1] / raw.size
     assert 0.004 < frac < 0.008
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_randomised_parameter_sweep(seed):
+    """Seeded random combinations of shape, input type, code width, group size, mode, steps, threshold,
+    statistic scope and iterate selection, so that combinations nobody thought of are compared too."""
+    import random
+    rng = random.Random(seed)
+    for case in range(60):
+        dtype = rng.choice(["f16", "f16", "bf16"])
+        cols = rng.choice([128, 256, 384, 640, 1024, 1280, 2048, 2176, 3072, 4096, 5120, 6144, 8192, 11008, 13824, 17920, 22016])
+        rows = rng.randint(1, 20 if cols <= 4096 else 6)
+        bits = rng.choice([2, 3, 4, 4, 4, 5, 6, 7, 8])
+        G = rng.choice([0, 0, 128, 128, 128, cols, 64, 32, 256])
+        if G and cols % G:
+            G = 128
+        recipe = eq_inputs.RECIPES[rng.choice(["c2", "c3", "c5"])]
+        if dtype == "bf16":
+            recipe = eq_inputs.with_dtype(recipe, "bf16")
+        W = eq_inputs.gen_matrix(rows, cols, recipe, seed=rng.randint(0, 10 ** 6), device=DEV)
+        if rng.random() < 0.2:
+            W[rng.randrange(rows)] = 0
+        if rng.random() < 0.15:
+            W[rng.randrange(rows)] *= rng.choice([1e-3, 30.0, 2000.0 if dtype == "f16" else 1e20])
+        p = eqo.Params(dtype=eqo.F16 if dtype == "f16" else eqo.BF16, bits=bits, group_size=G,
+                       mode=rng.choice([eqo.SYMMETRIC, eqo.ASYMMETRIC]), iters=rng.choice([0, 0, 1, 2, 5, 9, 14]),
+                       n_sigma=rng.choice([3.0, 3.0, 2.5, 2.0, 1.0, 0.7, 4.0, float("inf")]),
+                       stat_scope=rng.choice([eqo.STAT_ROW, eqo.STAT_ROW, eqo.STAT_ROW, eqo.STAT_MATRIX, eqo.STAT_GROUP]),
+                       select=rng.choice([eqo.SELECT_BEST, eqo.SELECT_LAST]), lr=rng.choice([1e-3, 1e-4, 5e-3]))
+        res = _check(W, p, f"sweep {seed}/{case} {dtype} n={p.n_sigma} scope={p.stat_scope} select={p.select} lr={p.lr}")
+        assert res["excused_elems"] == 0
