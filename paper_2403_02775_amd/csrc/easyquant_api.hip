@@ -179,6 +179,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       lc.pool_slots = kChanThreads;
       lc.lds_bytes = (size_t)kChanHeader + (size_t)kChanThreads * kSlotBytes;
       int64_t rpr = std::min<int64_t>(kChanThreads / upr, kChanMaxRows);
+      if (p->bits <= 4 && (c == 2048 || c == 4096 || c == 8192)) lc.kind = 7;   // lane count known at compile time
       // rows with 4-bit codes whose 128-element segments would leave many of the 256 lanes
       // idle (the MLP down-projections of the LLaMA shapes): equal pieces over all lanes instead
       // (eq_channel_split.h).  chunks_per_thread selects the instantiation.
@@ -361,7 +362,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
     if (lc.n_items == 0) continue;
     // the kernels of each family are instantiated in a translation unit of their own (eq_launch.h)
     const LaneKernel lk = (lc.kind == 3 || lc.kind == 6) ? pick_rtn_kernel<DT>(lc)
-                          : (lc.kind == 2 || lc.kind == 5) ? pick_channel_kernel<DT>(lc) : pick_units_kernel<DT>(lc);
+                          : (lc.kind == 2 || lc.kind == 5 || lc.kind == 7) ? pick_channel_kernel<DT>(lc) : pick_units_kernel<DT>(lc);
     const void* fn = lk.fn;
     const LaneLaunch launch = lk.launch;
     if (!fn) return EQ_E_UNSUPPORTED;

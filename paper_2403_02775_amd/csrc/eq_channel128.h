@@ -59,7 +59,9 @@ __device__ __forceinline__ int group_sum_dpp(int v) {
 }
 
 // K = 16-byte chunks of a row per thread (cols <= 8 * K * 256); rows are staged 16 / K at a time.
-template <int DT, int K>
+// FULL: cols == 8 * K * 256 exactly, i.e. rows of 2048, 4096 or 8192 elements over 16, 32 or 64 lanes:
+// the lane count is then a compile-time constant and the in-wavefront combination is the only path.
+template <int DT, int K, bool FULL>
 __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_channels128(
     const MatDesc* __restrict__ mats, const WorkItem* __restrict__ items, KParams kp) {
   constexpr int NT = kChanThreads;
@@ -72,7 +74,8 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
   unsigned char* pool = smem + kChanHeader;
   const WorkItem it = items[blockIdx.x];
   const MatDesc md = mats[it.mat];
-  const uint32_t segs = (uint32_t)md.cols >> 7;                 // lanes per row
+  static_assert(!FULL || K <= 4, "in-wavefront sums serve rows of up to 64 lanes");
+  const uint32_t segs = FULL ? 16u * K : (uint32_t)md.cols >> 7;   // lanes per row
   const uint32_t R = min((uint32_t)NT / segs, (uint32_t)kChanMaxRows);
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const uint32_t my_row = tid / segs, seg = tid - my_row * segs;
@@ -147,7 +150,8 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       //    instead of 64 single shares (64 atomics on one address serialise).
       // The 32-bit group sums need |level| <= 15, i.e. at most 4 bits.
       const bool small_levels = kp.bits <= 4;
-      const bool in_wave = small_levels && (segs == 16u || segs == 32u || segs == 64u);     // uniform over the grid
+      // uniform over the grid (FULL kernels are launched for code widths of at most 4 bits only)
+      const bool in_wave = FULL || (small_levels && (segs == 16u || segs == 32u || segs == 64u));
       const uint32_t half_row = (uint32_t)__shfl((int)my_row, (int)(lane & 32u));
       const bool half_valid = __shfl((int)valid, (int)(lane & 32u)) != 0;
       const bool halves_uniform = small_levels && __all(!valid || my_row == half_row);      // uniform over the wavefront

@@ -21,7 +21,8 @@ struct LaneClass {
   int32_t kind = 1;                     // 1: one lane per group of 128, 2: per-channel rows spread over lanes,
                                         // 3: group of 128 without optimisation steps (load-pipelined kernel),
                                         // 5: per-channel rows cut into equal pieces over all lanes,
-                                        // 6: per-channel rows without optimisation steps (kernel of kind 3, one range per row)
+                                        // 6: per-channel rows without optimisation steps (kernel of kind 3, one range per row),
+                                        // 7: kind 2 for rows of exactly 2048, 4096 or 8192 elements and at most 4 bits
   int32_t cols = 0, upr = 0;
   int32_t threads = kThreads;           // workgroup size = units per round
   int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
@@ -37,7 +38,7 @@ struct LaneKernel {
 };
 
 template <int DT> LaneKernel pick_units_kernel(const LaneClass& lc);     // kind 1
-template <int DT> LaneKernel pick_channel_kernel(const LaneClass& lc);   // kinds 2 and 5
+template <int DT> LaneKernel pick_channel_kernel(const LaneClass& lc);   // kinds 2, 5 and 7
 template <int DT> LaneKernel pick_rtn_kernel(const LaneClass& lc);       // kinds 3 and 6
 
 }  // namespace eq

@@ -25,15 +25,16 @@ LaneKernel pick_channel_kernel(const LaneClass& lc) {
 #undef EQ_SPLIT_VARIANT
     return k;
   }
-#define EQ_CHAN_VARIANT(K_)                                                                                     \
-  if (lc.chunks_per_thread == K_) {                                                                             \
-    k.fn = reinterpret_cast<const void*>(&quantize_channels128<DT, K_>);                                        \
+#define EQ_CHAN_VARIANT(K_, FULL_)                                                                              \
+  if (lc.chunks_per_thread == K_ && (lc.kind == 7) == FULL_) {                                                  \
+    k.fn = reinterpret_cast<const void*>(&quantize_channels128<DT, K_, FULL_>);                                 \
     k.launch = [](const LaneClass& c, const MatDesc* dm, const WorkItem* di, const KParams& kp, hipStream_t s) { \
-      hipLaunchKernelGGL((quantize_channels128<DT, K_>), dim3((unsigned)c.n_items), dim3(kChanThreads),         \
+      hipLaunchKernelGGL((quantize_channels128<DT, K_, FULL_>), dim3((unsigned)c.n_items), dim3(kChanThreads),  \
                          c.lds_bytes, s, dm, di + c.first_item, kp);                                            \
     };                                                                                                          \
   }
-  EQ_CHAN_VARIANT(1) EQ_CHAN_VARIANT(2) EQ_CHAN_VARIANT(4) EQ_CHAN_VARIANT(8) EQ_CHAN_VARIANT(16)
+  EQ_CHAN_VARIANT(1, false) EQ_CHAN_VARIANT(2, false) EQ_CHAN_VARIANT(4, false) EQ_CHAN_VARIANT(8, false) EQ_CHAN_VARIANT(16, false)
+  EQ_CHAN_VARIANT(1, true) EQ_CHAN_VARIANT(2, true) EQ_CHAN_VARIANT(4, true)
 #undef EQ_CHAN_VARIANT
   return k;
 }
