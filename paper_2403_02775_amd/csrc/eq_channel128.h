@@ -94,8 +94,13 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       cs->inexact = 0;
       cs->keep_bf16 = 0;
     }
-    for (uint32_t b = 0; b < nr; b += RB)       // ends with a barrier, which also publishes the clears above
-      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, row0 + b, (int)min((uint32_t)RB, nr - b), pool, b * segs * 16u, sc);
+    for (uint32_t b = 0; b < nr; b += RB) {     // ends with a barrier, which also publishes the clears above
+      uint32_t ch0 = b * segs * 16u;
+      // opaque on purpose: with a compile-time lane count the compiler would otherwise keep every
+      // thread's 16 pool addresses alive across the whole kernel, in scratch memory
+      asm volatile("" : "+s"(ch0));
+      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, row0 + b, (int)min((uint32_t)RB, nr - b), pool, ch0, sc);
+    }
 
     const bool valid = my_row < nr;
     unsigned char* slot = pool + (size_t)(valid ? tid : 0u) * kSlotBytes;
