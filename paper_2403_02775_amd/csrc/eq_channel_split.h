@@ -174,6 +174,7 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
         A = (double)ra->cc[set];
         double b = 0.0;
         const uint32_t first = (valid ? my_row : 0u) * LPR;
+#pragma unroll 4
         for (uint32_t j = 0; j < (uint32_t)LPR; ++j) b += cs->part[first + j];
         B = b;
         if (valid && seg == 0) ra->cc[(pass + 2u) % 3u] = 0;
