@@ -84,7 +84,7 @@ typedef struct eq_params {
   float   n_sigma;     /* threshold n of Eq. 3; 2.5..3 in the paper; +inf disables outliers */
   int32_t iters;       /* Adam steps T on the range (100 / 500 in the paper); 0 = outlier-aware RTN */
   float   lr;          /* Adam step size on the range (1e-3 / 1e-4 in the paper) */
-  float   beta1, beta2, eps; /* Adam moments and epsilon (paper silent: 0.9, 0.999, 1e-8) */
+  float   beta1, beta2, eps; /* Adam moments in [0, 1) and epsilon > 0 (paper silent: 0.9, 0.999, 1e-8) */
   int32_t select;      /* EQ_SELECT_* */
 } eq_params;
 
@@ -188,7 +188,8 @@ EQ_API void eq_default_params(eq_params* p);
  * (the kernels that run Algorithm 1's "Quantize"; not the small reset / prefix-sum / gather
  * kernels around them) is bracketed by HIP events on the call's stream.
  * eq_profile_read waits for those events, returns the summed kernel time in milliseconds and
- * the number of launches since the last read, and forgets them.  Not thread-safe. */
+ * the number of launches since the last read, and forgets them.  The list of events is shared by
+ * all host threads of the process (a lock guards it): a read returns every thread's launches. */
 EQ_API int eq_profile_enable(int on);
 EQ_API int eq_profile_read(double* kernel_ms, int32_t* launches);
 

@@ -261,6 +261,8 @@ def optimise_range(units: UnitView, p: Params, trace: Optional[list] = None):
     r0 = units.r0.astype(_f32)
     r32 = np.where(act, r0, _f32(1.0) * units.D).astype(_f32)   # inactive: s = 1
     lr, b1, b2, eps = (_f64(_f32(v)) for v in (p.lr, p.beta1, p.beta2, p.eps))
+    if not eps > 0:
+        raise ValueError("eps must be positive (a zero gradient would step by 0 / 0)")
     m = np.zeros(nu, _f64)
     v = np.zeros(nu, _f64)
     p1 = _f64(1.0)

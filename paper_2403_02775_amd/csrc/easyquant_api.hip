@@ -7,6 +7,8 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
+#include <mutex>
 #include <numeric>
 #include <vector>
 
@@ -26,7 +28,9 @@ using namespace eq;
 thread_local int g_last_hip_error = 0;
 
 // ---- optional event bracketing of the main kernels (eq_profile_*) ----
-bool g_profile = false;
+// (calls from several host threads may bracket kernels at once: the list has a lock)
+std::atomic<bool> g_profile{false};
+std::mutex g_events_lock;
 std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
 
 struct ScopedKernelTimer {
@@ -40,6 +44,7 @@ struct ScopedKernelTimer {
   ~ScopedKernelTimer() {
     if (!a) return;
     (void)hipEventRecord(b, st);
+    std::lock_guard<std::mutex> hold(g_events_lock);
     g_events.emplace_back(a, b);
   }
 };
@@ -62,7 +67,7 @@ bool params_ok(const eq_params* p) {
   if (!(p->n_sigma >= 0.0f)) return false;                 // NaN or negative
   if (!(p->lr >= 0.0f) || !std::isfinite(p->lr)) return false;
   if (!(p->beta1 >= 0.0f && p->beta1 < 1.0f) || !(p->beta2 >= 0.0f && p->beta2 < 1.0f)) return false;
-  if (!(p->eps >= 0.0f) || !std::isfinite(p->eps)) return false;
+  if (!(p->eps > 0.0f) || !std::isfinite(p->eps)) return false;   // 0 would make a zero gradient's step 0 / 0
   return true;
 }
 
@@ -467,7 +472,12 @@ int eq_profile_read(double* kernel_ms, int32_t* launches) {
   double total = 0.0;
   int32_t cnt = 0;
   int rc = EQ_OK;
-  for (auto& ev : g_events) {
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+  {
+    std::lock_guard<std::mutex> hold(g_events_lock);
+    events.swap(g_events);
+  }
+  for (auto& ev : events) {
     float ms = 0.0f;
     hipError_t e = hipEventSynchronize(ev.second);
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
@@ -477,7 +487,6 @@ int eq_profile_read(double* kernel_ms, int32_t* launches) {
     (void)hipEventDestroy(ev.first);
     (void)hipEventDestroy(ev.second);
   }
-  g_events.clear();
   if (kernel_ms) *kernel_ms = total;
   if (launches) *launches = cnt;
   return rc;

@@ -4,6 +4,11 @@ import sys
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+# The pins themselves are tested by running them against copies of the oracle with a planted
+# mistake (test_pins_catch_mistakes.py): that directory's `oracle` package then comes first.
+_ALT = os.environ.get("EASYQUANT_ORACLE_UNDER_TEST")
+if _ALT:
+    sys.path.insert(0, _ALT)
 
 
 def pytest_configure(config):

@@ -64,6 +64,10 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.eq_quantize_matrix(None, 8, 8, 8, None, ctypes.byref(q), None, 0, None) == -1
     bad = eqg.Params(bits=1).c()
     assert lib.eq_quantize_matrix(None, 8, 8, 8, ctypes.byref(bad), ctypes.byref(q), None, 0, None) == -3
+    # hyper-parameters out of range: epsilon must be positive, the moments' decay below 1, lr finite
+    for kw in ({"eps": 0.0}, {"beta1": 1.0}, {"beta2": -0.1}, {"lr": float("inf")}, {"n_sigma": float("nan")}, {"iters": -1}):
+        badp = eqg.Params(**kw).c()
+        assert lib.eq_quantize_matrix(None, 8, 8, 8, ctypes.byref(badp), ctypes.byref(q), None, 0, None) == -3, kw
     # cols not a multiple of 8, ld < cols, group that does not divide cols, row too long
     assert lib.eq_quantize_matrix(None, 8, 12, 16, ctypes.byref(cp), ctypes.byref(q), None, 0, None) == -2
     assert lib.eq_quantize_matrix(None, 8, 16, 8, ctypes.byref(cp), ctypes.byref(q), None, 0, None) == -2

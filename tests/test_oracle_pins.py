@@ -132,6 +132,10 @@ def test_mask_matches_plain_definition_and_chebyshev():
     assert (mg.reshape(-1, 128) == eq.outlier_mask(x.reshape(-1, 128), 3.0, eq.STAT_ROW, 0)).all()
     mm = eq.outlier_mask(x, 3.0, eq.STAT_MATRIX, 0)
     assert (mm.reshape(1, -1) == eq.outlier_mask(x.reshape(1, -1), 3.0, eq.STAT_ROW, 0)).all()
+    # Eq. 3 prints >=: a value exactly n sigma from the mean is an outlier (+-a: mean 0, sigma a, all exact)
+    pm = np.array([[0.5, -0.5] * 4], np.float32)
+    assert eq.outlier_mask(pm, 1.0, eq.STAT_ROW, 0).all()
+    assert not eq.outlier_mask(pm, 1.0 + 2.0 ** -10, eq.STAT_ROW, 0).any()
     # constant scope: no outliers; n = infinity: none
     assert not eq.outlier_mask(np.full((2, 64), 0.5, np.float32), 3.0, eq.STAT_ROW, 0).any()
     assert not eq.outlier_mask(x, float("inf"), eq.STAT_ROW, 0).any()
@@ -183,6 +187,7 @@ def test_asymmetric_initialisation():
     # all-positive data: the range still includes 0, so zero-point 0
     q2 = eq.quantize_matrix(_raw16(np.abs(x) + 1), p)
     assert int(q2["zero_points"][0, 0]) == 0
+    assert float(q2["scales"][0, 0]) == float(np.float32(2.0) / np.float32(15.0))      # range = max - 0, not max - min
 
 
 # --------------------------------------------------------------------------- #
@@ -336,6 +341,48 @@ def test_optimised_range_vs_brute_force_scan(mode, bits):
     assert np.median(ratios) < 1.05, (np.median(ratios), max(ratios))
 
 
+@pytest.mark.parametrize("iters,lr", [(3, 1e-3), (60, 2e-3)])
+def test_best_iterate_is_the_argmin_over_the_trajectory(iters, lr):
+    """The returned range is the iterate r_0 .. r_T with the smallest Eq. 1 loss, the loss recomputed
+    here from its definition.  Few small steps: the last iterate is the best one in some units;
+    many larger ones: Adam dithers and an earlier iterate wins."""
+    rec = eq_inputs.RECIPES["c1"]
+    w = eq_inputs.gen_matrix(16, 128, rec, seed=21)
+    raw = w.view(torch.int16).numpy().view(np.uint16)
+    p = eq.Params(bits=4, group_size=0, iters=iters, lr=lr)
+    tr = []
+    q = eq.quantize_matrix(raw, p, tr)
+    tr = np.array(tr)                                   # (T + 1) x units, binary32
+    assert tr.shape == (iters + 1, 16)
+    units = eq.UnitView(eq.widen(raw, eq.F16), q["mask"], p)
+    D = np.float32(units.D)
+    where = []
+    for i in range(16):
+        x = units.xt[i].astype(np.float64)[~q["mask"][i]]
+        lo, hi = float(units.c_lo[i]), float(units.c_hi[i])
+        losses = [_loss_eq1(x, float(np.float32(r) / D), lo, hi) for r in tr[:, i]]
+        chosen = _loss_eq1(x, float(q["scales"][i, 0]), lo, hi)
+        assert chosen <= min(losses) * (1 + 1e-9) + 1e-15
+        assert any(np.float32(q["range"][i, 0]) == np.float32(r) for r in tr[:, i])
+        where.append(int(np.argmin(losses)))
+    if iters == 3:
+        assert where.count(iters) >= 2                  # the iterate after the last step can win
+    else:
+        assert sum(1 for k in where if 0 < k < iters) >= 8   # ... and so can one in the middle
+
+
+def test_range_never_drops_below_its_floor():
+    """A learning rate far above the range: the first step would make the range negative; it stops
+    at r0 / 1024 and stays finite and positive from there on."""
+    x = np.array([[0.75] + [0.4375] * 7])               # rounds up at r0: sum (Q - x) c > 0, the range shrinks
+    p = eq.Params(bits=3, group_size=0, n_sigma=float("inf"), iters=4, lr=10.0, select=eq.SELECT_LAST)
+    tr = []
+    eq.quantize_matrix(_raw16(x), p, tr)
+    tr = np.array(tr, np.float64).reshape(-1)
+    assert tr[0] == 0.75 and tr[1] == 0.75 * 2.0 ** -10
+    assert np.isfinite(tr).all() and (tr >= 0.75 * 2.0 ** -10).all()
+
+
 def test_select_last_is_the_final_iterate_and_best_is_no_worse():
     rec = eq_inputs.RECIPES["c2"]
     w = eq_inputs.gen_matrix(8, 512, rec, seed=13)
@@ -408,6 +455,8 @@ def test_degenerate_units():
     assert q["codes"].shape == (0, 8) and q["out_row_ptr"].tolist() == [0]
     with pytest.raises(ValueError):
         eq.quantize_matrix(np.full((1, 64), 0x7C00, np.uint16), p)   # +inf
+    with pytest.raises(ValueError):
+        eq.quantize_matrix(raw, eq.Params(bits=4, group_size=32, iters=5, eps=0.0))
 
 
 def test_pack_unpack_and_bf16_rounding_against_torch():
