@@ -196,7 +196,7 @@ def bench_matvec(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama65b_f16_w4g128", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=-1, help="limit the number of layers (debugging; changes the workload)")
