@@ -21,7 +21,10 @@
  *    never allocates, frees or retains device memory.  Every pointer marked HOST is
  *    read before the call returns.
  *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
- *    default stream) and return without waiting for it.
+ *    default stream) and return without waiting for it.  The quantize calls first copy
+ *    their descriptors from pageable host memory into the workspace on that stream; the
+ *    runtime may hold such a copy, and with it the call, until work queued earlier on the
+ *    same stream has finished.
  *  - Return value: EQ_OK or a negative EQ_E_* code for problems visible on the host
  *    (nothing is enqueued then).  Conditions only the GPU can see are reported in
  *    the per-matrix DEVICE status word (EQ_S_* bits), valid once the stream is idle.
