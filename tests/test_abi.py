@@ -76,3 +76,33 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.eq_quantize_matrix(None, 8, 1 << 20, 1 << 20, ctypes.byref(cp), ctypes.byref(q), None, 0, None) == -6
     assert lib.eq_dequantize(None, 8, 8, ctypes.byref(cp), None, 8, None) == -1
     assert lib.eq_quantize_batch(0, None, None, None, None, None, None, None, 0, None) == 0
+
+
+def test_header_is_plain_c_and_links_from_a_c_program(lib, tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and a C program linked against the
+    library can call it (host-only entry points here; nothing touches a GPU)."""
+    import shutil
+    import subprocess
+    import paper_2403_02775_amd as eqg
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_abi.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include "easyquant.h"
+int main(void) {
+  eq_params p;
+  eq_default_params(&p);
+  eq_qmatrix q = {0};
+  int rc = eq_quantize_matrix(NULL, 8, 12, 16, &p, &q, NULL, 0, NULL);   /* cols not a multiple of 8 */
+  printf("%d %d %lld %d %s\n", p.bits, p.iters, (long long)eq_code_words_per_row(4096, 3), rc, eq_strerror(rc));
+  return 0;
+}
+""")
+    exe = tmp_path / "use_abi"
+    libdir = os.path.dirname(eqg.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-leasyquant", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split(None, 4)
+    assert out[:4] == ["4", "100", "384", "-2"] and "rows" in out[4]
