@@ -7,7 +7,7 @@ import torch
 import eq_inputs
 import paper_2403_02775_amd as eqg
 from oracle import easyquant_oracle as eqo
-from parity import compare, compare_sse, gpu_dequantize, raw_of, run_gpu, to_gpu_params
+from parity import compare, compare_sse, fetch, gpu_dequantize, raw_of, run_gpu, to_gpu_params
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -391,6 +391,31 @@ def test_edge_cases_empty_constant_and_zero_rows():
         We = torch.zeros(shape, dtype=torch.float16, device=DEV)
         outs, got = run_gpu([We], p)
         assert got[0]["status"] == 0 and (got[0]["out_row_ptr"] == 0).all()
+
+
+def test_calls_on_two_streams_do_not_share_state():
+    """Two calls with their own outputs and workspaces, in flight together on two streams (default
+    priority), give the bytes each gives alone: the library keeps no device state of its own."""
+    rec = eq_inputs.RECIPES["c5"]
+    p = eqo.Params(bits=4, group_size=128, iters=30)
+    gp = to_gpu_params(p)
+    jobs = []
+    for i, (r, c) in enumerate([(1500, 4096), (700, 8192)]):
+        W = eq_inputs.gen_matrix(r, c, rec, seed=900 + i, device=DEV)
+        cap = eqg.eq_outlier_capacity_bound(r, c, p.n_sigma)
+        _, alone = run_gpu([W], p)
+        out = eqg.alloc_outputs(r, c, gp, cap, DEV)
+        ws = torch.empty(eqg.eq_workspace_bytes([r], [c], [cap], gp), dtype=torch.uint8, device=DEV)
+        jobs.append((W, out, ws, alone[0], torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for _ in range(2):                                     # the second pass finds both streams busy
+        for W, out, ws, _, st in jobs:
+            eqg.eq_quantize_batch([W], gp, [out], ws, stream=st)
+    torch.cuda.synchronize()
+    for W, out, ws, alone, st in jobs:
+        got = fetch(out, W.shape[0], W.shape[1], p)
+        for k in alone:
+            assert np.array_equal(got[k], alone[k]), k
 
 
 def test_batch_of_mixed_shapes_matches_single_calls_and_is_deterministic():
