@@ -418,6 +418,46 @@ def test_calls_on_two_streams_do_not_share_state():
             assert np.array_equal(got[k], alone[k]), k
 
 
+def test_calls_from_two_host_threads():
+    """The header promises thread safety for calls with distinct outputs and workspaces: two host
+    threads (ctypes drops the interpreter lock during a call) each repeat their own call on their own
+    stream and find the bytes of a single-threaded run every time."""
+    import threading
+    rec = eq_inputs.RECIPES["c2"]
+    p = eqo.Params(bits=4, group_size=128, iters=10)
+    gp = to_gpu_params(p)
+    jobs = []
+    for i, (r, c) in enumerate([(300, 2048), (200, 4096)]):
+        W = eq_inputs.gen_matrix(r, c, rec, seed=950 + i, device=DEV)
+        cap = eqg.eq_outlier_capacity_bound(r, c, p.n_sigma)
+        _, alone = run_gpu([W], p)
+        out = eqg.alloc_outputs(r, c, gp, cap, DEV)
+        ws = torch.empty(eqg.eq_workspace_bytes([r], [c], [cap], gp), dtype=torch.uint8, device=DEV)
+        jobs.append((W, out, ws, alone[0], torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(job):
+        W, out, ws, alone, st = job
+        try:
+            for _ in range(8):
+                eqg.eq_quantize_batch([W], gp, [out], ws, stream=st)
+                st.synchronize()
+                got = fetch(out, W.shape[0], W.shape[1], p)
+                for k in alone:
+                    assert np.array_equal(got[k], alone[k]), k
+        except Exception as e:                               # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads)
+    assert not errors, errors
+
+
 def test_batch_of_mixed_shapes_matches_single_calls_and_is_deterministic():
     rec = eq_inputs.RECIPES["c5"]
     Ws = [eq_inputs.gen_matrix(r, c, rec, seed=50 + i, device=DEV) for i, (r, c) in
