@@ -133,7 +133,8 @@ typedef struct eq_qmatrix {
  * through (changes only how the work is cut up), EASYQUANT_FORCE_GENERAL=1 sends every
  * matrix to the general kernel, EASYQUANT_RTN_THREADS=256 | 512 runs the iters == 0 variant
  * with workgroups of 256 threads for every row length (default: 128 up to 8192 columns, 256
- * beyond) or of 512 threads for rows longer than 8192, EASYQUANT_CHANNEL_KERNEL=128 keeps
+ * beyond, 192 for 8193..12288 and 16385..24576) or of 512 threads for rows longer than 8192,
+ * EASYQUANT_CHANNEL_KERNEL=128 keeps
  * per-channel rows on the kernel with 128-element segments also where another one would
  * serve them (rows of 11008, 13824, 17920 and 22016 columns; iters == 0). */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,

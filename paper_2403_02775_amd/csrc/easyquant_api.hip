@@ -222,6 +222,9 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // than four-wavefront ones, whose barriers hold more wavefronts; longer rows take four
       // wavefronts (two workgroups per compute unit, 15 % faster on rows of 22016 than one of eight)
       lc.threads = c > 8192 ? 256 : 128;
+      // three wavefronts where the chunks per thread stay the same power of two (8 up to 12288
+      // columns, 16 up to 24576): fewer idle lanes and empty load slots (11008: 90 % instead of 67 %)
+      if ((c > 8192 && c <= 12288) || (c > 16384 && c <= 24576)) lc.threads = 192;
       if (const char* ov = std::getenv("EASYQUANT_RTN_THREADS")) {
         const long t = std::atol(ov);
         if (t == 256) lc.threads = 256;
@@ -233,7 +236,11 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       const int64_t rpb = 16 / lc.chunks_per_thread;
       lc.pool_slots = (uint32_t)(rpb * upr);
       lc.lds_bytes = (size_t)kLdsHeader + (size_t)lc.pool_slots * kSlotBytes;
-      int64_t target = std::min<int64_t>(32768, std::max<int64_t>(lc.threads, total_units / 4096));
+      // a launch is a few milliseconds long, so its tail (compute units running dry while the last
+      // items finish) weighs more than an item's start-up (one batch whose loads are not prefetched):
+      // some 30 000 items per launch, of 2048 to 8192 units each (measured on the 65B- and 7B-shaped
+      // sets against items 2, 4 and 8 times as large: 4 % and 8 % faster)
+      int64_t target = std::min<int64_t>(8192, std::max<int64_t>(2048, total_units / 32768));
       if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
         const long v = std::atol(ov);
         if (v > 0) target = v;

@@ -28,6 +28,7 @@ LaneKernel pick_rtn_kernel(const LaneClass& lc) {
   }
   EQ_RTN_VARIANT(128, 1) EQ_RTN_VARIANT(128, 2) EQ_RTN_VARIANT(128, 4) EQ_RTN_VARIANT(128, 8)
   EQ_RTN_VARIANT(256, 1) EQ_RTN_VARIANT(256, 2) EQ_RTN_VARIANT(256, 4) EQ_RTN_VARIANT(256, 8) EQ_RTN_VARIANT(256, 16)
+  EQ_RTN_VARIANT(192, 8) EQ_RTN_VARIANT(192, 16)
   EQ_RTN_VARIANT(512, 4) EQ_RTN_VARIANT(512, 8)
 #undef EQ_RTN_VARIANT
   return k;
