@@ -67,3 +67,15 @@ def test_benchmark_refuses_more_than_one_gpu():
     res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
     assert res.returncode != 0
     assert "one GPU only" in (res.stderr + res.stdout)
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """The product path has no CPU route: without the built library every entry point raises."""
+    import paper_2403_02775_amd as eqg
+    from paper_2403_02775_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "lib_path", lambda: str(tmp_path / "libeasyquant.so"))
+    with pytest.raises(ImportError, match="no CPU fallback"):
+        eqg.eq_workspace_bytes([8], [128], [16], eqg.Params(group_size=128))
+    with pytest.raises(ImportError):
+        eqg.eq_code_words_per_row(128, 4)
