@@ -79,3 +79,28 @@ def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
         eqg.eq_workspace_bytes([8], [128], [16], eqg.Params(group_size=128))
     with pytest.raises(ImportError):
         eqg.eq_code_words_per_row(128, 4)
+
+
+def test_only_tests_smoke_and_the_cpu_baseline_touch_the_oracle():
+    """The oracle is test infrastructure: the package, the C sources, the header and the input
+    generator never mention it; bench.py imports it inside its cpu_baseline leg only, and
+    __graft_entry__ inside smoke() only.  Nor does the oracle know the HIP path."""
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    product = [os.path.join(root, "eq_inputs.py")]
+    for d in ("paper_2403_02775_amd", os.path.join("paper_2403_02775_amd", "csrc"), "include"):
+        product += [os.path.join(root, d, f) for f in os.listdir(os.path.join(root, d))
+                    if f.endswith((".py", ".h", ".hip"))]
+    imp = re.compile(r"^\s*(from\s+oracle\b|import\s+oracle\b)", re.M)
+    for path in product:
+        text = open(path).read()
+        assert not imp.search(text) and "easyquant_oracle" not in text, path
+    for name, scope in (("bench.py", "def cpu_baseline"), ("__graft_entry__.py", "def smoke")):
+        text = open(os.path.join(root, name)).read()
+        hits = [m.start() for m in imp.finditer(text)]
+        assert len(hits) == 1, name
+        before = text[:hits[0]]
+        last_def = before.rfind("\ndef ")
+        assert before[last_def + 1:].startswith(scope), (name, before[last_def + 1:last_def + 40])
+    oracle = open(os.path.join(root, "oracle", "easyquant_oracle.py")).read()
+    assert "paper_2403_02775_amd" not in oracle and "ctypes" not in oracle and "import torch" not in oracle
