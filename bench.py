@@ -204,6 +204,10 @@ def main():
     ap.add_argument("--lr", type=float, default=1e-3)
     ap.add_argument("--bits", type=int, default=0, help="code width (default: the workload's, 4)")
     ap.add_argument("--group-size", type=int, default=128, help="0 = one range per output channel (secondary measurement)")
+    ap.add_argument("--stat-scope", choices=["row", "matrix"], default="row",
+                    help="scope of mean / sigma in the outlier criterion; matrix = Eq. 3 as printed (secondary measurement)")
+    ap.add_argument("--select", choices=["best", "last"], default="best",
+                    help="which iterate is kept; last = the paper's wording (secondary measurement)")
     ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
     ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the first matrix given to the CPU oracle (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -230,7 +234,8 @@ def main():
     if args.bits:
         bits = args.bits
     gp = eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=args.group_size, mode=eqg.EQ_SYMMETRIC,
-                    stat_scope=eqg.EQ_STAT_ROW, n_sigma=3.0, iters=args.iters, lr=args.lr, select=eqg.EQ_SELECT_BEST)
+                    stat_scope=eqg.EQ_STAT_ROW if args.stat_scope == "row" else eqg.EQ_STAT_MATRIX, n_sigma=3.0,
+                    iters=args.iters, lr=args.lr, select=eqg.EQ_SELECT_BEST if args.select == "best" else eqg.EQ_SELECT_LAST)
     caps = [int(w.numel() * args.capacity_frac) for w in Ws]
     outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, dev) for w, c in zip(Ws, caps)]
     ws_bytes = eqg.eq_workspace_bytes([w.shape[0] for w in Ws], [w.shape[1] for w in Ws], caps, gp)
@@ -298,10 +303,12 @@ def main():
         "metric": "fp16 weight GB/s quantized (fraction of HBM peak); s per 65B-shaped model",
         "value": weight_gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if True else None, "data": "synthetic",
+        "dtype": "f32",                              # levels in binary32; the sums are exact integers, the recurrence binary64
+        "data": "synthetic",
         "config": {"workload": args.workload + ("" if args.layers < 0 else f"[first {args.layers} layers]"),
                    "matrices": len(Ws), "elements": elems, "bits": bits, "group_size": args.group_size, "mode": "symmetric",
-                   "n_sigma": 3.0, "iters": args.iters, "lr": args.lr, "select": "best", "weights_dtype": dt,
+                   "n_sigma": 3.0, "stat_scope": args.stat_scope, "iters": args.iters, "lr": args.lr, "select": args.select,
+                   "weights_dtype": dt,
                    "parallelism": "1 GPU, one batch call"},
         "seconds_per_model": ms_per_step * 1e-3,
         "weight_hbm_frac": weight_gbs * 1e9 / HBM_PEAK,
@@ -309,9 +316,9 @@ def main():
         "wall_s_per_step": wall / args.steps,
         "roofline": roof,
     }
-    if args.cpu_rows > 0:
+    if args.cpu_rows > 0 and args.stat_scope == "row":       # (a sample of rows has no whole-matrix statistics)
         kw = dict(dtype=gp.dtype, bits=bits, group_size=args.group_size, mode=0, stat_scope=0, n_sigma=3.0, iters=args.iters,
-                  lr=args.lr, select=0)
+                  lr=args.lr, select=0 if args.select == "best" else 1)
         gbs, secs, shape = cpu_baseline(Ws, kw, args.cpu_rows)
         out["cpu_baseline"] = {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
                                "sample": f"first {shape[0]} rows x {shape[1]} cols of layer 0 q_proj ({secs:.1f} s, NumPy, "
