@@ -280,7 +280,8 @@ def main():
     elems = sum(w.numel() for w in Ws)
     ms_per_step = gpu_ms / args.steps
     weight_gbs = elems * 2 / (ms_per_step * 1e-3) / 1e9
-    passes = args.iters + 2 if args.iters else 1  # T+1 evaluations (best-iterate selection) + the emitting one
+    # T evaluations, one more for best-iterate selection, and the emitting pass
+    passes = (args.iters + (2 if args.select == "best" else 1)) if args.iters else 1
     lane_ops = elems * (5 * passes + 12)          # useful lane-operations: 5 per element and pass, 12 fixed
     kern_s = kern_ms * 1e-3 / args.steps          # main kernels per step (one launch per row-length class)
     alg_bytes = algorithmic_bytes(Ws, bits, n_out, args.group_size)
