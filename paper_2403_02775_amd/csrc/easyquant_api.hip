@@ -143,6 +143,22 @@ bool channel_kernel_ok(int64_t rows, int64_t cols, const eq_params* p) {
   return (p->group_size == 0 || p->group_size == cols) && rows > 0 && cols % kG == 0 && cols >= 2048 && cols <= 32768;
 }
 
+// Share of the lanes that have a unit when rows of `upr` units are staged into a pool of `slots`
+// slots and taken out in rounds of `nt` (the fill and take rules of quantize_units128): a pool
+// that cannot hold a whole number of rounds plus a row runs a partly filled round now and then.
+double lane_use_of_rounds(int64_t upr, int64_t nt, int64_t slots) {
+  int64_t pool = 0, used = 0, offered = 0;
+  for (int i = 0; i < 2048; ++i) {
+    while (pool < nt && pool + upr <= slots) pool += upr;
+    if (pool == 0) return 0.0;                       // not even one row fits
+    const int64_t take = pool >= nt ? (pool / nt) * nt : pool;
+    used += take;
+    offered += (take + nt - 1) / nt * nt;
+    pool -= take;
+  }
+  return (double)used / (double)offered;
+}
+
 Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* cap, const eq_params* p) {
   Plan pl;
   pl.path.assign((size_t)n, 0);
@@ -270,7 +286,18 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     };
     int64_t nt = kThreads;
     int64_t slots = pool_for(nt);
-    if (fixed + (size_t)slots * kSlotBytes > kLdsPerCu / 2 || c / 8 > 4 * kThreads) {
+    bool two_per_cu = fixed + (size_t)slots * kSlotBytes <= kLdsPerCu / 2 && c / 8 <= 4 * kThreads;
+    if (!two_per_cu && c / 8 <= 8 * kThreads) {
+      // Two 256-thread workgroups with pools cut down to half the LDS each still keep (almost) every
+      // lane busy for some row lengths (11008: 98 %), and then one workgroup computes while the
+      // other stages, which a single 512-thread workgroup per compute unit cannot do.
+      const int64_t capped = (int64_t)((kLdsPerCu / 2 - fixed) / kSlotBytes);
+      if (lane_use_of_rounds(upr, nt, capped) >= 0.95) {
+        two_per_cu = true;
+        slots = capped;
+      }
+    }
+    if (!two_per_cu) {
       nt = 512;
       slots = std::min<int64_t>(pool_for(nt), (int64_t)((kLdsPerCu - 64 - fixed) / kSlotBytes));
     }

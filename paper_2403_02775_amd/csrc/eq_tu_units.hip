@@ -18,7 +18,7 @@ LaneKernel pick_units_kernel(const LaneClass& lc) {
                          dm, di + c.first_item, kp, c.pool_slots);                                             \
     };                                                                                                          \
   }
-  EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4)
+  EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4) EQ_VARIANT(256, 8)
   EQ_VARIANT(512, 2) EQ_VARIANT(512, 4) EQ_VARIANT(512, 8)
 #undef EQ_VARIANT
   return k;
