@@ -141,12 +141,14 @@ def bench_matvec(args):
     import paper_2403_02775_amd as eqg
     dev = "cuda:0"
     rows, cols = 14336, 57344
-    gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=0)
+    G = args.matvec_group                            # 0: one range per row (the paper's setting)
+    upr = cols // G if G else 1
+    gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=G)
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (rows, cols * 4 // 32), dtype=torch.int32, device=dev, generator=g)
-    scales = torch.rand((rows, 1), device=dev, generator=g) * 0.01 + 0.001
-    zps = torch.full((rows, 1), 7, dtype=torch.uint8, device=dev)
+    scales = torch.rand((rows, upr), device=dev, generator=g) * 0.01 + 0.001
+    zps = torch.full((rows, upr), 7, dtype=torch.uint8, device=dev)
     k = max(1, int(round(cols * args.outlier_pct / 100.0)))
     stride = cols // k                              # one outlier in every stride-wide stretch: ascending, no duplicates
     col = (torch.arange(k, device=dev, dtype=torch.int32) * stride).view(1, -1) + \
@@ -185,8 +187,9 @@ def bench_matvec(args):
     dense_ms = timed(lambda: torch.mv(W, x))
     y_ref = torch.mv(W.float(), x.float())
     rel = float((y - y_ref).abs().max() / y_ref.abs().max())
-    traffic = rows * cols * 0.5 + rows * (5 + 4) + rows * k * 6 + cols * 2
-    print(json.dumps({"metric": f"eq_dequant_matvec ms (14336x57344, int4 x fp16 vector, {args.outlier_pct:g} % outliers)", "value": fused_ms, "unit": "ms",
+    traffic = rows * cols * 0.5 + rows * upr * 5 + rows * 4 + rows * k * 6 + cols * 2
+    print(json.dumps({"metric": f"eq_dequant_matvec ms (14336x57344, int4 x fp16 vector, {args.outlier_pct:g} % outliers, "
+                                f"{'one range per row' if not G else 'groups of %d' % G})", "value": fused_ms, "unit": "ms",
                       "n_gpus": 1, "steps": args.steps, "higher_is_better": False, "data": "synthetic",
                       "GBps": traffic / (fused_ms * 1e-3) / 1e9, "hbm_frac": traffic / (fused_ms * 1e-3) / HBM_PEAK,
                       "torch_fp16_mv_on_dequantized_ms": dense_ms, "speedup_vs_fp16_mv": dense_ms / fused_ms,
@@ -215,6 +218,7 @@ def main():
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) has a kernel of known traffic to scale by")
     ap.add_argument("--dequant", action="store_true", help="measure eq_dequantize instead (secondary benchmark, own JSON line)")
     ap.add_argument("--outlier-pct", type=float, default=1.0, help="outlier ratio in percent for --matvec")
+    ap.add_argument("--matvec-group", type=int, default=0, help="group size for --matvec (0 = one range per row)")
     ap.add_argument("--matvec", action="store_true", help="measure eq_dequant_matvec instead (secondary benchmark, own JSON line)")
     args = ap.parse_args()
     if args.dequant:

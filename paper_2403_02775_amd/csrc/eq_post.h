@@ -395,12 +395,18 @@ __device__ __forceinline__ float dot8(const uint4 w, const uint4 x, float acc) {
 // (dequantize_chunk4).  MODE 2: 4-bit codes and one range per row: the 16 values a weight of a row
 // can take, fl16(fl32(s (u - z))) for u = 0..15, are tabulated in LDS once and every weight is
 // one 16-bit LDS read (two address instructions) instead of five arithmetic instructions.
+// MODE 3: 4-bit codes with groups of 128 or more elements that tile the 4096-column segments (or
+// are tiled by them): the same tables per (row, group) of a segment, at most 256 of them, built
+// by one thread each while the segment's loads are in flight, double-buffered so that one barrier
+// per segment suffices; scale and zero-point of the next segment's tables are loaded a segment
+// ahead.  The host checks the group size (eq_dequant_matvec).
 template <int DT, int MODE>
 __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_GLOBAL uint16_t* __restrict__ x,
                                                             EQ_GLOBAL float* __restrict__ y) {
   constexpr bool FOUR = MODE != 0;
   __shared__ float red[kMvRows][kWaves];
   __shared__ uint16_t lut[kMvRows][16];
+  __shared__ __align__(16) uint16_t lut3[MODE == 3 ? 2 : 1][MODE == 3 ? kThreads : 1][16];
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int64_t row0 = (int64_t)blockIdx.x * kMvRows;
   const int nrows = (int)min((int64_t)kMvRows, (int64_t)d.rows - row0);
@@ -463,6 +469,28 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
       }
     }
   };
+  // MODE 3: tables per (row, group) of a segment.  gps = groups per segment (1 when a group spans
+  // whole segments); thread t < kMvRows * gps builds the table of row t / gps, group t % gps.
+  constexpr uint32_t kSegCols = kMvChunks * kThreads * 8u;
+  const uint32_t lg = (uint32_t)__ffs(d.G) - 1u;                       // MODE 3: the group size is a power of two
+  const uint32_t gps = MODE == 3 ? ((uint32_t)d.G >= kSegCols ? 1u : kSegCols >> lg) : 1u;
+  const uint32_t t_row = tid / gps, t_grp = tid - t_row * gps;
+  uint32_t tab_of[kMvChunks];                              // which of a row's tables serves chunk j of this thread
+#pragma unroll
+  for (int j = 0; j < kMvChunks; ++j) tab_of[j] = gps == 1u ? 0u : (((uint32_t)j * kThreads + tid) * 8u) >> lg;
+  float s_tab = 0.0f, z_tab = 0.0f;                        // scale and zero-point of this thread's next table
+  auto load_table_params = [&](uint32_t ch0n) {
+    const uint32_t col = ch0n * 8u + (gps == 1u ? 0u : t_grp << lg);
+    s_tab = 0.0f;                                          // a table nobody reads: zeros (finite)
+    z_tab = 0.0f;
+    if (t_row < (uint32_t)nrows && tid < (uint32_t)kMvRows * gps && col < (uint32_t)d.cols) {
+      const int64_t unit = (row0 + t_row) * (int64_t)d.upr + (col >> lg);
+      s_tab = d.scales[unit];
+      z_tab = (float)d.zps[unit];
+    }
+  };
+  if (MODE == 3) load_table_params(0u);
+  uint32_t buf = 0;
   for (uint32_t ch0 = 0; ch0 < nchunks; ch0 += kMvChunks * kThreads) {
     uint4 xv[kMvChunks];
 #pragma unroll
@@ -477,24 +505,43 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
 #pragma unroll
         for (int j = 0; j < kMvChunks; ++j)
           wq[r][j] = buffer_load32(crow[r], (ch0 + (uint32_t)j * kThreads + tid) * 4u);
+      if (MODE == 3) {
+        if (tid < (uint32_t)kMvRows * gps) {
+          uint32_t h[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            float prod = s_tab * ((float)u - z_tab);
+            asm volatile("" : "+v"(prod));    // two roundings, as in dequantize_chunk
+            h[u] = narrow16<DT>(prod);
+          }
+          uint4* dst = reinterpret_cast<uint4*>(&lut3[buf][tid][0]);
+          dst[0] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+          dst[1] = make_uint4(h[8] | (h[9] << 16), h[10] | (h[11] << 16), h[12] | (h[13] << 16), h[14] | (h[15] << 16));
+        }
+        load_table_params(ch0 + kMvChunks * kThreads);     // for the next segment (past the end: no load)
+        // the tables of this segment are complete; the other buffer, which the next segment
+        // rewrites, was last read before this barrier
+        __syncthreads();
+      }
 #pragma unroll
       for (int r = 0; r < kMvRows; ++r) {
 #pragma unroll
         for (int j = 0; j < kMvChunks; ++j) {
           float s = srow[r], zf = zrow[r];
-          if (!per_row) {                                // uniform
+          if (MODE == 1 && !per_row) {                   // uniform
             const uint32_t ch = min(ch0 + (uint32_t)j * kThreads + tid, nchunks - 1u);
             const int64_t unit = (r < nrows ? row0 + r : row0) * (int64_t)d.upr + (ch * 8u) / (uint32_t)d.G;
             s = d.scales[unit];
             zf = (float)d.zps[unit];
           }
           uint4 wv;
-          if (MODE == 2) {
-            // byte offsets into the row's table, four at a time: even elements, odd elements
+          if (MODE == 2 || MODE == 3) {
+            // byte offsets into the table, four at a time: even elements, odd elements
             const uint32_t w = wq[r][j];
             uint32_t ev = (w << 1) & 0x1E1E1E1Eu, od = (w >> 3) & 0x1E1E1E1Eu;
             asm("" : "+v"(ev), "+v"(od));     // keep the two words: a byte of them is one bit-field extract away
-            const unsigned char* tab = reinterpret_cast<const unsigned char*>(&lut[r][0]);
+            const unsigned char* tab = MODE == 2 ? reinterpret_cast<const unsigned char*>(&lut[r][0])
+                                                 : reinterpret_cast<const unsigned char*>(&lut3[buf][(uint32_t)r * gps + tab_of[j]][0]);
             typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
             uint32_t pr[4];
 #pragma unroll
@@ -511,6 +558,7 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
           acc[r] = dot8<DT>(wv, xv[j], acc[r]);
         }
       }
+      buf ^= 1u;
     } else {
 #pragma unroll
       for (int r = 0; r < kMvRows; ++r) {

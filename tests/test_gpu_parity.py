@@ -194,7 +194,11 @@ def test_exact_rounding_ties_go_to_the_even_level(iters):
 
 @pytest.mark.parametrize("rows,cols,bits,G,dtype", [(37, 4096, 4, 128, "f16"), (19, 8192, 4, 0, "f16"), (9, 22016, 3, 128, "f16"),
                                                     (70, 1280, 8, 32, "bf16"), (5, 57344, 4, 0, "f16"), (8, 256, 2, 64, "bf16"),
-                                                    (17, 4096, 4, 0, "bf16"), (33, 2048, 4, 128, "bf16")])
+                                                    (17, 4096, 4, 0, "bf16"), (33, 2048, 4, 128, "bf16"),
+                                                    # 4-bit groups: tables per group (groups of 128 .. 4096 and 8192, ragged
+                                                    # last segment, one row short of a workgroup), plain arithmetic (64, 384)
+                                                    (23, 11008, 4, 128, "f16"), (15, 12288, 4, 256, "f16"), (9, 16384, 4, 4096, "bf16"),
+                                                    (10, 24576, 4, 8192, "f16"), (12, 4096, 4, 64, "f16"), (7, 3072, 4, 384, "f16")])
 def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     """eq_dequant_matvec against the oracle's W^ x (binary64) on the GPU's own quantized output:
     the weights are bit-identical by construction (the same Eq. 4 arithmetic as eq_dequantize), so
@@ -229,6 +233,24 @@ def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     q2["out_val"] = got[0]["out_val"][:0]
     err2 = np.abs(y2.cpu().numpy().astype(np.float64) - eqo.dequant_matvec(q2, rows, cols, p, x_raw))
     assert (err2 <= bound).all()
+
+
+def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(monkeypatch):
+    """Groups of 128 with 4-bit codes: the per-group tables hold exactly the weights the plain
+    arithmetic computes and the additions come in the same order, so y is bit-identical."""
+    rows, cols = 21, 11008 + 128
+    W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c2"], seed=5150, device=DEV)
+    p = eqo.Params(bits=4, group_size=128, iters=2, mode=eqo.ASYMMETRIC)
+    outs, _ = run_gpu([W], p)
+    x = torch.randn(cols, device=DEV).to(torch.float16)
+    ys = []
+    for tables in ("1", "0"):
+        monkeypatch.setenv("EASYQUANT_MATVEC_TABLES", tables)
+        y = torch.empty(rows, dtype=torch.float32, device=DEV)
+        eqg.eq_dequant_matvec(outs[0], rows, cols, to_gpu_params(p), x, y)
+        torch.cuda.synchronize()
+        ys.append(y)
+    assert torch.equal(ys[0].view(torch.int32), ys[1].view(torch.int32))
 
 
 def test_consumers_replay_from_a_hip_graph():
