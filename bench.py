@@ -99,12 +99,14 @@ def bench_dequantize(args):
     import paper_2403_02775_amd as eqg
     dev = "cuda:0"
     rows, cols = 14336, 57344
-    gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=0)
+    G = args.matvec_group                            # 0: one range per row (the paper's setting)
+    upr = cols // G if G else 1
+    gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=G)
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (rows, cols * 4 // 32), dtype=torch.int32, device=dev, generator=g)
-    scales = torch.rand((rows, 1), device=dev, generator=g) * 0.01 + 0.001
-    zps = torch.full((rows, 1), 7, dtype=torch.uint8, device=dev)
+    scales = torch.rand((rows, upr), device=dev, generator=g) * 0.01 + 0.001
+    zps = torch.full((rows, upr), 7, dtype=torch.uint8, device=dev)
     out = torch.empty((rows, cols), dtype=torch.float16, device=dev)
     res = {}
     for ratio in (0.0, 1e-4, 1e-3, 5e-3, 1e-2, 5e-2, 1e-1):
@@ -124,8 +126,9 @@ def bench_dequantize(args):
         torch.cuda.synchronize()
         res[f"{ratio:.4%}"] = e0.elapsed_time(e1) / args.steps
     dense_ms = res["0.0000%"]
-    traffic = rows * cols * 2.5 + rows * 5
-    print(json.dumps({"metric": "eq_dequantize ms (14336x57344, int4 -> fp16)", "value": dense_ms, "unit": "ms",
+    traffic = rows * cols * 2.5 + rows * upr * 5
+    print(json.dumps({"metric": "eq_dequantize ms (14336x57344, int4 -> fp16, %s)" % ("one range per row" if not G else "groups of %d" % G),
+                      "value": dense_ms, "unit": "ms",
                       "n_gpus": 1, "steps": args.steps, "higher_is_better": False, "data": "synthetic",
                       "dense_GBps": traffic / (dense_ms * 1e-3) / 1e9, "dense_hbm_frac": traffic / (dense_ms * 1e-3) / HBM_PEAK,
                       "outlier_overhead_ms": {k: v - dense_ms for k, v in res.items() if k != "0.0000%"},
@@ -218,7 +221,7 @@ def main():
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) has a kernel of known traffic to scale by")
     ap.add_argument("--dequant", action="store_true", help="measure eq_dequantize instead (secondary benchmark, own JSON line)")
     ap.add_argument("--outlier-pct", type=float, default=1.0, help="outlier ratio in percent for --matvec")
-    ap.add_argument("--matvec-group", type=int, default=0, help="group size for --matvec (0 = one range per row)")
+    ap.add_argument("--matvec-group", type=int, default=0, help="group size for --dequant and --matvec (0 = one range per row)")
     ap.add_argument("--matvec", action="store_true", help="measure eq_dequant_matvec instead (secondary benchmark, own JSON line)")
     args = ap.parse_args()
     if args.dequant:
