@@ -445,16 +445,27 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
                           FOUR && r < nrows ? (uint32_t)d.words_per_row * 4u : 0u);
   auto sparse_part = [&] {
     if (!d.out_col) return;
-    // the sparse lists of the workgroup's rows are one contiguous stretch of the CSR arrays: one
-    // strided walk over it, each entry credited to the row whose range holds its index
-    const uint32_t b = rp[0], e = rp[kMvRows];
+    // Every wavefront takes the sparse lists of two of the workgroup's rows, one contiguous stretch
+    // of the CSR arrays, in a strided walk; an entry belongs to the first of the two rows if its
+    // index lies below the second row's start.  (The rows' sums are combined over all threads at
+    // the end anyway, so it does not matter which thread adds an entry.)
+    static_assert(kMvRows == 2 * kWaves, "two rows per wavefront");
+    const uint32_t w2 = 2u * (uint32_t)__builtin_amdgcn_readfirstlane((int)wave);
+    uint32_t b = 0, m = 0, e = 0;
+#pragma unroll
+    for (int r = 0; r <= kMvRows; ++r) {
+      if ((uint32_t)r == w2) b = rp[r];
+      if ((uint32_t)r == w2 + 1u) m = rp[r];
+      if ((uint32_t)r == w2 + 2u) e = rp[r];
+    }
+    float sa = 0.0f, sb = 0.0f;
     constexpr int kAhead = 4;                            // entries per thread in flight (two dependent loads each)
-    for (uint32_t i0 = b + tid; i0 < e; i0 += kAhead * kThreads) {
+    for (uint32_t i0 = b + lane; i0 < e; i0 += kAhead * kWave) {
       uint32_t col[kAhead];
       float val[kAhead], xg[kAhead];
 #pragma unroll
       for (int a = 0; a < kAhead; ++a) {
-        const uint32_t i = i0 + (uint32_t)a * kThreads;
+        const uint32_t i = i0 + (uint32_t)a * kWave;
         col[a] = i < e ? d.out_col[i] : 0xFFFFFFFFu;
         val[a] = i < e ? widen16<DT>(d.out_val[i]) : 0.0f;
       }
@@ -462,12 +473,14 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
       for (int a = 0; a < kAhead; ++a) xg[a] = col[a] < (uint32_t)d.cols ? widen16<DT>(x[col[a]]) : 0.0f;
 #pragma unroll
       for (int a = 0; a < kAhead; ++a) {
-        const uint32_t i = i0 + (uint32_t)a * kThreads;
+        const uint32_t i = i0 + (uint32_t)a * kWave;
         const float prod = val[a] * xg[a];
-#pragma unroll
-        for (int r = 0; r < kMvRows; ++r) acc[r] += (i >= rp[r] && i < rp[r + 1]) ? prod : 0.0f;
+        sa += i < m ? prod : 0.0f;
+        sb += i < m ? 0.0f : prod;
       }
     }
+#pragma unroll
+    for (int r = 0; r < kMvRows; ++r) acc[r] += (uint32_t)r == w2 ? sa : ((uint32_t)r == w2 + 1u ? sb : 0.0f);
   };
   // MODE 3: tables per (row, group) of a segment.  gps = groups per segment (1 when a group spans
   // whole segments); thread t < kMvRows * gps builds the table of row t / gps, group t % gps.
