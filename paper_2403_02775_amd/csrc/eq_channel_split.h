@@ -119,18 +119,17 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
 
     uint32_t pass = 0;                           // evaluations so far in this round (selects the accumulator set)
     float r_sel = optimise_range(kp, r_start, [&](float inv, double& A, double& B) {
-      int a[4] = {0, 0, 0, 0}, bh[4] = {0, 0, 0, 0}, bl[4] = {0, 0, 0, 0};
+      int cc = 0, hc = 0, lc = 0;                // one accumulator per sum, taking turns (see eval_sums)
 #pragma unroll
       for (int j = 0; j < P; ++j) {
         const float x0 = widen16<DT>(x[j] & 0xFFFFu), x1 = widen16<DT>(x[j] >> 16);
         const float t0 = __builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, kMagic), mlo, mhi);
         const float t1 = __builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, kMagic), mlo, mhi);
         const short2_t c = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm(__float_as_uint(t1), __float_as_uint(t0), 0x05040100u));
-        a[j & 3] = __builtin_amdgcn_sdot2(c, c, a[j & 3], false);
-        bh[j & 3] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, H[j]), c, bh[j & 3], false);
-        bl[j & 3] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[j]), c, bl[j & 3], false);
+        cc = __builtin_amdgcn_sdot2(c, c, cc, false);
+        hc = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, H[j]), c, hc, false);
+        lc = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[j]), c, lc, false);
       }
-      int cc = (a[0] + a[1]) + (a[2] + a[3]), hc = (bh[0] + bh[1]) + (bh[2] + bh[3]), lc = (bl[0] + bl[1]) + (bl[2] + bl[3]);
       if (!valid) cc = hc = lc = 0;
       // 32-lane half sums (no 32-bit wrap-around: 32 * 2 P elements, |level| <= 15, 16-bit planes)
       cc = group_sum_dpp<true>(cc);

@@ -108,7 +108,9 @@ __device__ __forceinline__ void eval_sums(const unsigned char* slot, const uint3
                                           const uint32_t (&Lo)[kPairs], float inv, float mlo, float mhi,
                                           int& sum_cc, int& sum_hc, int& sum_lc) {
   asm volatile("" ::: "memory");
-  int a[4] = {0, 0, 0, 0}, bh[4] = {0, 0, 0, 0}, bl[4] = {0, 0, 0, 0};   // four chains each
+  // one accumulator per sum, the three sums taking turns: a dependent dot product is then three
+  // instructions away, and there is nothing to clear or to add up beyond the three registers
+  int a = 0, bh = 0, bl = 0;
   uint4 nxt = *reinterpret_cast<const uint4*>(slot);
 #pragma unroll
   for (int ch = 0; ch < 16; ++ch) {
@@ -117,16 +119,16 @@ __device__ __forceinline__ void eval_sums(const unsigned char* slot, const uint3
     short2_t c[4];
     chunk_levels<DT>(cur, inv, mlo, mhi, c);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) a[j] = __builtin_amdgcn_sdot2(c[j], c[j], a[j], false);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) bh[j] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, H[4 * ch + j]), c[j], bh[j], false);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) bl[j] = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[4 * ch + j]), c[j], bl[j], false);
+    for (int j = 0; j < 4; ++j) {
+      a = __builtin_amdgcn_sdot2(c[j], c[j], a, false);
+      bh = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, H[4 * ch + j]), c[j], bh, false);
+      bl = __builtin_amdgcn_sdot2(__builtin_bit_cast(short2_t, Lo[4 * ch + j]), c[j], bl, false);
+    }
     __builtin_amdgcn_sched_barrier(0);
   }
-  sum_cc = (a[0] + a[1]) + (a[2] + a[3]);
-  sum_hc = (bh[0] + bh[1]) + (bh[2] + bh[3]);
-  sum_lc = (bl[0] + bl[1]) + (bl[2] + bl[3]);
+  sum_cc = a;
+  sum_hc = bh;
+  sum_lc = bl;
 }
 template <int DT>
 __device__ __forceinline__ void eval_regs(const unsigned char* slot, const uint32_t (&H)[kPairs],
