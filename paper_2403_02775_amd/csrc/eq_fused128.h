@@ -403,12 +403,13 @@ __device__ __forceinline__ float optimise_range(const KParams& kp, float r0, Eva
 // NT = threads per workgroup = units per round: 256 when two workgroups' pools fit the LDS of
 // a compute unit, 512 (one workgroup per compute unit) for long rows; two wavefronts per SIMD
 // either way.  K = 16-byte chunks of a row per thread (cols <= 8 * K * NT); rows are staged in
-// batches of 16 / K rows (16 chunks = 64 registers of row data per thread).
-template <int DT, int NT, int K>
+// batches of RB rows, 16 / K unless stated (16 chunks = 64 registers of row data per thread; a
+// batch of 3 rows of 8 chunks, 96 registers, lets rows of which three fill a round of 512 be
+// staged in one go: the planes are not live while rows are staged).
+template <int DT, int NT, int K, int RB = 16 / K>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void quantize_units128(const MatDesc* __restrict__ mats,
                                                               const WorkItem* __restrict__ items, KParams kp,
                                                               uint32_t pool_slots) {
-  constexpr int RB = 16 / K;
   typedef BatchScratch<RB, NT / kWave> Scratch;
   static_assert(sizeof(Scratch) <= kLdsHeader, "staging scratch must fit the LDS header");
   extern __shared__ __align__(16) unsigned char smem[];

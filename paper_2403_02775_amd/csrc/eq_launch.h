@@ -26,6 +26,7 @@ struct LaneClass {
   int32_t cols = 0, upr = 0;
   int32_t threads = kThreads;           // workgroup size = units per round
   int32_t chunks_per_thread = 1;        // 16-byte chunks of a row per thread, rounded up to 1, 2, 4 or 8
+  int32_t rows_per_batch = 0;           // rows staged at once by the kind-1 kernel; 0 = 16 / chunks_per_thread
   uint32_t pool_slots = 0;
   size_t lds_bytes = 0;
   size_t first_item = 0, n_items = 0;
