@@ -308,9 +308,9 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     }
     lc.pool_slots = (uint32_t)slots;
     lc.lds_bytes = fixed + (size_t)lc.pool_slots * kSlotBytes;
-    // rows of which three fill a round of 512 (129 .. 192 units, e.g. 22016 columns): all three staged
+    // rows of which three fill a round (22016 columns for 512 lanes, 11008 for 256): all three staged
     // as one batch instead of two and one
-    if (nt == 512 && lc.chunks_per_thread == 8 && 3 * upr >= nt && 3 * upr <= slots) lc.rows_per_batch = 3;
+    if (lc.chunks_per_thread == 8 && 3 * upr >= nt && 3 * upr <= slots) lc.rows_per_batch = 3;
     const int64_t g = std::gcd(upr, nt);
     // rows per work item: enough units to amortise the partly filled last round of an item,
     // few enough that the grid has dozens of items per compute unit (the last items of a launch

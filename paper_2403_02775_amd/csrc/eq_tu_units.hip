@@ -19,7 +19,7 @@ LaneKernel pick_units_kernel(const LaneClass& lc) {
     };                                                                                                          \
   }
 #define EQ_VARIANT(NT_, K_) EQ_VARIANT_RB(NT_, K_, 16 / K_)
-  EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4) EQ_VARIANT(256, 8)
+  EQ_VARIANT(256, 1) EQ_VARIANT(256, 2) EQ_VARIANT(256, 4) EQ_VARIANT(256, 8) EQ_VARIANT_RB(256, 8, 3)
   EQ_VARIANT(512, 2) EQ_VARIANT(512, 4) EQ_VARIANT(512, 8) EQ_VARIANT_RB(512, 8, 3)
 #undef EQ_VARIANT
 #undef EQ_VARIANT_RB
