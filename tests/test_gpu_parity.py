@@ -49,7 +49,9 @@ def test_small_matrices_across_bits_groups_modes(bits, G, mode):
 
 @pytest.mark.parametrize("rows,cols,units_per_item", [(130, 1280, 1000), (9, 22016, 0), (24, 11008, 1500),
                                                       (3, 32768, 0), (70, 8192, 2048), (64, 4096, 0),
-                                                      (70, 22016, 20000), (40, 11008, 20000)])
+                                                      (70, 22016, 20000), (40, 11008, 20000),
+                                                      # the ends of the row lengths that are staged three rows to a batch
+                                                      (11, 24576, 0), (7, 21888, 0), (10, 10880, 0), (9, 11776, 0)])
 def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_item, monkeypatch):
     # group 128: rows whose unit count does not divide the 256- or 512-unit rounds leave units
     # behind that are carried to the next fill; the override makes work items span several rounds.
