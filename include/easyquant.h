@@ -168,7 +168,7 @@ EQ_API int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const 
  *   x  DEVICE, cols elements of p->dtype, 16-byte aligned.    y  DEVICE, rows binary32 values.
  * Products and sums are binary32 in an unspecified order: y agrees with the exact product to
  * within 3e-5 * sum_j |W^_ij x_j| per row.  q as for eq_dequantize.  cols == 0 gives y = 0.
- * 4-bit codes with one range per row, or with groups of a power of two >= 128 elements, are
+ * 4-bit codes with one range per row, or with groups of a power of two >= 64 elements, are
  * served from small tables of the 16 values a weight of the row / group can take
  * (EASYQUANT_MATVEC_TABLES=0 in the environment, for tests and measurements, takes the plain
  * arithmetic for grouped codes instead; the weights are the same bits either way). */

@@ -668,18 +668,20 @@ int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_
     const EQ_GLOBAL uint16_t* xd = dev(static_cast<const uint16_t*>(x));
     EQ_GLOBAL float* yd = dev(y);
     const dim3 grid(blocks), block(kThreads);
-    // per-group tables (mode 3) need groups of at least 128 elements that tile the kernel's
+    // per-group tables (modes 3 and 4) need groups of at least 64 elements that tile the kernel's
     // 4096-column segments or are tiled by them
     const int64_t seg_cols = (int64_t)kMvChunks * kThreads * 8;
     const char* tv = std::getenv("EASYQUANT_MATVEC_TABLES");           // test / measurement override: 0 = arithmetic
-    const bool tables = d.G >= 128 && (d.G & (d.G - 1)) == 0 && (seg_cols % d.G == 0 || d.G % seg_cols == 0) &&
+    const bool tables = d.G >= 64 && (d.G & (d.G - 1)) == 0 && (seg_cols % d.G == 0 || d.G % seg_cols == 0) &&
                         !(tv && tv[0] == '0');
-    const int mode = p->bits != 4 ? 0 : d.upr == 1 ? 2 : tables ? 3 : 1;
+    const int mode = p->bits != 4 ? 0 : d.upr == 1 ? 2 : tables ? (d.G == 64 ? 4 : 3) : 1;
 #define EQ_MV(DT_, MODE_) hipLaunchKernelGGL((dequant_matvec<DT_, MODE_>), grid, block, 0, st, d, xd, yd)
     if (p->dtype == EQ_F16) {
-      if (mode == 3) EQ_MV(EQ_F16, 3); else if (mode == 2) EQ_MV(EQ_F16, 2); else if (mode == 1) EQ_MV(EQ_F16, 1); else EQ_MV(EQ_F16, 0);
+      if (mode == 4) EQ_MV(EQ_F16, 4); else if (mode == 3) EQ_MV(EQ_F16, 3); else if (mode == 2) EQ_MV(EQ_F16, 2);
+      else if (mode == 1) EQ_MV(EQ_F16, 1); else EQ_MV(EQ_F16, 0);
     } else {
-      if (mode == 3) EQ_MV(EQ_BF16, 3); else if (mode == 2) EQ_MV(EQ_BF16, 2); else if (mode == 1) EQ_MV(EQ_BF16, 1); else EQ_MV(EQ_BF16, 0);
+      if (mode == 4) EQ_MV(EQ_BF16, 4); else if (mode == 3) EQ_MV(EQ_BF16, 3); else if (mode == 2) EQ_MV(EQ_BF16, 2);
+      else if (mode == 1) EQ_MV(EQ_BF16, 1); else EQ_MV(EQ_BF16, 0);
     }
 #undef EQ_MV
   }

@@ -399,14 +399,17 @@ __device__ __forceinline__ float dot8(const uint4 w, const uint4 x, float acc) {
 // are tiled by them): the same tables per (row, group) of a segment, at most 256 of them, built
 // by one thread each while the segment's loads are in flight, double-buffered so that one barrier
 // per segment suffices; scale and zero-point of the next segment's tables are loaded a segment
-// ahead.  The host checks the group size (eq_dequant_matvec).
+// ahead.  MODE 4: the same for groups of 64 elements, two tables per thread.  The host checks the
+// group size (eq_dequant_matvec).
 template <int DT, int MODE>
 __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_GLOBAL uint16_t* __restrict__ x,
                                                             EQ_GLOBAL float* __restrict__ y) {
   constexpr bool FOUR = MODE != 0;
+  constexpr bool TABLES = MODE == 3 || MODE == 4;        // tables per (row, group) of a segment
+  constexpr int TPT = MODE == 4 ? 2 : 1;                 // tables built per thread and segment
   __shared__ float red[kMvRows][kWaves];
   __shared__ uint16_t lut[kMvRows][16];
-  __shared__ __align__(16) uint16_t lut3[MODE == 3 ? 2 : 1][MODE == 3 ? kThreads : 1][16];
+  __shared__ __align__(16) uint16_t lut3[TABLES ? 2 : 1][TABLES ? TPT * kThreads : 1][16];
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int64_t row0 = (int64_t)blockIdx.x * kMvRows;
   const int nrows = (int)min((int64_t)kMvRows, (int64_t)d.rows - row0);
@@ -482,27 +485,34 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
 #pragma unroll
     for (int r = 0; r < kMvRows; ++r) acc[r] += (uint32_t)r == w2 ? sa : ((uint32_t)r == w2 + 1u ? sb : 0.0f);
   };
-  // MODE 3: tables per (row, group) of a segment.  gps = groups per segment (1 when a group spans
-  // whole segments); thread t < kMvRows * gps builds the table of row t / gps, group t % gps.
+  // MODE 3 / 4: tables per (row, group) of a segment.  gps = groups per segment (1 when a group spans
+  // whole segments); table t < kMvRows * gps is that of row t / gps, group t % gps; thread tid builds
+  // tables tid, tid + 256, ...
   constexpr uint32_t kSegCols = kMvChunks * kThreads * 8u;
-  const uint32_t lg = (uint32_t)__ffs(d.G) - 1u;                       // MODE 3: the group size is a power of two
-  const uint32_t gps = MODE == 3 ? ((uint32_t)d.G >= kSegCols ? 1u : kSegCols >> lg) : 1u;
-  const uint32_t t_row = tid / gps, t_grp = tid - t_row * gps;
+  const uint32_t lg = (uint32_t)__ffs(d.G) - 1u;                       // with tables the group size is a power of two
+  const uint32_t gps = TABLES ? ((uint32_t)d.G >= kSegCols ? 1u : kSegCols >> lg) : 1u;
   uint32_t tab_of[kMvChunks];                              // which of a row's tables serves chunk j of this thread
 #pragma unroll
   for (int j = 0; j < kMvChunks; ++j) tab_of[j] = gps == 1u ? 0u : (((uint32_t)j * kThreads + tid) * 8u) >> lg;
-  float s_tab = 0.0f, z_tab = 0.0f;                        // scale and zero-point of this thread's next table
+  float s_tab[TPT], z_tab[TPT];                            // scale and zero-point of this thread's next tables
   auto load_table_params = [&](uint32_t ch0n) {
-    const uint32_t col = ch0n * 8u + (gps == 1u ? 0u : t_grp << lg);
-    s_tab = 0.0f;                                          // a table nobody reads: zeros (finite)
-    z_tab = 0.0f;
-    if (t_row < (uint32_t)nrows && tid < (uint32_t)kMvRows * gps && col < (uint32_t)d.cols) {
-      const int64_t unit = (row0 + t_row) * (int64_t)d.upr + (col >> lg);
-      s_tab = d.scales[unit];
-      z_tab = (float)d.zps[unit];
+#pragma unroll
+    for (int k = 0; k < TPT; ++k) {
+      const uint32_t t = tid + (uint32_t)k * kThreads;
+      const uint32_t t_row = t / gps, t_grp = t - t_row * gps;
+      const uint32_t col = ch0n * 8u + (gps == 1u ? 0u : t_grp << lg);
+      s_tab[k] = 0.0f;                                     // a table nobody reads: zeros (finite)
+      z_tab[k] = 0.0f;
+      if (t_row < (uint32_t)nrows && t < (uint32_t)kMvRows * gps && col < (uint32_t)d.cols) {
+        const int64_t unit = (row0 + t_row) * (int64_t)d.upr + (col >> lg);
+        s_tab[k] = d.scales[unit];
+        z_tab[k] = (float)d.zps[unit];
+      }
     }
   };
-  if (MODE == 3) load_table_params(0u);
+#pragma unroll
+  for (int k = 0; k < TPT; ++k) s_tab[k] = z_tab[k] = 0.0f;
+  if (TABLES) load_table_params(0u);
   uint32_t buf = 0;
   for (uint32_t ch0 = 0; ch0 < nchunks; ch0 += kMvChunks * kThreads) {
     uint4 xv[kMvChunks];
@@ -518,18 +528,22 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
 #pragma unroll
         for (int j = 0; j < kMvChunks; ++j)
           wq[r][j] = buffer_load32(crow[r], (ch0 + (uint32_t)j * kThreads + tid) * 4u);
-      if (MODE == 3) {
-        if (tid < (uint32_t)kMvRows * gps) {
-          uint32_t h[16];
+      if (TABLES) {
 #pragma unroll
-          for (int u = 0; u < 16; ++u) {
-            float prod = s_tab * ((float)u - z_tab);
-            asm volatile("" : "+v"(prod));    // two roundings, as in dequantize_chunk
-            h[u] = narrow16<DT>(prod);
+        for (int k = 0; k < TPT; ++k) {
+          const uint32_t t = tid + (uint32_t)k * kThreads;
+          if (t < (uint32_t)kMvRows * gps) {
+            uint32_t h[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+              float prod = s_tab[k] * ((float)u - z_tab[k]);
+              asm volatile("" : "+v"(prod));    // two roundings, as in dequantize_chunk
+              h[u] = narrow16<DT>(prod);
+            }
+            uint4* dst = reinterpret_cast<uint4*>(&lut3[buf][t][0]);
+            dst[0] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            dst[1] = make_uint4(h[8] | (h[9] << 16), h[10] | (h[11] << 16), h[12] | (h[13] << 16), h[14] | (h[15] << 16));
           }
-          uint4* dst = reinterpret_cast<uint4*>(&lut3[buf][tid][0]);
-          dst[0] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-          dst[1] = make_uint4(h[8] | (h[9] << 16), h[10] | (h[11] << 16), h[12] | (h[13] << 16), h[14] | (h[15] << 16));
         }
         load_table_params(ch0 + kMvChunks * kThreads);     // for the next segment (past the end: no load)
         // the tables of this segment are complete; the other buffer, which the next segment
@@ -548,7 +562,7 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
             zf = (float)d.zps[unit];
           }
           uint4 wv;
-          if (MODE == 2 || MODE == 3) {
+          if (MODE == 2 || TABLES) {
             // byte offsets into the table, four at a time: even elements, odd elements
             const uint32_t w = wq[r][j];
             uint32_t ev = (w << 1) & 0x1E1E1E1Eu, od = (w >> 3) & 0x1E1E1E1Eu;

@@ -200,7 +200,8 @@ def test_exact_rounding_ties_go_to_the_even_level(iters):
                                                     # 4-bit groups: tables per group (groups of 128 .. 4096 and 8192, ragged
                                                     # last segment, one row short of a workgroup), plain arithmetic (64, 384)
                                                     (23, 11008, 4, 128, "f16"), (15, 12288, 4, 256, "f16"), (9, 16384, 4, 4096, "bf16"),
-                                                    (10, 24576, 4, 8192, "f16"), (12, 4096, 4, 64, "f16"), (7, 3072, 4, 384, "f16")])
+                                                    (10, 24576, 4, 8192, "f16"), (12, 4096, 4, 64, "f16"), (7, 3072, 4, 384, "f16"),
+                                                    (19, 11008, 4, 64, "bf16"), (9, 2048, 4, 32, "f16")])
 def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     """eq_dequant_matvec against the oracle's W^ x (binary64) on the GPU's own quantized output:
     the weights are bit-identical by construction (the same Eq. 4 arithmetic as eq_dequantize), so
@@ -237,12 +238,13 @@ def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     assert (err2 <= bound).all()
 
 
-def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(monkeypatch):
-    """Groups of 128 with 4-bit codes: the per-group tables hold exactly the weights the plain
+@pytest.mark.parametrize("G", [128, 64, 1024])
+def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(G, monkeypatch):
+    """Groups of 64 and up with 4-bit codes: the per-group tables hold exactly the weights the plain
     arithmetic computes and the additions come in the same order, so y is bit-identical."""
-    rows, cols = 21, 11008 + 128
+    rows, cols = 21, 11008 + 256
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c2"], seed=5150, device=DEV)
-    p = eqo.Params(bits=4, group_size=128, iters=2, mode=eqo.ASYMMETRIC)
+    p = eqo.Params(bits=4, group_size=G, iters=2, mode=eqo.ASYMMETRIC)
     outs, _ = run_gpu([W], p)
     x = torch.randn(cols, device=DEV).to(torch.float16)
     ys = []
