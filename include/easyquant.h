@@ -65,7 +65,9 @@ enum {
   EQ_E_ALIGN = -4,        /* W or W_out not 16-byte aligned, codes not 4-byte aligned */
   EQ_E_WORKSPACE = -5,    /* workspace NULL, misaligned (256 B) or smaller than eq_workspace_bytes() */
   EQ_E_UNSUPPORTED = -6,  /* a row too long for on-chip staging (cols > EQ_MAX_COLS) */
-  EQ_E_HIP = -7           /* a HIP runtime call failed (launch, copy); eq_last_hip_error() has the code */
+  EQ_E_HIP = -7,          /* a HIP runtime call failed (launch, copy); eq_last_hip_error() has the code */
+  EQ_E_SCRATCH = -8       /* eq_quantize_matrix_noalloc: the matrix and its outlier capacity need more
+                             scratch memory than the library's built-in EQ_STATIC_SCRATCH_BYTES */
 };
 /* bits of the DEVICE status word */
 enum {
@@ -147,6 +149,28 @@ EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t
 EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols,
                       const int64_t* ld, const eq_params* p, const eq_qmatrix* outs,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* eq_quantize_matrix for callers that cannot allocate or copy: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and the same outputs,
+ * bit for bit, but there is no workspace argument: the scratch memory (descriptors, work items,
+ * Adam's bias-correction table, per-row outlier counts and the staging copy of the outlier
+ * list) is a built-in device array of EQ_STATIC_SCRATCH_BYTES that every GPU the library runs
+ * on holds until the process ends, and the descriptors are written there by a small kernel
+ * from by-value arguments instead of being copied from host memory.  The call allocates and
+ * frees nothing on the device and enqueues kernels only.
+ *   Limit: eq_workspace_bytes(1, &rows, &cols, &out->out_capacity, p) must not exceed
+ *   EQ_STATIC_SCRATCH_BYTES (32 MiB), else EQ_E_SCRATCH (nothing is enqueued).  The need is
+ *   about 6 bytes per entry of out_capacity plus 8 bytes per row: a 22016 x 8192 matrix with a
+ *   capacity of 2 % of its elements takes 21 MiB, a 4096 x 4096 one with the never-overflowing
+ *   capacity of eq_outlier_capacity_bound 11 MiB.
+ *   The device that is current when the call is made must be the one hip_stream belongs to;
+ *   the address of that device's array is looked up on the first call per device.
+ *   All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams,
+ *   two host threads) race; calls on one stream, or otherwise ordered, are safe, and nothing
+ *   needs to be cleared between them. */
+#define EQ_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+EQ_API int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_t ld,
+                               const eq_params* p, const eq_qmatrix* out, void* hip_stream);
 
 /* Algorithm 1, "Dequantize" (Eq. 4): W_out[i][j] = round_to_dtype(scale * (code - zero_point))
  * for normal values, the stored raw pattern for outliers.  W_out DEVICE, rows x cols of

@@ -13,6 +13,7 @@ EQ_SYMMETRIC, EQ_ASYMMETRIC = 0, 1
 EQ_STAT_ROW, EQ_STAT_GROUP, EQ_STAT_MATRIX = 0, 1, 2
 EQ_SELECT_BEST, EQ_SELECT_LAST = 0, 1
 EQ_S_OUTLIER_OVERFLOW, EQ_S_NONFINITE = 1, 2
+EQ_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -54,6 +55,9 @@ def lib() -> C.CDLL:
         L.eq_quantize_matrix.restype = C.c_int
         L.eq_quantize_matrix.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.POINTER(_CParams),
                                          C.POINTER(_CQMatrix), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.eq_quantize_matrix_noalloc.restype = C.c_int
+        L.eq_quantize_matrix_noalloc.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.POINTER(_CParams),
+                                                 C.POINTER(_CQMatrix), C.c_void_p]
         L.eq_quantize_batch.restype = C.c_int
         L.eq_quantize_batch.argtypes = [C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                         C.POINTER(C.c_int64), C.POINTER(_CParams), C.POINTER(_CQMatrix), C.c_void_p,
@@ -206,6 +210,16 @@ def eq_quantize_matrix(W: torch.Tensor, p: Params, out: QMatrix, workspace: torc
                                   _stream_ptr(stream))
     if rc != 0:
         raise EasyQuantError(rc, "eq_quantize_matrix")
+
+
+def eq_quantize_matrix_noalloc(W: torch.Tensor, p: Params, out: QMatrix, stream=None) -> None:
+    """eq_quantize_matrix without a workspace argument (the library's built-in scratch array)."""
+    _check_w(W, p)
+    rows, cols = W.shape
+    cp, cq = p.c(), out.c()
+    rc = lib().eq_quantize_matrix_noalloc(W.data_ptr(), rows, cols, _ld(W), C.byref(cp), C.byref(cq), _stream_ptr(stream))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_quantize_matrix_noalloc")
 
 
 def eq_quantize_batch(Ws: List[torch.Tensor], p: Params, outs: List[QMatrix], workspace: torch.Tensor, stream=None) -> None:

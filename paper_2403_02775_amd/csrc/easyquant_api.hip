@@ -21,11 +21,23 @@
 #include "eq_post.h"
 #include "eq_rowstage.h"
 
+// Scratch memory of eq_quantize_matrix_noalloc: every GPU the library's code object is loaded
+// on holds its own copy of this array, at its own address, until the process ends.  In host code
+// the name is only a handle for hipGetSymbolAddress; kernels and copies get the address that
+// call returned for the device at hand.
+static __device__ __align__(256) unsigned char scratch[EQ_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace eq;
 
 thread_local int g_last_hip_error = 0;
+
+// Address of `scratch` on the current device, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
 
 // ---- optional event bracketing of the main kernels (eq_profile_*) ----
 // (calls from several host threads may bracket kernels at once: the list has a lock)
@@ -220,6 +232,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       int64_t rpi = std::max<int64_t>(rpr, target / upr);
       rpi -= rpi % rpr;
       lc.first_item = pl.work.size();
+      lc.rows_per_item = rpi;
       for (size_t j = k; j < e; ++j) {
         const int32_t m = order[j];
         for (int64_t r = 0; r < rows[m]; r += rpi)
@@ -264,6 +277,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       int64_t rpi = std::max<int64_t>(rpb, target / upr);
       rpi -= rpi % rpb;
       lc.first_item = pl.work.size();
+      lc.rows_per_item = rpi;
       for (size_t j = k; j < e; ++j) {
         const int32_t m = order[j];
         for (int64_t r = 0; r < rows[m]; r += rpi)
@@ -331,6 +345,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     int64_t rpi = std::max<int64_t>(1, rounds * nt / upr);
     if (rpi >= period) rpi -= rpi % period;
     lc.first_item = pl.work.size();
+    lc.rows_per_item = rpi;
     for (size_t j = k; j < e; ++j) {
       const int32_t m = order[j];
       for (int64_t r = 0; r < rows[m]; r += rpi)
@@ -376,6 +391,21 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       return EQ_E_HIP;                                \
     }                                                 \
   } while (0)
+
+int static_scratch_of_current_device(unsigned char** out) {
+  int device = -1;
+  EQ_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= kMaxDevices) return EQ_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    EQ_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || ((uintptr_t)ptr & 255)) return EQ_E_WORKSPACE;
+    g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_ptr[device];
+  return EQ_OK;
+}
 
 template <int DT>
 int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const std::vector<MatDesc>& h, const Plan& pl,
@@ -470,6 +500,119 @@ int make_deq_desc(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_para
   return EQ_OK;
 }
 
+
+// Host-visible checks of a batch and its launch plan (no HIP call).
+int check_and_plan(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols, const int64_t* ld,
+                   const eq_params* p, const eq_qmatrix* outs, Plan& pl) {
+  if (!W || !rows || !cols || !ld || !p || !outs) return EQ_E_NULL;
+  if (!params_ok(p)) return EQ_E_PARAM;
+  std::vector<int64_t> caps((size_t)n);
+  for (int32_t i = 0; i < n; ++i) {
+    const int rc = shape_check(rows[i], cols[i], ld[i], p);
+    if (rc != EQ_OK) return rc;
+    const eq_qmatrix& o = outs[i];
+    if (!o.out_row_ptr || !o.status) return EQ_E_NULL;
+    if (o.out_capacity < 0) return EQ_E_SHAPE;
+    const bool empty = rows[i] == 0 || cols[i] == 0;
+    if (!empty && (!W[i] || !o.codes || !o.scales || !o.zero_points)) return EQ_E_NULL;
+    if (o.out_capacity > 0 && (!o.out_col || !o.out_val)) return EQ_E_NULL;
+    if (((uintptr_t)W[i] & 15) || ((uintptr_t)o.codes & 3) || ((uintptr_t)o.scales & 3) ||
+        ((uintptr_t)o.out_row_ptr & 3) || ((uintptr_t)o.out_col & 3) || ((uintptr_t)o.out_val & 1) ||
+        ((uintptr_t)o.status & 3))
+      return EQ_E_ALIGN;
+    caps[(size_t)i] = o.out_capacity;
+  }
+  pl = make_plan(n, rows, cols, caps.data(), p);
+  for (int32_t i = 0; i < n; ++i)
+    if (pl.path[(size_t)i] != 0 && ((uintptr_t)outs[i].codes & 15)) return EQ_E_ALIGN;   // 128-bit code stores
+  return EQ_OK;
+}
+
+// The matrices' descriptors, their workspace slices carved out of `ws` as the plan lays them out.
+int fill_descriptors(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols, const int64_t* ld,
+                     const eq_params* p, const eq_qmatrix* outs, const Plan& pl, unsigned char* ws, std::vector<MatDesc>& h) {
+  h.resize((size_t)n);
+  for (int32_t i = 0; i < n; ++i) {
+    MatDesc& m = h[(size_t)i];
+    std::memset(&m, 0, sizeof(m));
+    const eq_qmatrix& o = outs[i];
+    m.W = dev(static_cast<const uint16_t*>(W[i]));
+    m.codes = dev(o.codes); m.scales = dev(o.scales); m.zps = dev(o.zero_points);
+    m.out_row_ptr = dev(o.out_row_ptr); m.out_col = dev(o.out_col); m.out_val = dev(o.out_val); m.status = dev(o.status);
+    m.cursor = dev(reinterpret_cast<unsigned long long*>(ws + pl.cursor[(size_t)i]));
+    m.row_count = dev(reinterpret_cast<uint32_t*>(ws + pl.row_count[(size_t)i]));
+    m.row_stage = dev(reinterpret_cast<uint32_t*>(ws + pl.row_stage[(size_t)i]));
+    m.st_col = dev(reinterpret_cast<uint32_t*>(ws + pl.st_col[(size_t)i]));
+    m.st_val = dev(reinterpret_cast<uint16_t*>(ws + pl.st_val[(size_t)i]));
+    if (p->stat_scope == EQ_STAT_MATRIX) {
+      m.mat_stats = dev(reinterpret_cast<double*>(ws + pl.mat_stats[(size_t)i]));
+      m.mat_partial = dev(reinterpret_cast<double*>(ws + pl.mat_partial[(size_t)i]));
+    }
+    m.ld = ld[i];
+    m.capacity = clamp_capacity(o.out_capacity);
+    m.rows = (int32_t)rows[i];
+    m.cols = (int32_t)cols[i];
+    m.G = p->group_size ? p->group_size : (int32_t)cols[i];
+    m.upr = m.G ? m.cols / m.G : 0;
+    m.words_per_row = (int32_t)eq_code_words_per_row(cols[i], p->bits);
+    m.path = pl.path[(size_t)i];
+  }
+  return EQ_OK;
+}
+
+// ---- the allocation-free entry point ----------------------------------------------------------
+// What eq_quantize_batch copies from host memory into its workspace, written by a kernel from
+// by-value arguments instead: the one descriptor, the work items (a matrix is cut into items of
+// rows_per_item rows, the last one shorter), Adam's bias corrections 1 - beta^t with their
+// correctly rounded reciprocals (the running products formed as the recurrence defines them,
+// p <- p * beta in binary64; the division is the IEEE one), and the reset of cursor and status.
+constexpr int kNoallocMaxIters = 65536;   // the table is filled by one thread: a bound on that loop
+
+struct SingleSetup {
+  MatDesc md;
+  MatDesc* dmats;
+  WorkItem* ditems;
+  EQ_GLOBAL double* dtab;
+  int64_t rows_per_item;
+  int32_t n_items, iters;
+  double b1, b2;
+};
+
+__global__ __launch_bounds__(kThreads) void setup_single_matrix(SingleSetup s) {
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) {
+      s.dmats[0] = s.md;
+      *s.md.cursor = 0ull;
+      *s.md.status = 0;
+    }
+    if (threadIdx.x == kWave) {            // another wavefront than the one that writes the descriptor
+      double p1 = 1.0, p2 = 1.0;
+      for (int t = 0; t < s.iters; ++t) {
+        p1 = p1 * s.b1;
+        p2 = p2 * s.b2;
+        s.dtab[4 * (size_t)t + 0] = 1.0 - p1;
+        s.dtab[4 * (size_t)t + 1] = 1.0 / (1.0 - p1);
+        s.dtab[4 * (size_t)t + 2] = 1.0 - p2;
+        s.dtab[4 * (size_t)t + 3] = 1.0 / (1.0 - p2);
+      }
+      if (s.iters == 0) {
+        s.dtab[0] = 1.0; s.dtab[1] = 1.0; s.dtab[2] = 1.0; s.dtab[3] = 1.0;
+      }
+    }
+    return;
+  }
+  const int64_t i = (int64_t)(blockIdx.x - 1) * kThreads + threadIdx.x;
+  if (i < s.n_items) {
+    const int64_t r0 = i * s.rows_per_item;
+    WorkItem it;
+    it.mat = 0;
+    it.row0 = (int32_t)r0;
+    it.nrows = (int32_t)(s.md.rows - r0 < s.rows_per_item ? s.md.rows - r0 : s.rows_per_item);
+    it.pad_ = 0;
+    s.ditems[i] = it;
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -491,6 +634,7 @@ const char* eq_strerror(int code) {
     case EQ_E_WORKSPACE: return "workspace missing, misaligned or too small";
     case EQ_E_UNSUPPORTED: return "row too long for on-chip staging";
     case EQ_E_HIP: return "HIP runtime call failed";
+    case EQ_E_SCRATCH: return "matrix and outlier capacity exceed the built-in scratch memory of the allocation-free entry point";
     default: return "unknown error code";
   }
 }
@@ -556,55 +700,14 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
                       void* hip_stream) {
   if (n < 0 || n > 65535) return EQ_E_SHAPE;
   if (n == 0) return EQ_OK;
-  if (!W || !rows || !cols || !ld || !p || !outs) return EQ_E_NULL;
-  if (!params_ok(p)) return EQ_E_PARAM;
-  std::vector<int64_t> caps((size_t)n);
-  for (int32_t i = 0; i < n; ++i) {
-    const int rc = shape_check(rows[i], cols[i], ld[i], p);
-    if (rc != EQ_OK) return rc;
-    const eq_qmatrix& o = outs[i];
-    if (!o.out_row_ptr || !o.status) return EQ_E_NULL;
-    if (o.out_capacity < 0) return EQ_E_SHAPE;
-    const bool empty = rows[i] == 0 || cols[i] == 0;
-    if (!empty && (!W[i] || !o.codes || !o.scales || !o.zero_points)) return EQ_E_NULL;
-    if (o.out_capacity > 0 && (!o.out_col || !o.out_val)) return EQ_E_NULL;
-    if (((uintptr_t)W[i] & 15) || ((uintptr_t)o.codes & 3) || ((uintptr_t)o.scales & 3) ||
-        ((uintptr_t)o.out_row_ptr & 3) || ((uintptr_t)o.out_col & 3) || ((uintptr_t)o.out_val & 1) ||
-        ((uintptr_t)o.status & 3))
-      return EQ_E_ALIGN;
-    caps[(size_t)i] = o.out_capacity;
-  }
-  const Plan pl = make_plan(n, rows, cols, caps.data(), p);
+  Plan pl;
+  std::vector<MatDesc> h;
+  int rc = check_and_plan(n, W, rows, cols, ld, p, outs, pl);
+  if (rc != EQ_OK) return rc;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return EQ_E_WORKSPACE;
-
   unsigned char* ws = static_cast<unsigned char*>(workspace);
-  std::vector<MatDesc> h((size_t)n);
-  for (int32_t i = 0; i < n; ++i) {
-    MatDesc& m = h[(size_t)i];
-    std::memset(&m, 0, sizeof(m));
-    const eq_qmatrix& o = outs[i];
-    m.W = dev(static_cast<const uint16_t*>(W[i]));
-    m.codes = dev(o.codes); m.scales = dev(o.scales); m.zps = dev(o.zero_points);
-    m.out_row_ptr = dev(o.out_row_ptr); m.out_col = dev(o.out_col); m.out_val = dev(o.out_val); m.status = dev(o.status);
-    m.cursor = dev(reinterpret_cast<unsigned long long*>(ws + pl.cursor[(size_t)i]));
-    m.row_count = dev(reinterpret_cast<uint32_t*>(ws + pl.row_count[(size_t)i]));
-    m.row_stage = dev(reinterpret_cast<uint32_t*>(ws + pl.row_stage[(size_t)i]));
-    m.st_col = dev(reinterpret_cast<uint32_t*>(ws + pl.st_col[(size_t)i]));
-    m.st_val = dev(reinterpret_cast<uint16_t*>(ws + pl.st_val[(size_t)i]));
-    if (p->stat_scope == EQ_STAT_MATRIX) {
-      m.mat_stats = dev(reinterpret_cast<double*>(ws + pl.mat_stats[(size_t)i]));
-      m.mat_partial = dev(reinterpret_cast<double*>(ws + pl.mat_partial[(size_t)i]));
-    }
-    m.ld = ld[i];
-    m.capacity = clamp_capacity(o.out_capacity);
-    m.rows = (int32_t)rows[i];
-    m.cols = (int32_t)cols[i];
-    m.G = p->group_size ? p->group_size : (int32_t)cols[i];
-    m.upr = m.G ? m.cols / m.G : 0;
-    m.words_per_row = (int32_t)eq_code_words_per_row(cols[i], p->bits);
-    m.path = pl.path[(size_t)i];
-    if (m.path != 0 && ((uintptr_t)o.codes & 15)) return EQ_E_ALIGN;   // 128-bit code stores
-  }
+  rc = fill_descriptors(n, W, rows, cols, ld, p, outs, pl, ws, h);
+  if (rc != EQ_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   MatDesc* dmats = reinterpret_cast<MatDesc*>(ws + pl.descs);
   // pageable source: the runtime stages the bytes before returning, so `h` may die with this frame
@@ -619,6 +722,47 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   kp.adam_tab = dev(dtab);
   return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, h, pl, kp, st)
                             : launch_all<EQ_BF16>(n, dmats, ditems, h, pl, kp, st);
+}
+
+int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,
+                               const eq_qmatrix* out, void* hip_stream) {
+  if (!out) return EQ_E_NULL;
+  Plan pl;
+  std::vector<MatDesc> h;
+  int rc = check_and_plan(1, &W, &rows, &cols, &ld, p, out, pl);
+  if (rc != EQ_OK) return rc;
+  if (pl.total > (size_t)EQ_STATIC_SCRATCH_BYTES) return EQ_E_SCRATCH;
+  if (p->iters > kNoallocMaxIters) return EQ_E_UNSUPPORTED;
+  unsigned char* ws = nullptr;
+  rc = static_scratch_of_current_device(&ws);
+  if (rc != EQ_OK) return rc;
+  rc = fill_descriptors(1, &W, &rows, &cols, &ld, p, out, pl, ws, h);
+  if (rc != EQ_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // a matrix is served by one launch class at most, whose work items are a regular cut of its rows
+  SingleSetup su;
+  su.md = h[0];
+  su.dmats = reinterpret_cast<MatDesc*>(ws + pl.descs);
+  su.ditems = reinterpret_cast<WorkItem*>(ws + pl.items);
+  su.dtab = dev(reinterpret_cast<double*>(ws + pl.adam));
+  su.n_items = (int32_t)pl.work.size();
+  su.rows_per_item = pl.classes.empty() ? 0 : pl.classes[0].rows_per_item;
+  su.iters = p->iters;
+  su.b1 = (double)p->beta1;
+  su.b2 = (double)p->beta2;
+  // the kernel regenerates the plan's items from (rows, rows_per_item): make sure they are that regular
+  if (pl.classes.size() > 1) return EQ_E_UNSUPPORTED;
+  for (size_t i = 0; i < pl.work.size(); ++i) {
+    const int64_t r0 = (int64_t)i * su.rows_per_item;
+    const WorkItem& w = pl.work[i];
+    if (w.mat != 0 || w.row0 != r0 || w.nrows != std::min<int64_t>(su.rows_per_item, rows - r0)) return EQ_E_UNSUPPORTED;
+  }
+  hipLaunchKernelGGL(setup_single_matrix, dim3((unsigned)((su.n_items + kThreads - 1) / kThreads + 1)), dim3(kThreads), 0, st, su);
+  EQ_HIP(hipGetLastError());
+  KParams kp = make_kparams(p);
+  kp.adam_tab = su.dtab;
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(1, su.dmats, su.ditems, h, pl, kp, st)
+                            : launch_all<EQ_BF16>(1, su.dmats, su.ditems, h, pl, kp, st);
 }
 
 int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,

@@ -30,6 +30,7 @@ struct LaneClass {
   uint32_t pool_slots = 0;
   size_t lds_bytes = 0;
   size_t first_item = 0, n_items = 0;
+  int64_t rows_per_item = 0;            // every matrix of the class is cut into items of this many rows (the last one shorter)
 };
 
 typedef void (*LaneLaunch)(const LaneClass&, const MatDesc*, const WorkItem*, const KParams&, hipStream_t);

@@ -78,6 +78,24 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.eq_quantize_batch(0, None, None, None, None, None, None, None, 0, None) == 0
 
 
+def test_noalloc_entry_point_rejects_what_does_not_fit_its_scratch(lib):
+    """Checked on the host before any HIP call, so no GPU is needed (the pointers are never dereferenced)."""
+    import paper_2403_02775_amd as eqg
+    gp = eqg.Params(group_size=128, iters=1)
+    rows, cols = 8192, 8192
+    cap = eqg.eq_outlier_capacity_bound(rows, cols, gp.n_sigma)     # 11 % of the elements: 45 MB of staging
+    assert eqg.eq_workspace_bytes([rows], [cols], [cap], gp) > eqg.EQ_STATIC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "easyquant.h")).read()
+    assert re.search(r"#define\s+EQ_STATIC_SCRATCH_BYTES\s+\(32u \* 1024u \* 1024u\)", text) and eqg.EQ_STATIC_SCRATCH_BYTES == 32 << 20
+    cp = gp.c()
+    q = eqg.binding._CQMatrix(1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 20, 1 << 20, cap, 1 << 20)
+    rc = lib.eq_quantize_matrix_noalloc(1 << 20, rows, cols, cols, ctypes.byref(cp), ctypes.byref(q), None)
+    assert rc == -8 and "scratch" in eqg.eq_strerror(rc)
+    assert lib.eq_quantize_matrix_noalloc(1 << 20, rows, cols, cols, ctypes.byref(cp), None, None) == -1
+    bad = eqg.Params(bits=9).c()
+    assert lib.eq_quantize_matrix_noalloc(1 << 20, rows, cols, cols, ctypes.byref(bad), ctypes.byref(q), None) == -3
+
+
 def test_header_is_plain_c_and_links_from_a_c_program(lib, tmp_path):
     """The boundary is a C ABI: the header compiles as C99 and a C program linked against the
     library can call it (host-only entry points here; nothing touches a GPU)."""
