@@ -21,10 +21,11 @@
  *    never allocates, frees or retains device memory.  Every pointer marked HOST is
  *    read before the call returns.
  *  - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
- *    default stream) and return without waiting for it.  The quantize calls first copy
- *    their descriptors from pageable host memory into the workspace on that stream; the
- *    runtime may hold such a copy, and with it the call, until work queued earlier on the
- *    same stream has finished.
+ *    default stream) and return without waiting for it.  eq_quantize_matrix / _batch first
+ *    copy their descriptors into the workspace on that stream, in one piece, from a pinned
+ *    host block that the library owns and reuses once the copy has completed (a few hundred
+ *    KB, allocated on first use): the call does not depend on how the runtime treats
+ *    pageable memory and never waits for work queued earlier.
  *  - Return value: EQ_OK or a negative EQ_E_* code for problems visible on the host
  *    (nothing is enqueued then).  Conditions only the GPU can see are reported in
  *    the per-matrix DEVICE status word (EQ_S_* bits), valid once the stream is idle.
@@ -62,7 +63,8 @@ enum {
   EQ_E_NULL = -1,         /* a required pointer is NULL */
   EQ_E_SHAPE = -2,        /* rows/cols/ld/group_size inconsistent (see eq_quantize_matrix) */
   EQ_E_PARAM = -3,        /* bits, mode, dtype, scope, select or a hyper-parameter out of range */
-  EQ_E_ALIGN = -4,        /* W or W_out not 16-byte aligned, codes not 4-byte aligned */
+  EQ_E_ALIGN = -4,        /* W, W_out or x not 16-byte aligned; codes not 16-byte aligned in a quantize
+                             call (4-byte in the consumers); another output not aligned to its type */
   EQ_E_WORKSPACE = -5,    /* workspace NULL, misaligned (256 B) or smaller than eq_workspace_bytes() */
   EQ_E_UNSUPPORTED = -6,  /* a row too long for on-chip staging (cols > EQ_MAX_COLS) */
   EQ_E_HIP = -7,          /* a HIP runtime call failed (launch, copy); eq_last_hip_error() has the code */
@@ -113,7 +115,8 @@ typedef struct eq_qmatrix {
 
 /* Algorithm 1, "Quantize", for one matrix.
  *   W      DEVICE, rows x cols elements of p->dtype, row stride ld elements (ld >= cols,
- *          ld % 8 == 0, W 16-byte aligned).  Read only.
+ *          ld % 8 == 0, W 16-byte aligned).  Read only.  out->codes must be 16-byte aligned
+ *          as well (the kernels store code words 128 bits at a time).
  *   rows   >= 0, cols >= 0 with cols % 8 == 0 (cols % 32 == 0 when group_size != 0) and
  *          cols <= EQ_MAX_COLS.  rows == 0 or cols == 0 enqueues nothing but still
  *          clears status / out_row_ptr.
@@ -130,15 +133,7 @@ typedef struct eq_qmatrix {
  * one range per row with cols a multiple of 128 in 2048..32768 spreads the row over
  * cols / 128 lanes (rows of 11008, 13824, 17920 or 22016 columns with 4-bit codes: in
  * equal pieces over 128 or 256 lanes); everything else goes to a general kernel (one
- * workgroup per row, one wavefront per unit).  Four environment variables, read at every call, exist for tests and
- * measurements: EASYQUANT_UNITS_PER_ITEM=<n> sets the number of units a workgroup walks
- * through (changes only how the work is cut up), EASYQUANT_FORCE_GENERAL=1 sends every
- * matrix to the general kernel, EASYQUANT_RTN_THREADS=256 | 512 runs the iters == 0 variant
- * with workgroups of 256 threads for every row length (default: 128 up to 8192 columns, 256
- * beyond, 192 for 8193..12288 and 16385..24576) or of 512 threads for rows longer than 8192,
- * EASYQUANT_CHANNEL_KERNEL=128 keeps
- * per-channel rows on the kernel with 128-element segments also where another one would
- * serve them (rows of 11008, 13824, 17920 and 22016 columns; iters == 0). */
+ * workgroup per row, one wavefront per unit). */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,
                        const eq_params* p, const eq_qmatrix* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -176,9 +171,9 @@ EQ_API int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols,
  * for normal values, the stored raw pattern for outliers.  W_out DEVICE, rows x cols of
  * p->dtype with row stride ld_out (>= cols, % 8 == 0, 16-byte aligned).  Only dtype, bits
  * and group_size of p are read.  q->status is not touched.  The outlier list must be in the
- * form eq_quantize_* writes it: columns ascending within each row (an entry out of order, or
- * with a column >= cols, ends the row's list: it and the entries after it are not applied;
- * nothing outside W_out is ever written).  q->out_col / q->out_val NULL: no outliers.
+ * form eq_quantize_* writes it: columns ascending within each row (for a malformed list, with
+ * an entry out of order or a column >= cols, it is unspecified which entries of that row are
+ * applied; nothing outside W_out is ever written).  q->out_col / q->out_val NULL: no outliers.
  * One kernel launch on hip_stream, every argument passed by value, no device memory
  * allocated or copied: the call (like eq_dequant_matvec) may be recorded into a HIP graph;
  * the eq_quantize_* calls may not, they upload descriptors from host memory. */
@@ -193,9 +188,8 @@ EQ_API int eq_dequantize(const eq_qmatrix* q, int64_t rows, int64_t cols, const 
  * Products and sums are binary32 in an unspecified order: y agrees with the exact product to
  * within 3e-5 * sum_j |W^_ij x_j| per row.  q as for eq_dequantize.  cols == 0 gives y = 0.
  * 4-bit codes with one range per row, or with groups of a power of two >= 64 elements, are
- * served from small tables of the 16 values a weight of the row / group can take
- * (EASYQUANT_MATVEC_TABLES=0 in the environment, for tests and measurements, takes the plain
- * arithmetic for grouped codes instead; the weights are the same bits either way). */
+ * served from small tables of the 16 values a weight of the row / group can take (the weights
+ * are the same bits as with the plain arithmetic that serves every other format). */
 EQ_API int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_params* p,
                       const void* x, float* y, void* hip_stream);
 
@@ -216,7 +210,8 @@ EQ_API int64_t eq_outlier_capacity_bound(int64_t rows, int64_t cols, float n_sig
  * Adam lr 1e-3 for 100 steps (Sec. 5, Setup), fp16, row statistics, best iterate. */
 EQ_API void eq_default_params(eq_params* p);
 
-/* Instrumentation for benchmarks.  While enabled, every launch of a main quantization kernel
+/* INSTRUMENTATION for benchmarks (not needed to use the library; off by default, and the
+ * quantization and its results are the same with it on).  While enabled, every launch of a main quantization kernel
  * (the kernels that run Algorithm 1's "Quantize"; not the small reset / prefix-sum / gather
  * kernels around them) is bracketed by HIP events on the call's stream.
  * eq_profile_read waits for those events, returns the summed kernel time in milliseconds and
@@ -224,13 +219,6 @@ EQ_API void eq_default_params(eq_params* p);
  * all host threads of the process (a lock guards it): a read returns every thread's launches. */
 EQ_API int eq_profile_enable(int on);
 EQ_API int eq_profile_read(double* kernel_ms, int32_t* launches);
-
-/* Diagnostics (host only, no GPU): the library divides by values whose correctly rounded
- * reciprocal it knows (Adam's bias corrections, the level count D) with a short multiply-add
- * sequence instead of a hardware division.  These run that same sequence on the host so that
- * a test can confirm it returns the IEEE quotient a / b bit for bit. */
-EQ_API double eq_diag_div_f64(double a, double b);
-EQ_API float eq_diag_div_f32(float a, float b);
 
 /* Static description of a return code. */
 EQ_API const char* eq_strerror(int code);

@@ -81,10 +81,16 @@ def lib() -> C.CDLL:
         L.eq_strerror.argtypes = [C.c_int]
         L.eq_last_hip_error.restype = C.c_int
         L.eq_last_hip_error.argtypes = []
-        L.eq_diag_div_f64.restype = C.c_double
-        L.eq_diag_div_f64.argtypes = [C.c_double, C.c_double]
-        L.eq_diag_div_f32.restype = C.c_float
-        L.eq_diag_div_f32.argtypes = [C.c_float, C.c_float]
+        # hooks for the library's own tests and measurements (csrc/eq_testing.h; not part of the C ABI)
+        L.eq_test_div_f64.restype = C.c_double
+        L.eq_test_div_f64.argtypes = [C.c_double, C.c_double]
+        L.eq_test_div_f32.restype = C.c_float
+        L.eq_test_div_f32.argtypes = [C.c_float, C.c_float]
+        L.eq_test_set_override.restype = C.c_int
+        L.eq_test_set_override.argtypes = [C.c_int, C.c_int64]
+        L.eq_test_plan_items.restype = C.c_int64
+        L.eq_test_plan_items.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                         C.POINTER(_CParams), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int64]
         L.eq_profile_enable.restype = C.c_int
         L.eq_profile_enable.argtypes = [C.c_int]
         L.eq_profile_read.restype = C.c_int
@@ -258,3 +264,45 @@ def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tens
                              _ld(W_out), _stream_ptr(stream))
     if rc != 0:
         raise EasyQuantError(rc, "eq_dequantize")
+
+
+# ---- hooks for tests and measurements (csrc/eq_testing.h; not part of the C ABI) ----------------
+OVR_UNITS_PER_ITEM, OVR_FORCE_GENERAL, OVR_RTN_THREADS, OVR_CHANNEL_KERNEL, OVR_MATVEC_ARITHMETIC = range(5)
+
+
+class override:
+    """`with override(OVR_FORCE_GENERAL, 1): ...` sets a kernel-selection override of the library
+    for the duration of the block (process-wide; results do not depend on it)."""
+
+    def __init__(self, which: int, value: int):
+        self.which, self.value = which, int(value)
+
+    def __enter__(self):
+        set_override(self.which, self.value)
+        return self
+
+    def __exit__(self, *exc):
+        set_override(self.which, 0)
+        return False
+
+
+def set_override(which: int, value: int) -> None:
+    rc = lib().eq_test_set_override(which, int(value))
+    if rc != 0:
+        raise EasyQuantError(rc, "eq_test_set_override")
+
+
+def plan_items(rows: Sequence[int], cols: Sequence[int], capacities: Sequence[int], p: Params):
+    """The work items eq_quantize_batch would launch for these shapes: a list of
+    (matrix, first row, rows, launch index) in launch order (host only, no GPU)."""
+    n = len(rows)
+    A = C.c_int64 * max(n, 1)
+    cp = p.c()
+    args = (n, A(*rows), A(*cols), A(*capacities), C.byref(cp))
+    cnt = int(lib().eq_test_plan_items(*args, None, None, 0))
+    if cnt < 0:
+        raise EasyQuantError(cnt, "eq_test_plan_items")
+    items = (C.c_int32 * (3 * max(cnt, 1)))()
+    launch = (C.c_int32 * max(cnt, 1))()
+    lib().eq_test_plan_items(*args, items, launch, cnt)
+    return [(items[3 * i], items[3 * i + 1], items[3 * i + 2], launch[i]) for i in range(cnt)]

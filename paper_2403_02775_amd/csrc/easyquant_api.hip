@@ -20,6 +20,7 @@
 #include "eq_launch.h"
 #include "eq_post.h"
 #include "eq_rowstage.h"
+#include "eq_testing.h"
 
 // Scratch memory of eq_quantize_matrix_noalloc: every GPU the library's code object is loaded
 // on holds its own copy of this array, at its own address, until the process ends.  In host code
@@ -38,6 +39,10 @@ constexpr int kMaxDevices = 64;
 std::mutex g_scratch_lock;
 unsigned char* g_scratch_ptr[kMaxDevices] = {};
 
+
+// ---- kernel-selection overrides for tests and measurements (eq_testing.h); 0 = default ----
+std::atomic<int64_t> g_override[EQ_OVR_COUNT] = {};
+inline int64_t override_of(int which) { return g_override[which].load(std::memory_order_relaxed); }
 
 // ---- optional event bracketing of the main kernels (eq_profile_*) ----
 // (calls from several host threads may bracket kernels at once: the list has a lock)
@@ -176,8 +181,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
   pl.path.assign((size_t)n, 0);
   // ---- launch plan ----
   std::vector<int32_t> order;
-  const char* fg = std::getenv("EASYQUANT_FORCE_GENERAL");        // test / measurement override
-  const bool force_general = fg && fg[0] == '1';
+  const bool force_general = override_of(EQ_OVR_FORCE_GENERAL) == 1;   // test / measurement override
   for (int32_t i = 0; i < n; ++i) {
     if (force_general) {
       if (rows[i] > 0 && cols[i] > 0) pl.any_general = true;
@@ -201,8 +205,8 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     LaneClass lc;
     lc.cols = (int32_t)c;
     lc.upr = (int32_t)upr;
-    const char* chan_which = std::getenv("EASYQUANT_CHANNEL_KERNEL");
-    const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && p->iters == 0 && !(chan_which && std::strcmp(chan_which, "128") == 0);
+    const bool chan_keep128 = override_of(EQ_OVR_CHANNEL_KERNEL) == 128;
+    const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && p->iters == 0 && !chan_keep128;
     if (pl.path[(size_t)order[k]] == 2 && !chan_rtn) {
       // per-channel: a round is floor(256 / segments) whole rows; items are multiples of that
       lc.kind = 2;
@@ -216,19 +220,15 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // rows with 4-bit codes whose 128-element segments would leave many of the 256 lanes
       // idle (the MLP down-projections of the LLaMA shapes): equal pieces over all lanes instead
       // (eq_channel_split.h).  chunks_per_thread selects the instantiation.
-      const char* which = std::getenv("EASYQUANT_CHANNEL_KERNEL");
       const int split = c == 86 * 256 ? 1 : c == 86 * 128 ? 2 : c == 54 * 256 ? 3 : c == 70 * 256 ? 4 : 0;
-      if (split && p->bits == 4 && !(which && std::strcmp(which, "128") == 0)) {
+      if (split && p->bits == 4 && !chan_keep128) {
         lc.kind = 5;
         rpr = split == 2 ? 2 : 1;
         lc.chunks_per_thread = split;
         lc.lds_bytes = (size_t)kChanHeader + (size_t)rpr * (size_t)c * 2;
       }
       int64_t target = std::min<int64_t>(8192, std::max<int64_t>(kChanThreads, total_units / 16384));
-      if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
-        const long v = std::atol(ov);
-        if (v > 0) target = v;
-      }
+      if (override_of(EQ_OVR_UNITS_PER_ITEM) > 0) target = override_of(EQ_OVR_UNITS_PER_ITEM);
       int64_t rpi = std::max<int64_t>(rpr, target / upr);
       rpi -= rpi % rpr;
       lc.first_item = pl.work.size();
@@ -254,11 +254,8 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // three wavefronts where the chunks per thread stay the same power of two (8 up to 12288
       // columns, 16 up to 24576): fewer idle lanes and empty load slots (11008: 90 % instead of 67 %)
       if ((c > 8192 && c <= 12288) || (c > 16384 && c <= 24576)) lc.threads = 192;
-      if (const char* ov = std::getenv("EASYQUANT_RTN_THREADS")) {
-        const long t = std::atol(ov);
-        if (t == 256) lc.threads = 256;
-        if (t == 512 && c > 8192) lc.threads = 512;
-      }
+      if (override_of(EQ_OVR_RTN_THREADS) == 256) lc.threads = 256;
+      if (override_of(EQ_OVR_RTN_THREADS) == 512 && c > 8192) lc.threads = 512;
       const int64_t per_thread = (c / 8 + lc.threads - 1) / lc.threads;
       lc.chunks_per_thread = per_thread <= 1 ? 1 : per_thread <= 2 ? 2 : per_thread <= 4 ? 4 : per_thread <= 8 ? 8 : 16;
       if (lc.threads == 512 && lc.chunks_per_thread < 4) lc.chunks_per_thread = 4;
@@ -270,10 +267,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // some 30 000 items per launch, of 2048 to 8192 units each (measured on the 65B- and 7B-shaped
       // sets against items 2, 4 and 8 times as large: 4 % and 8 % faster)
       int64_t target = std::min<int64_t>(8192, std::max<int64_t>(2048, total_units / 32768));
-      if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {
-        const long v = std::atol(ov);
-        if (v > 0) target = v;
-      }
+      if (override_of(EQ_OVR_UNITS_PER_ITEM) > 0) target = override_of(EQ_OVR_UNITS_PER_ITEM);
       int64_t rpi = std::max<int64_t>(rpb, target / upr);
       rpi -= rpi % rpb;
       lc.first_item = pl.work.size();
@@ -334,10 +328,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     // an item's last round is partly filled when rows do not tile the rounds: at least four
     // rounds per item as long as that still leaves a thousand items
     if (target < 4 * nt && total_units / (4 * nt) >= 1024) target = 4 * nt;
-    if (const char* ov = std::getenv("EASYQUANT_UNITS_PER_ITEM")) {   // tuning / test override
-      const long v = std::atol(ov);
-      if (v > 0) target = v;
-    }
+    if (override_of(EQ_OVR_UNITS_PER_ITEM) > 0) target = override_of(EQ_OVR_UNITS_PER_ITEM);   // tuning / test override
     const int64_t period = nt / g;
     // as many rows as fill a whole number of rounds as nearly as possible from below: the last
     // round of an item runs with the lanes that are left
@@ -405,6 +396,67 @@ int static_scratch_of_current_device(unsigned char** out) {
   }
   *out = g_scratch_ptr[device];
   return EQ_OK;
+}
+
+// ---- pinned host blocks for the descriptor upload ---------------------------------------------
+// A call packs what it uploads into one of these and records an event behind the copy; a block is
+// taken again only when its event has completed, so its bytes outlive the copy whatever the
+// runtime does with host memory.  Blocks are allocated on demand (a few at most: one per call in
+// flight), kept for the life of the process, and handed out under a lock.
+struct PinnedBlock {
+  void* host = nullptr;
+  size_t bytes = 0;
+  hipEvent_t done = nullptr;
+  bool in_use = false;          // between acquire and release
+  bool pending = false;         // a copy from it has been enqueued: `done` says when it is over
+};
+std::mutex g_pinned_lock;
+std::vector<PinnedBlock*> g_pinned;
+
+PinnedBlock* acquire_pinned(size_t bytes) {
+  std::lock_guard<std::mutex> hold(g_pinned_lock);
+  PinnedBlock* pick = nullptr;
+  for (PinnedBlock* b : g_pinned) {
+    if (b->in_use) continue;
+    if (b->pending && hipEventQuery(b->done) != hipSuccess) continue;    // its copy is still on its way
+    b->pending = false;
+    if (!pick || (pick->bytes < bytes && b->bytes > pick->bytes)) pick = b;
+    if (pick->bytes >= bytes) break;
+  }
+  if (!pick) {
+    if (g_pinned.size() >= 16) {
+      // many calls in flight: wait for the oldest block instead of growing without bound
+      for (PinnedBlock* b : g_pinned)
+        if (!b->in_use) { pick = b; break; }
+      if (!pick) { g_last_hip_error = (int)hipErrorOutOfMemory; return nullptr; }
+      hipError_t e = hipEventSynchronize(pick->done);
+      if (e != hipSuccess) { g_last_hip_error = (int)e; return nullptr; }
+      pick->pending = false;
+    } else {
+      pick = new PinnedBlock();
+      hipError_t e = hipEventCreateWithFlags(&pick->done, hipEventDisableTiming);
+      if (e != hipSuccess) { g_last_hip_error = (int)e; delete pick; return nullptr; }
+      g_pinned.push_back(pick);
+    }
+  }
+  if (pick->bytes < bytes) {
+    if (pick->host) (void)hipHostFree(pick->host);
+    pick->host = nullptr;
+    pick->bytes = 0;
+    const size_t want = align_up(bytes + bytes / 4, 65536);
+    hipError_t e = hipHostMalloc(&pick->host, want, hipHostMallocDefault);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; pick->host = nullptr; return nullptr; }
+    pick->bytes = want;
+  }
+  pick->in_use = true;
+  return pick;
+}
+
+void release_pinned(PinnedBlock* b, hipStream_t st, bool copy_enqueued) {
+  std::lock_guard<std::mutex> hold(g_pinned_lock);
+  if (copy_enqueued && hipEventRecord(b->done, st) == hipSuccess) b->pending = true;
+  else if (copy_enqueued) (void)hipStreamSynchronize(st);   // no event: make sure the copy is over instead
+  b->in_use = false;
 }
 
 template <int DT>
@@ -516,15 +568,13 @@ int check_and_plan(int32_t n, const void* const* W, const int64_t* rows, const i
     const bool empty = rows[i] == 0 || cols[i] == 0;
     if (!empty && (!W[i] || !o.codes || !o.scales || !o.zero_points)) return EQ_E_NULL;
     if (o.out_capacity > 0 && (!o.out_col || !o.out_val)) return EQ_E_NULL;
-    if (((uintptr_t)W[i] & 15) || ((uintptr_t)o.codes & 3) || ((uintptr_t)o.scales & 3) ||
+    if (((uintptr_t)W[i] & 15) || ((uintptr_t)o.codes & 15) || ((uintptr_t)o.scales & 3) ||
         ((uintptr_t)o.out_row_ptr & 3) || ((uintptr_t)o.out_col & 3) || ((uintptr_t)o.out_val & 1) ||
         ((uintptr_t)o.status & 3))
       return EQ_E_ALIGN;
     caps[(size_t)i] = o.out_capacity;
   }
   pl = make_plan(n, rows, cols, caps.data(), p);
-  for (int32_t i = 0; i < n; ++i)
-    if (pl.path[(size_t)i] != 0 && ((uintptr_t)outs[i].codes & 15)) return EQ_E_ALIGN;   // 128-bit code stores
   return EQ_OK;
 }
 
@@ -641,8 +691,35 @@ const char* eq_strerror(int code) {
 
 int eq_last_hip_error(void) { return g_last_hip_error; }
 
-double eq_diag_div_f64(double a, double b) { return div_known_rcp(a, b, 1.0 / b); }
-float eq_diag_div_f32(float a, float b) { return div_known_rcp(a, b, 1.0f / b); }
+double eq_test_div_f64(double a, double b) { return div_known_rcp(a, b, 1.0 / b); }
+float eq_test_div_f32(float a, float b) { return div_known_rcp(a, b, 1.0f / b); }
+
+int eq_test_set_override(int which, int64_t value) {
+  if (which < 0 || which >= EQ_OVR_COUNT) return EQ_E_PARAM;
+  g_override[which].store(value, std::memory_order_relaxed);
+  return EQ_OK;
+}
+
+int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
+                           const eq_params* p, int32_t* items, int32_t* launch_of_item, int64_t max_items) {
+  if (n < 0 || !p || (n > 0 && (!rows || !cols || !out_capacity))) return EQ_E_NULL;
+  if (!params_ok(p)) return EQ_E_PARAM;
+  for (int32_t i = 0; i < n; ++i)
+    if (rows[i] < 0 || cols[i] < 0 || rows[i] > 0x7FFFFFFF) return EQ_E_SHAPE;
+  const Plan pl = make_plan(n, rows, cols, out_capacity, p);
+  for (size_t c = 0; c < pl.classes.size(); ++c) {
+    const LaneClass& lc = pl.classes[c];
+    for (size_t i = lc.first_item; i < lc.first_item + lc.n_items && (int64_t)i < max_items; ++i) {
+      if (items) {
+        items[3 * i + 0] = pl.work[i].mat;
+        items[3 * i + 1] = pl.work[i].row0;
+        items[3 * i + 2] = pl.work[i].nrows;
+      }
+      if (launch_of_item) launch_of_item[i] = (int32_t)c;
+    }
+  }
+  return (int64_t)pl.work.size();
+}
 
 int eq_profile_enable(int on) {
   g_profile = on != 0;
@@ -710,15 +787,22 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   if (rc != EQ_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   MatDesc* dmats = reinterpret_cast<MatDesc*>(ws + pl.descs);
-  // pageable source: the runtime stages the bytes before returning, so `h` may die with this frame
-  EQ_HIP(hipMemcpyAsync(dmats, h.data(), sizeof(MatDesc) * (size_t)n, hipMemcpyHostToDevice, st));
   WorkItem* ditems = reinterpret_cast<WorkItem*>(ws + pl.items);
-  if (!pl.work.empty())
-    EQ_HIP(hipMemcpyAsync(ditems, pl.work.data(), sizeof(WorkItem) * pl.work.size(), hipMemcpyHostToDevice, st));
-  KParams kp = make_kparams(p);
-  const std::vector<double> tab = make_adam_table(p);
   double* dtab = reinterpret_cast<double*>(ws + pl.adam);
-  EQ_HIP(hipMemcpyAsync(dtab, tab.data(), sizeof(double) * tab.size(), hipMemcpyHostToDevice, st));
+  // Descriptors, work items and Adam's table lead the workspace in that order: they are packed
+  // with the same offsets into one pinned host block and go up in a single copy.
+  const std::vector<double> tab = make_adam_table(p);
+  const size_t head_bytes = pl.adam + sizeof(double) * tab.size();
+  PinnedBlock* blk = acquire_pinned(head_bytes);
+  if (!blk) return EQ_E_HIP;
+  unsigned char* hb = static_cast<unsigned char*>(blk->host);
+  std::memcpy(hb + pl.descs, h.data(), sizeof(MatDesc) * (size_t)n);
+  if (!pl.work.empty()) std::memcpy(hb + pl.items, pl.work.data(), sizeof(WorkItem) * pl.work.size());
+  std::memcpy(hb + pl.adam, tab.data(), sizeof(double) * tab.size());
+  hipError_t ce = hipMemcpyAsync(ws, hb, head_bytes, hipMemcpyHostToDevice, st);
+  release_pinned(blk, st, ce == hipSuccess);
+  EQ_HIP(ce);
+  KParams kp = make_kparams(p);
   kp.adam_tab = dev(dtab);
   return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, h, pl, kp, st)
                             : launch_all<EQ_BF16>(n, dmats, ditems, h, pl, kp, st);
@@ -815,9 +899,8 @@ int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_
     // per-group tables (modes 3 and 4) need groups of at least 64 elements that tile the kernel's
     // 4096-column segments or are tiled by them
     const int64_t seg_cols = (int64_t)kMvChunks * kThreads * 8;
-    const char* tv = std::getenv("EASYQUANT_MATVEC_TABLES");           // test / measurement override: 0 = arithmetic
     const bool tables = d.G >= 64 && (d.G & (d.G - 1)) == 0 && (seg_cols % d.G == 0 || d.G % seg_cols == 0) &&
-                        !(tv && tv[0] == '0');
+                        override_of(EQ_OVR_MATVEC_ARITHMETIC) != 1;   // test / measurement override
     const int mode = p->bits != 4 ? 0 : d.upr == 1 ? 2 : tables ? (d.G == 64 ? 4 : 3) : 1;
 #define EQ_MV(DT_, MODE_) hipLaunchKernelGGL((dequant_matvec<DT_, MODE_>), grid, block, 0, st, d, xd, yd)
     if (p->dtype == EQ_F16) {

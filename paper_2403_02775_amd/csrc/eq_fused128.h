@@ -462,7 +462,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       const int q = 30 - E;
       // What follows works on the slot either in the input type or, for bf16, in the fp16 form
       // described at slot_fits_f16 (DX, with k = shift): planes, optimisation, emission.
-      auto rest = [&](auto dx, const int shift) {
+      auto optimise = [&](auto dx, const int shift) -> float {
         constexpr int DX = decltype(dx)::value;
         const float unshift = ldexpf(1.0f, -shift);          // exact power of two
         uint32_t H[kPairs], Lo[kPairs];
@@ -482,26 +482,37 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             B = ldexp(B, -shift);
           });
         }
-
-        // ---- emit (Algorithm 1, third step) ----
+        return r_sel;
+      };
+      // ---- emit (Algorithm 1, third step) ----
+      auto emit = [&](auto dx, const int shift, const float r_sel) {
+        constexpr int DX = decltype(dx)::value;
         float s32, inv;
         scale_of(kp, r_sel, s32, inv);
-        __syncthreads();              // every lane has finished reading slots that are not its own
-        if (valid) {
-          emit_codes_to_slot<DX>(kp, slot, inv * unshift, z);
-          const int64_t gu = unit_base + slot_i;
-          md.scales[gu] = s32;
-          md.zps[gu] = (unsigned char)z;
-        }
+        emit_codes_to_slot<DX>(kp, slot, inv * ldexpf(1.0f, -shift), z);
+        const int64_t gu = unit_base + slot_i;
+        md.scales[gu] = s32;
+        md.zps[gu] = (unsigned char)z;
       };
+      // bf16 units are taken in their fp16 form when every unit of the WAVEFRONT has one (the choice
+      // may differ between the wavefronts of a workgroup: both branches below are barrier-free, and
+      // all wavefronts meet at the one barrier between optimisation and emission).  A lane without a
+      // unit works on a copy of the round's first slot and discards the result; it may read that slot
+      // while its owner converts or emits it, which only changes what is discarded.
       bool as_f16 = false;
       const int shift = 15 - E;
       if (DT == EQ_BF16) {
         as_f16 = __all(!valid || slot_fits_f16(slot, shift));
         if (as_f16 && valid) slot_bf16_to_f16(slot, shift);
       }
-      if (DT == EQ_BF16 && as_f16) rest(std::integral_constant<int, EQ_F16>{}, shift);
-      else rest(std::integral_constant<int, DT>{}, 0);
+      float r_sel;
+      if (DT == EQ_BF16 && as_f16) r_sel = optimise(std::integral_constant<int, EQ_F16>{}, shift);
+      else r_sel = optimise(std::integral_constant<int, DT>{}, 0);
+      __syncthreads();                // every lane has finished reading slots that are not its own
+      if (valid) {
+        if (DT == EQ_BF16 && as_f16) emit(std::integral_constant<int, EQ_F16>{}, shift, r_sel);
+        else emit(std::integral_constant<int, DT>{}, 0, r_sel);
+      }
       __syncthreads();
       copy_wave_codes(kp, md, pool, unit_base, base + wave * kWave, take, lane);
     }

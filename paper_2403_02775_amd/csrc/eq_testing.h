@@ -1,0 +1,49 @@
+/*
+ * eq_testing.h -- hooks of libeasyquant.so for its own tests and measurements.
+ *
+ * These symbols are exported by the library but are NOT part of its C ABI (include/easyquant.h):
+ * they may change with the kernels.  Nothing here changes a result: the overrides only change
+ * which of several equivalent kernels serves a matrix or how the rows are cut into work items.
+ */
+#ifndef EQ_TESTING_H_
+#define EQ_TESTING_H_
+
+#include "easyquant.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Kernel-selection overrides, process-wide, 0 = the library's own choice (the default). */
+enum {
+  EQ_OVR_UNITS_PER_ITEM = 0, /* n > 0: units a workgroup walks through (how the work is cut up) */
+  EQ_OVR_FORCE_GENERAL = 1,  /* 1: every matrix goes to the general kernel */
+  EQ_OVR_RTN_THREADS = 2,    /* 256 | 512: workgroup size of the kernel without optimisation steps
+                                (512 only for rows longer than 8192) */
+  EQ_OVR_CHANNEL_KERNEL = 3, /* 128: per-channel rows stay on the kernel with 128-element segments
+                                where another one would serve them */
+  EQ_OVR_MATVEC_ARITHMETIC = 4, /* 1: eq_dequant_matvec takes the plain arithmetic for grouped 4-bit
+                                   codes instead of the per-group tables (same weights either way) */
+  EQ_OVR_COUNT = 5
+};
+EQ_API int eq_test_set_override(int which, int64_t value);   /* EQ_OK or EQ_E_PARAM */
+
+/* The launch plan of eq_quantize_batch for these shapes (host only, no GPU): writes up to
+ * max_items work items as (matrix, first row, rows) triples into `items` and returns the number
+ * of items of the plan (which may exceed max_items), or a negative EQ_E_* code.  Matrices that
+ * the general kernel serves (one workgroup per row) have no items.  `launch_of_item`, if not
+ * NULL, receives for each written item the index of the launch (row-length class) it belongs to. */
+EQ_API int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
+                                  const eq_params* p, int32_t* items, int32_t* launch_of_item, int64_t max_items);
+
+/* The library divides by values whose correctly rounded reciprocal it knows (Adam's bias
+ * corrections, the level count D) with a short multiply-add sequence instead of a hardware
+ * division.  These run that same sequence on the host so that a test can confirm it returns the
+ * IEEE quotient a / b bit for bit. */
+EQ_API double eq_test_div_f64(double a, double b);
+EQ_API float eq_test_div_f32(float a, float b);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EQ_TESTING_H_ */

@@ -52,13 +52,13 @@ def test_small_matrices_across_bits_groups_modes(bits, G, mode):
                                                       (70, 22016, 20000), (40, 11008, 20000),
                                                       # the ends of the row lengths that are staged three rows to a batch
                                                       (11, 24576, 0), (7, 21888, 0), (10, 10880, 0), (9, 11776, 0)])
-def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_item, monkeypatch):
+def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_item, eq_override):
     # group 128: rows whose unit count does not divide the 256- or 512-unit rounds leave units
     # behind that are carried to the next fill; the override makes work items span several rounds.
     # The two largest cases run long enough for the carried units to exhaust the LDS pool of the
     # 512-thread variant, which then runs a partly filled round.
     if units_per_item:
-        monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", str(units_per_item))
+        eq_override(eqg.OVR_UNITS_PER_ITEM, units_per_item)
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows + cols, device=DEV)
     for bits in (4, 3):
         res = _check(W, eqo.Params(bits=bits, group_size=128, iters=12), f"lane kernel {rows}x{cols}")
@@ -68,11 +68,11 @@ def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_it
 @pytest.mark.parametrize("rows,cols,units_per_item", [(37, 4096, 0), (21, 8192, 300), (5, 22016, 0), (11, 11008, 0),
                                                       (13, 5120, 0), (40, 2048, 512), (3, 32768, 0), (4, 13824, 0),
                                                       (3, 17920, 0), (7, 11008, 200)])
-def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, monkeypatch):
+def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, eq_override):
     # one range per row, the row spread over cols / 128 lanes: rounds of 8, 4, 1, 2, 6, 16 and 1
     # rows, a ragged last round, several rounds per work item, staging in one or several batches
     if units_per_item:
-        monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", str(units_per_item))
+        eq_override(eqg.OVR_UNITS_PER_ITEM, units_per_item)
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows * 7 + cols, device=DEV)
     for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
         res = _check(W, eqo.Params(bits=bits, group_size=0, mode=mode, iters=12), f"channel kernel {rows}x{cols}")
@@ -80,7 +80,7 @@ def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, monkeypa
 
 
 @pytest.mark.parametrize("cols", [22016, 11008])
-def test_per_channel_rows_cut_into_equal_pieces(cols, monkeypatch):
+def test_per_channel_rows_cut_into_equal_pieces(cols, eq_override):
     # rows of 86 * 256 or 86 * 128 values with 4-bit codes take the kernel that cuts a row into
     # equal pieces over all 256 lanes: its variants, its binary64 fallback, and the 128-element
     # kernel it replaces on the same input
@@ -110,13 +110,13 @@ def test_per_channel_rows_cut_into_equal_pieces(cols, monkeypatch):
     Wb[2] = Wb[2] * 1e30
     res = _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=0, iters=10), f"split {cols} bf16 wide span")
     assert res["excused_elems"] == 0
-    monkeypatch.setenv("EASYQUANT_CHANNEL_KERNEL", "128")
+    eq_override(eqg.OVR_CHANNEL_KERNEL, 128)
     res = _check(W, eqo.Params(bits=4, group_size=0, iters=8), f"128-element kernel on {cols}")
     assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
 
 @pytest.mark.parametrize("rows,cols", [(37, 4096), (9, 22016), (21, 8192), (40, 2048), (3, 32768), (11, 11008)])
-def test_per_channel_without_optimisation_steps(rows, cols, monkeypatch):
+def test_per_channel_without_optimisation_steps(rows, cols, eq_override):
     # iters = 0 with one range per row: the load-pipelined kernel in its per-row form
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows * 3 + cols, device=DEV)
     W[rows // 2] = 0                                     # an all-zero row keeps scale 1
@@ -125,7 +125,7 @@ def test_per_channel_without_optimisation_steps(rows, cols, monkeypatch):
         assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
     Wb = eq_inputs.gen_matrix(rows, cols, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=rows, device=DEV)
     _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=cols, iters=0, stat_scope=eqo.STAT_MATRIX), f"per-row rtn bf16 {rows}x{cols}")
-    monkeypatch.setenv("EASYQUANT_CHANNEL_KERNEL", "128")  # the same through the kernel that optimises
+    eq_override(eqg.OVR_CHANNEL_KERNEL, 128)  # the same through the kernel that optimises
     res = _check(W, eqo.Params(bits=4, group_size=0, iters=0), f"channel kernel at T=0 {rows}x{cols}")
     assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
@@ -160,20 +160,20 @@ def test_bf16_wide_exponent_span_takes_the_binary64_evaluation(G):
 
 @pytest.mark.parametrize("rows,cols,units_per_item", [(130, 1280, 1000), (9, 22016, 0), (24, 11008, 1500), (3, 32768, 0),
                                                       (70, 8192, 2048), (64, 4096, 0), (33, 2048, 0), (5, 128, 0)])
-def test_no_optimisation_steps_kernel_row_shapes(rows, cols, units_per_item, monkeypatch):
+def test_no_optimisation_steps_kernel_row_shapes(rows, cols, units_per_item, eq_override):
     # iters = 0, group 128: the load-pipelined kernel (batches of 16, 8, 4, 2 or 1 rows, odd and
     # even numbers of batches per work item, a ragged last batch)
     if units_per_item:
-        monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", str(units_per_item))
+        eq_override(eqg.OVR_UNITS_PER_ITEM, units_per_item)
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows + 3 * cols, device=DEV)
     for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
         res = _check(W, eqo.Params(bits=bits, group_size=128, mode=mode, iters=0), f"rtn kernel {rows}x{cols}")
         assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
     # the same with the other workgroup sizes: four wavefronts for short rows, eight for long ones
-    monkeypatch.setenv("EASYQUANT_RTN_THREADS", "256" if cols <= 8192 else "512")
+    eq_override(eqg.OVR_RTN_THREADS, 256 if cols <= 8192 else 512)
     res = _check(W, eqo.Params(bits=4, group_size=128, iters=0), f"rtn kernel, other workgroup size, {rows}x{cols}")
     assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
-    monkeypatch.delenv("EASYQUANT_RTN_THREADS")
+    eq_override(eqg.OVR_RTN_THREADS, 0)
     Wb = eq_inputs.gen_matrix(rows, cols, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=rows, device=DEV)
     _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=0, n_sigma=2.0), f"rtn kernel bf16 {rows}x{cols}")
 
@@ -239,7 +239,7 @@ def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
 
 
 @pytest.mark.parametrize("G", [128, 64, 1024])
-def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(G, monkeypatch):
+def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(G, eq_override):
     """Groups of 64 and up with 4-bit codes: the per-group tables hold exactly the weights the plain
     arithmetic computes and the additions come in the same order, so y is bit-identical."""
     rows, cols = 21, 11008 + 256
@@ -248,8 +248,8 @@ def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(G, monkeypatch):
     outs, _ = run_gpu([W], p)
     x = torch.randn(cols, device=DEV).to(torch.float16)
     ys = []
-    for tables in ("1", "0"):
-        monkeypatch.setenv("EASYQUANT_MATVEC_TABLES", tables)
+    for arithmetic in (0, 1):
+        eq_override(eqg.OVR_MATVEC_ARITHMETIC, arithmetic)
         y = torch.empty(rows, dtype=torch.float32, device=DEV)
         eqg.eq_dequant_matvec(outs[0], rows, cols, to_gpu_params(p), x, y)
         torch.cuda.synchronize()
@@ -547,6 +547,14 @@ def test_argument_validation_on_device_pointers():
     with pytest.raises(eqg.EasyQuantError) as e:
         eqg.eq_quantize_matrix(W.view(-1)[4:4 + 7 * 256].view(7, 256), gp, out, ws)
     assert e.value.code == -4
+    # code words are stored 128 bits at a time: codes must be 16-byte aligned in every quantize call
+    for g in (128, 0):
+        gq = eqg.Params(group_size=g)
+        o2 = eqg.alloc_outputs(9, 256, gq, 64, DEV)
+        o2.codes = o2.codes.view(-1)[1:1 + 8 * o2.codes.shape[1]].view(8, -1)
+        with pytest.raises(eqg.EasyQuantError) as e:
+            eqg.eq_quantize_matrix(W, gq, o2, ws)
+        assert e.value.code == -4
 
 
 def test_config2_llama7b_attention_projection():

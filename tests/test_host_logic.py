@@ -33,7 +33,7 @@ def test_division_by_known_reciprocal_is_the_ieee_quotient(lib):
     for b in divisors:
         for a in np.concatenate([rng.standard_normal(40) * 10.0 ** rng.integers(-12, 6, 40), [0.0, -0.0, 1e-300, 3e280]]):
             a = float(a)
-            got = lib.eq_diag_div_f64(a, b)
+            got = lib.eq_test_div_f64(a, b)
             want = a / b
             assert got == want or (math.isnan(got) and math.isnan(want)), (a, b, got, want)
             if a != 0 and abs(a) < 1e200 and abs(a) > 1e-200:
@@ -43,19 +43,41 @@ def test_division_by_known_reciprocal_is_the_ieee_quotient(lib):
     for b in (7.0, 15.0, 3.0, 1.0, 127.0, 255.0):
         a32 = (rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 3, 20000)).astype(np.float32)
         for a in a32[:3000]:
-            got = lib.eq_diag_div_f32(ctypes.c_float(float(a)), ctypes.c_float(b))
+            got = lib.eq_test_div_f32(ctypes.c_float(float(a)), ctypes.c_float(b))
             assert np.float32(got) == np.float32(a) / np.float32(b), (a, b)
 
 
-def test_work_split_env_override_does_not_change_workspace_contract(lib, monkeypatch):
+def test_work_split_override_does_not_change_workspace_contract(lib):
     import paper_2403_02775_amd as eqg
     p = eqg.Params(group_size=128)
     a = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
-    monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", "100000")
-    b = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
-    monkeypatch.setenv("EASYQUANT_UNITS_PER_ITEM", "256")
-    c = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
+    with eqg.override(eqg.OVR_UNITS_PER_ITEM, 100000):
+        b = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
+    with eqg.override(eqg.OVR_UNITS_PER_ITEM, 256):
+        c = eqg.eq_workspace_bytes([4096], [4096], [100000], p)
     assert a > 0 and b > 0 and c >= a
+    assert eqg.eq_workspace_bytes([4096], [4096], [100000], p) == a      # the override is gone
+
+
+def test_plan_items_cover_every_row_exactly_once(lib):
+    """Host side of the batch call: the work items of the launch plan tile the rows of every
+    matrix that a lane kernel serves, in order, without gaps or overlaps."""
+    import paper_2403_02775_amd as eqg
+    shapes = [(8192, 8192), (22016, 8192), (8192, 22016), (100, 4096), (7, 1024), (0, 4096), (33, 256)]
+    rows, cols = [s[0] for s in shapes], [s[1] for s in shapes]
+    for p in (eqg.Params(group_size=128, iters=100), eqg.Params(group_size=128, iters=0), eqg.Params(group_size=0, iters=10)):
+        items = eqg.plan_items(rows, cols, [1000] * len(shapes), p)
+        covered = {}
+        launches = {}
+        for m, r0, nr, launch in items:
+            assert nr > 0 and r0 == covered.get(m, 0), (m, r0, nr)
+            covered[m] = r0 + nr
+            launches.setdefault(launch, set()).add(cols[m])
+        for launch, cs in launches.items():
+            assert len(cs) == 1                                        # one row length per launch
+        for m, (r, c) in enumerate(shapes):
+            served_by_lanes = r > 0 and ((p.group_size == 128) or (c % 128 == 0 and 2048 <= c <= 32768))
+            assert covered.get(m, 0) == (r if served_by_lanes else 0), (m, r, c, p.group_size)
 
 
 def test_benchmark_refuses_more_than_one_gpu():
