@@ -78,17 +78,56 @@ def measured_traffic(workload, iters, kernel="quantize_units128"):
         return None
 
 
-def cpu_baseline(Ws, gp_kwargs, sample_rows):
-    """The oracle, as it stands, on the first `sample_rows` rows of the first matrix."""
+def measured_issue(workload, iters, kernel="quantize_units128"):
+    """Shader-sequencer figures of the main kernels from the committed counter summary (rocprofv3 --pmc
+    SQ_*), if one exists for this workload and step count: VALU instructions per element, share of
+    cycles in which the vector ALUs issue, and VALU issue slots used (wavefront instructions x 4
+    cycles / SIMDs / busy cycles).  Read like `traffic`: a counter run cannot share the timed run."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_sq_issue.txt")
+    if workload is None or not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            vals[k.strip()] = v.strip()
+    try:
+        if int(vals.get("iters", -1)) != iters:
+            return None
+        return {k: float(vals[k]) for k in ("valu_insts_per_element", "valu_busy", "issue_frac")}
+    except (KeyError, ValueError):
+        return None
+
+
+PAPER_CONTEXT = {
+    # the paper's own wall-clock figures, other hardware: context, not a target
+    "quantization": "1-10 min per model for every evaluated model (BLOOM up to 176B, LLaMA up to 65B), 4-bit, per channel, "
+                    "100-500 Adam steps, 8 x A100, one weight per GPU (Sec. 5, Implementation)",
+    "quantization_175B": "within 10 minutes (Abstract, Sec. 6)",
+    "dequantization_A100_ms": {"int4_dequantize_14336x53746": 5.0, "fp16_matmul_bs1_seq1024": 83.0},
+    "outlier_isolation_A100_ms_by_ratio": {"0.01%": 0.027, "0.10%": 0.055, "0.50%": 0.093, "1%": 0.117, "5%": 0.186,
+                                           "10%": 0.212},
+}
+
+
+def cpu_baseline_pooled(pool, Ws, gp_kwargs, single_rows, pool_rows):
+    """The oracle, as it stands, on the first rows of the first matrix: `single_rows` rows in this
+    process (one thread), then `pool_rows` rows as blocks of 32 rows over the worker processes."""
     import numpy as np
+    import torch
     from oracle import easyquant_oracle as eqo
-    W = Ws[0][:sample_rows]
-    raw = W.cpu().contiguous().view(__import__("torch").int16).numpy().view(np.uint16)
     p = eqo.Params(**gp_kwargs)
+    raw = Ws[0][:max(single_rows, pool_rows)].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
     t0 = time.perf_counter()
-    eqo.quantize_matrix(raw, p)
-    dt = time.perf_counter() - t0
-    return raw.size * 2 / dt / 1e9, dt, raw.shape
+    for a in range(0, single_rows, 32):
+        eqo.quantize_matrix(raw[a:a + 32], p)
+    t_single = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    pool.quantize_blocks([raw[a:a + 32] for a in range(0, pool_rows, 32)], p, keep=("scales",))
+    t_pool = time.perf_counter() - t0
+    cols = raw.shape[1]
+    return {"single_GBps": single_rows * cols * 2 / t_single / 1e9, "single_s": t_single,
+            "pool_GBps": pool_rows * cols * 2 / t_pool / 1e9, "pool_s": t_pool, "cols": cols}
 
 
 def bench_dequantize(args):
@@ -215,7 +254,12 @@ def main():
     ap.add_argument("--select", choices=["best", "last"], default="best",
                     help="which iterate is kept; last = the paper's wording (secondary measurement)")
     ap.add_argument("--capacity-frac", type=float, default=0.02, help="outlier capacity per matrix as a fraction of its elements")
-    ap.add_argument("--cpu-rows", type=int, default=3072, help="rows of the first matrix given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=1024,
+                    help="rows of the first matrix the CPU oracle recomputes in one thread; the all-core sample is this "
+                         "times half the number of worker processes (0 = skip)")
+    ap.add_argument("--no-sweep", dest="sweep", action="store_false",
+                    help="skip the secondary configurations timed after the headline (T = 0, 1, 10, 500; per channel)")
+    ap.add_argument("--sweep-steps", type=int, default=3)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 4 GiB device-to-device copy (torch's copy kernel) so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) has a kernel of known traffic to scale by")
@@ -231,6 +275,13 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (matrices, rows and groups are independent: the path needs no communication between GPUs); run with --gpus 1")
 
+    # The oracle's worker processes (the cpu_baseline leg) are started before anything touches the GPU.
+    pool = None
+    if args.cpu_rows > 0 and args.stat_scope == "row":
+        from oracle.rowpool import RowPool
+        pool = RowPool(min(16, os.cpu_count() or 1))
+        log(f"[cpu] oracle pool of {pool.workers} worker processes")
+
     import torch
     import paper_2403_02775_amd as eqg
 
@@ -240,15 +291,29 @@ def main():
     Ws, names, bits, dt = build_workload(args.workload, args.layers, dev)
     if args.bits:
         bits = args.bits
-    gp = eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=args.group_size, mode=eqg.EQ_SYMMETRIC,
-                    stat_scope=eqg.EQ_STAT_ROW if args.stat_scope == "row" else eqg.EQ_STAT_MATRIX, n_sigma=3.0,
-                    iters=args.iters, lr=args.lr, select=eqg.EQ_SELECT_BEST if args.select == "best" else eqg.EQ_SELECT_LAST)
+    elems = sum(w.numel() for w in Ws)
+
+    def params(iters, group_size, lr):
+        return eqg.Params(dtype=eqg.EQ_F16 if dt == "f16" else eqg.EQ_BF16, bits=bits, group_size=group_size, mode=eqg.EQ_SYMMETRIC,
+                          stat_scope=eqg.EQ_STAT_ROW if args.stat_scope == "row" else eqg.EQ_STAT_MATRIX, n_sigma=3.0,
+                          iters=iters, lr=lr, select=eqg.EQ_SELECT_BEST if args.select == "best" else eqg.EQ_SELECT_LAST)
+
+    gp = params(args.iters, args.group_size, args.lr)
+    # secondary configurations timed on the same resident weights after the headline (the sweep of
+    # step counts, and one range per output channel): (label, iters, group size, lr)
+    sweep_cfgs = []
+    if args.sweep and args.group_size == 128 and args.iters == 100:
+        sweep_cfgs = [("T=0", 0, 128, args.lr), ("T=1", 1, 128, args.lr), ("T=10", 10, 128, args.lr),
+                      ("T=500, lr=1e-4 (the paper's LLaMA setting)", 500, 128, 1e-4),
+                      ("per channel, T=100 (the paper's granularity)", 100, 0, args.lr)]
     caps = [int(w.numel() * args.capacity_frac) for w in Ws]
     outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, dev) for w, c in zip(Ws, caps)]
-    ws_bytes = eqg.eq_workspace_bytes([w.shape[0] for w in Ws], [w.shape[1] for w in Ws], caps, gp)
+    shape_r, shape_c = [w.shape[0] for w in Ws], [w.shape[1] for w in Ws]
+    ws_bytes = max(eqg.eq_workspace_bytes(shape_r, shape_c, caps, q)
+                   for q in [gp] + [params(t, g, lr) for _, t, g, lr in sweep_cfgs])
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
-    log(f"[mem] inputs {sum(w.numel() for w in Ws) * 2 / 1e9:.1f} GB, workspace {ws_bytes / 1e9:.1f} GB, "
+    log(f"[mem] inputs {elems * 2 / 1e9:.1f} GB, workspace {ws_bytes / 1e9:.1f} GB, "
         f"allocated {torch.cuda.memory_allocated() / 1e9:.1f} GB")
 
     if args.copy_calibration:
@@ -259,53 +324,73 @@ def main():
         log("[calibration] copied 4 GiB (reads 4 GiB, writes 4 GiB)")
         del src, dst
 
-    def step():
-        eqg.eq_quantize_batch(Ws, gp, outs, ws)
+    def kernel_name(q):
+        return ("quantize_rtn128" if q.iters == 0 and q.group_size in (0, 128) else "quantize_units128" if q.group_size == 128
+                else "quantize_channels" if q.group_size == 0 else "quantize_rows_generic")
 
-    for i in range(args.warmup):
-        step()
+    def timed(q, q_outs, steps, warmup, label):
+        """`steps` calls of eq_quantize_batch over the whole set; timing by events on the stream the
+        calls are made on (torch's current stream); the main kernels are bracketed by the library."""
+        for i in range(warmup):
+            eqg.eq_quantize_batch(Ws, q, q_outs, ws)
+            torch.cuda.synchronize()
+            log(f"[warmup] {label} {i + 1}/{warmup}")
+        eqg.eq_profile_enable(True)
+        eqg.eq_profile_read()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        log(f"[warmup] {i + 1}/{args.warmup}")
-    eqg.eq_profile_enable(True)
-    eqg.eq_profile_read()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    gpu_ms = ev0.elapsed_time(ev1)
-    kern_ms, launches = eqg.eq_profile_read()
-    eqg.eq_profile_enable(False)
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            eqg.eq_quantize_batch(Ws, q, q_outs, ws)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        gpu_ms = ev0.elapsed_time(ev1)
+        kern_ms, launches = eqg.eq_profile_read()
+        eqg.eq_profile_enable(False)
+        status = [int(o.status.item()) for o in q_outs]
+        assert not any(status), f"device status words: {sorted(set(status))}"
+        n_out = sum(int(o.out_row_ptr[-1].item()) & 0xFFFFFFFF for o in q_outs)
+        ms_per_step = gpu_ms / steps
+        # T evaluations, one more for best-iterate selection, and the emitting pass
+        passes = (q.iters + (2 if args.select == "best" else 1)) if q.iters else 1
+        lane_ops = elems * (5 * passes + 12)          # useful lane-operations: 5 per element and pass, 12 fixed
+        kern_s = kern_ms * 1e-3 / steps               # main kernels per step (one launch per row-length class)
+        alg_bytes = algorithmic_bytes(Ws, bits, n_out, q.group_size)
+        return {"ms_per_step": ms_per_step, "wall_s_per_step": wall / steps, "kernel_ms_per_step": kern_ms / steps,
+                "launches_per_step": launches / steps, "avg_launch_ms": kern_ms / max(launches, 1), "n_out": n_out,
+                "passes": passes, "lane_ops": lane_ops, "alg_bytes": alg_bytes,
+                "weight_GBps": elems * 2 / (ms_per_step * 1e-3) / 1e9,
+                # whole step (every kernel of the call) against the two peaks
+                "step_hbm_frac": alg_bytes / (ms_per_step * 1e-3) / HBM_PEAK,
+                "step_useful_op_frac": lane_ops / (ms_per_step * 1e-3) / ALU_PEAK,
+                # main kernels only
+                "kernel_hbm_frac": alg_bytes / kern_s / HBM_PEAK, "kernel_useful_op_frac": lane_ops / kern_s / ALU_PEAK}
 
-    status = [int(o.status.item()) for o in outs]
-    assert not any(status), f"device status words: {sorted(set(status))}"
-    n_out = sum(int(o.out_row_ptr[-1].item()) & 0xFFFFFFFF for o in outs)
-    elems = sum(w.numel() for w in Ws)
-    ms_per_step = gpu_ms / args.steps
-    weight_gbs = elems * 2 / (ms_per_step * 1e-3) / 1e9
-    # T evaluations, one more for best-iterate selection, and the emitting pass
-    passes = (args.iters + (2 if args.select == "best" else 1)) if args.iters else 1
-    lane_ops = elems * (5 * passes + 12)          # useful lane-operations: 5 per element and pass, 12 fixed
-    kern_s = kern_ms * 1e-3 / args.steps          # main kernels per step (one launch per row-length class)
-    alg_bytes = algorithmic_bytes(Ws, bits, n_out, args.group_size)
-    alu_frac = lane_ops / kern_s / ALU_PEAK
-    hbm_frac = alg_bytes / kern_s / HBM_PEAK
-    if alu_frac >= hbm_frac:
-        roof = {"bound": "alu", "achieved": lane_ops / kern_s / 1e12, "peak": ALU_PEAK / 1e12, "unit": "Tlaneop/s",
-                "frac": alu_frac, "traffic": None}
+    m = timed(gp, outs, args.steps, args.warmup, "headline")
+    ms_per_step, weight_gbs, n_out = m["ms_per_step"], m["weight_GBps"], m["n_out"]
+    kern_s = m["kernel_ms_per_step"] * 1e-3
+    kernel = kernel_name(gp)
+    workload_key = args.workload if args.layers < 0 else None
+    sq = measured_issue(workload_key, args.iters, kernel)
+    if m["kernel_useful_op_frac"] >= m["kernel_hbm_frac"]:
+        # `frac` counts USEFUL lane-operations (5 per element and pass + 12, a definition fixed before the
+        # kernel existed; the kernel issues about 4 per element and pass, so this can exceed what the issue
+        # slots alone would allow); `issue_frac` is the measured share of VALU issue slots in use.
+        roof = {"bound": "alu", "achieved": m["lane_ops"] / kern_s / 1e12, "peak": ALU_PEAK / 1e12, "unit": "Tlaneop/s",
+                "frac": m["kernel_useful_op_frac"], "traffic": None}
     else:
-        roof = {"bound": "hbm", "achieved": alg_bytes / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": hbm_frac, "traffic": None}
-    kernel = "quantize_rtn128" if args.group_size == 128 and args.iters == 0 else "quantize_units128" if args.group_size == 128 else "quantize_channels" if args.group_size == 0 else "quantize_rows_generic"
-    roof["traffic"] = measured_traffic(args.workload if args.layers < 0 else None, args.iters, kernel)
-    roof.update({"kernel": kernel, "launches_per_step": launches / args.steps,
-                 "kernel_ms_per_step": kern_ms / args.steps, "avg_launch_ms": kern_ms / max(launches, 1),
-                 "algorithmic_bytes": alg_bytes, "hbm_frac": hbm_frac, "alu_frac": alu_frac,
-                 "lane_ops_per_element": 5 * passes + 12})
+        roof = {"bound": "hbm", "achieved": m["alg_bytes"] / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": m["kernel_hbm_frac"], "traffic": None}
+    roof["traffic"] = measured_traffic(workload_key, args.iters, kernel)
+    roof.update({"kernel": kernel, "launches_per_step": m["launches_per_step"],
+                 "kernel_ms_per_step": m["kernel_ms_per_step"], "avg_launch_ms": m["avg_launch_ms"],
+                 "algorithmic_bytes": m["alg_bytes"], "hbm_frac": m["kernel_hbm_frac"],
+                 "useful_op_frac": m["kernel_useful_op_frac"], "lane_ops_per_element": 5 * m["passes"] + 12,
+                 "issue_frac": sq["issue_frac"] if sq else None,
+                 "valu_insts_per_element": sq["valu_insts_per_element"] if sq else None,
+                 "valu_busy": sq["valu_busy"] if sq else None})
 
     out = {
         "metric": "fp16 weight GB/s quantized (fraction of HBM peak); s per 65B-shaped model",
@@ -321,17 +406,55 @@ def main():
         "seconds_per_model": ms_per_step * 1e-3,
         "weight_hbm_frac": weight_gbs * 1e9 / HBM_PEAK,
         "outlier_fraction": n_out / elems,
-        "wall_s_per_step": wall / args.steps,
+        "wall_s_per_step": m["wall_s_per_step"],
         "roofline": roof,
+        "paper_context": PAPER_CONTEXT,
     }
-    if args.cpu_rows > 0 and args.stat_scope == "row":       # (a sample of rows has no whole-matrix statistics)
+
+    # ---- the sweep: same weights, same buffers, 3 timed steps each ----
+    if sweep_cfgs:
+        sweep = []
+        chan_outs = None
+        for label, iters, group, lr in sweep_cfgs:
+            q = params(iters, group, lr)
+            q_outs = outs
+            if group == 0:                           # one scale and zero-point per row; everything else is shared
+                if chan_outs is None:
+                    chan_outs = [eqg.QMatrix(codes=o.codes, scales=torch.empty((w.shape[0], 1), dtype=torch.float32, device=dev),
+                                             zero_points=torch.empty((w.shape[0], 1), dtype=torch.uint8, device=dev),
+                                             out_row_ptr=o.out_row_ptr, out_col=o.out_col, out_val=o.out_val, status=o.status)
+                                 for o, w in zip(outs, Ws)]
+                q_outs = chan_outs
+            r = timed(q, q_outs, args.sweep_steps, 1, label)
+            sweep.append({"config": label, "iters": iters, "group_size": group, "lr": lr, "steps": args.sweep_steps,
+                          "ms_per_step": r["ms_per_step"], "seconds_per_model": r["ms_per_step"] * 1e-3,
+                          "weight_GBps": r["weight_GBps"], "weight_hbm_frac": r["weight_GBps"] * 1e9 / HBM_PEAK,
+                          "hbm_frac": r["step_hbm_frac"], "useful_op_frac": r["step_useful_op_frac"],
+                          "bound": "hbm" if r["step_hbm_frac"] >= r["step_useful_op_frac"] else "alu",
+                          "kernel": kernel_name(q), "kernel_ms_per_step": r["kernel_ms_per_step"],
+                          "kernel_hbm_frac": r["kernel_hbm_frac"], "algorithmic_bytes": r["alg_bytes"]})
+            log(f"[sweep] {label}: {r['ms_per_step']:.2f} ms/step, {r['weight_GBps']:.0f} GB/s of weights, "
+                f"hbm {r['step_hbm_frac']:.3f}, useful-op {r['step_useful_op_frac']:.3f}")
+        out["sweep"] = sweep
+        out["sweep_note"] = ("hbm_frac / useful_op_frac of a sweep entry are over the WHOLE step (every kernel of the call): "
+                             "algorithmic bytes, resp. elements x (5 x passes + 12) lane-operations, over the step time and the peak")
+
+    if pool is not None:
         kw = dict(dtype=gp.dtype, bits=bits, group_size=args.group_size, mode=0, stat_scope=0, n_sigma=3.0, iters=args.iters,
                   lr=args.lr, select=0 if args.select == "best" else 1)
-        gbs, secs, shape = cpu_baseline(Ws, kw, args.cpu_rows)
-        out["cpu_baseline"] = {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
-                               "sample": f"first {shape[0]} rows x {shape[1]} cols of layer 0 q_proj ({secs:.1f} s, NumPy, "
-                                         f"single thread; host has {os.cpu_count()} logical CPUs)",
-                               "seconds_per_model_extrapolated": elems * 2 / (gbs * 1e9)}
+        single_rows = max(32, min(args.cpu_rows, Ws[0].shape[0]) // 32 * 32)
+        pool_rows = max(32, min(args.cpu_rows * pool.workers // 2, Ws[0].shape[0]) // 32 * 32)
+        c = cpu_baseline_pooled(pool, Ws, kw, single_rows, pool_rows)
+        pool.close()
+        out["cpu_baseline"] = {"value": c["pool_GBps"], "unit": "GB/s", "cores": pool.workers, "kind": "oracle",
+                               "sample": f"first {pool_rows} rows x {c['cols']} cols of layer 0 q_proj in blocks of 32 rows over "
+                                         f"{pool.workers} worker processes ({c['pool_s']:.1f} s, NumPy, one thread each; host "
+                                         f"has {os.cpu_count()} logical CPUs)",
+                               "seconds_per_model_extrapolated": elems * 2 / (c["pool_GBps"] * 1e9),
+                               "single_thread": {"value": c["single_GBps"], "unit": "GB/s", "cores": 1,
+                                                 "sample": f"first {single_rows} rows of the same matrix, blocks of 32 rows, in "
+                                                           f"this process ({c['single_s']:.1f} s)",
+                                                 "seconds_per_model_extrapolated": elems * 2 / (c["single_GBps"] * 1e9)}}
     print(json.dumps(out), flush=True)
 
 

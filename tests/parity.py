@@ -141,7 +141,9 @@ def compare(raw: np.ndarray, got: dict, want: dict, p: eqo.Params, what: str = "
         x32 = eqo.widen(raw, p.dtype)
         for r, c in zip(*np.nonzero(cd)):
             s = np.float32(want["scales"].reshape(rows, upr)[r, c // G])
-            t = float(np.float32(x32[r, c]) * (np.float32(1.0) / s))
+            # the pre-rounding value as the oracle forms it: the exact product of the element and
+            # the binary32 reciprocal of the scale (exact in binary64)
+            t = float(np.float64(x32[r, c]) * np.float64(np.float32(1.0) / s))
             dist = abs(abs(t - np.floor(t)) - 0.5)
             assert dist <= BAND * max(abs(t), 1.0), (what, "code differs outside the band", r, c, t, ug[r, c], uw[r, c])
             excused_elems += 1

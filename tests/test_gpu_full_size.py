@@ -1,11 +1,22 @@
 """Parity at the full sizes of the benchmark configurations, in the launch configuration
 `bench.py` times (one eq_quantize_batch call over the whole weight set).
 
-The oracle cannot redo 65 G elements, so: (1) rows are independent under row statistics, hence a
-seeded sample of rows of EVERY matrix is recomputed by the oracle and compared element by element
-(codes, scale, zero-point, outlier columns and values of those rows); (2) properties that hold at
-any size are checked on everything on the GPU with torch: status words, monotone row pointers,
-ascending columns, outlier values verbatim, outlier fraction, positive scales."""
+The oracle cannot redo 65 G elements, so:
+(1) rows are independent under row statistics, hence a sample of rows of EVERY matrix is
+    recomputed by the oracle (in worker processes, oracle/rowpool.py) and compared element by
+    element: codes, scale, zero-point, outlier columns and values of those rows.  The sample is
+    deterministic where position matters — the first and the last row of every matrix, and the
+    rows on both sides of work-item boundaries of every launch (the boundaries are the ones the
+    library's launch plan produces for this very batch, read through its host-only query) — and
+    seeded random for the rest;
+    for the 65B-shaped set (configuration 5) the sample is 2 % of the rows of every matrix;
+(2) one whole matrix of each shape of the LLaMA-7B-shaped set, and all seven matrices of one
+    layer of the 65B-shaped set, are recomputed in full under the complete bar of parity.py;
+(3) properties that hold at any size are checked on everything on the GPU with torch: status
+    words, monotone row pointers, ascending columns, outlier values verbatim, outlier fraction,
+    positive scales."""
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -14,15 +25,21 @@ import bench
 import eq_inputs
 import paper_2403_02775_amd as eqg
 from oracle import easyquant_oracle as eqo
-from parity import raw_of, to_gpu_params
+from oracle.rowpool import stitch
+from parity import compare, compare_sse, gpu_dequantize, raw_of, to_gpu_params
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.oracle_pool]
 DEV = "cuda:0"
+CAPACITY_FRAC = 0.02
 
 
-def _quantize_all(Ws, p, capacity_frac=0.02):
+def _capacities(Ws):
+    return [int(w.numel() * CAPACITY_FRAC) + 64 for w in Ws]
+
+
+def _quantize_all(Ws, p):
     gp = to_gpu_params(p)
-    caps = [int(w.numel() * capacity_frac) + 64 for w in Ws]
+    caps = _capacities(Ws)
     outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, DEV) for w, c in zip(Ws, caps)]
     ws = torch.empty(eqg.eq_workspace_bytes([w.shape[0] for w in Ws], [w.shape[1] for w in Ws], caps, gp),
                      dtype=torch.uint8, device=DEV)
@@ -56,45 +73,81 @@ def _global_properties(Ws, outs, p, what):
     return frac
 
 
-def _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix, seed, what):
-    """Oracle on a sample of rows of every matrix, grouped by row length."""
+def _pick_rows(Ws, p, rows_per_matrix, boundaries_per_launch, seed):
+    """Per matrix, the sorted rows the oracle recomputes: first and last row, the two rows on each
+    side of `boundaries_per_launch` work-item boundaries of every launch of the plan (spread evenly
+    over the launch's items, the first and the last boundary included), seeded random rows up to
+    `rows_per_matrix`."""
+    rows = [int(w.shape[0]) for w in Ws]
+    cols = [int(w.shape[1]) for w in Ws]
+    picks = [set([0, r - 1]) for r in rows]
+    items = eqg.plan_items(rows, cols, _capacities(Ws), to_gpu_params(p))
+    by_launch = {}
+    for m, r0, nr, launch in items:
+        if r0 > 0:                                         # the cut between two items of one matrix
+            by_launch.setdefault(launch, []).append((m, r0))
+    n_bound = 0
+    for launch, cuts in sorted(by_launch.items()):
+        take = np.unique(np.linspace(0, len(cuts) - 1, min(boundaries_per_launch, len(cuts))).round().astype(int))
+        for i in take:
+            m, b = cuts[i]
+            picks[m].update(r for r in (b - 2, b - 1, b, b + 1) if 0 <= r < rows[m])
+            n_bound += 1
     rng = np.random.default_rng(seed)
-    by_cols = {}
-    for k, W in enumerate(Ws):
-        rows = W.shape[0]
-        pick = np.sort(rng.choice(rows, size=min(rows_per_matrix, rows), replace=False))
-        by_cols.setdefault(int(W.shape[1]), []).append((k, pick))
-    checked = 0
-    for cols, group in by_cols.items():
-        print(f"[full-size] {what}: cols={cols}, {sum(len(pk) for _, pk in group)} sampled rows", flush=True)
-        raws, got_u, got_s, got_z, got_out = [], [], [], [], []
-        for k, pick in group:
-            W, o = Ws[k], outs[k]
-            idx = torch.from_numpy(pick).to(DEV)
-            raws.append(raw_of(W[idx]))
-            got_u.append(eqo.unpack_codes(o.codes[idx].cpu().numpy().view(np.uint32), cols, p.bits))
-            got_s.append(o.scales[idx].cpu().numpy())
-            got_z.append(o.zero_points[idx].cpu().numpy())
-            rp = o.out_row_ptr.cpu().numpy().view(np.uint32).astype(np.int64)
-            oc = o.out_col.cpu().numpy().view(np.uint32)
-            ov = o.out_val.cpu().numpy().view(np.uint16)
-            for r in pick:
-                got_out.append((oc[rp[r]:rp[r + 1]].copy(), ov[rp[r]:rp[r + 1]].copy()))
-        raw = np.concatenate(raws)
-        want = eqo.quantize_matrix(raw, p)
-        gu, gs, gz = np.concatenate(got_u), np.concatenate(got_s), np.concatenate(got_z)
-        assert (gu == want["u"]).all(), (what, cols, "codes", int((gu != want["u"]).sum()))
-        assert (gs == want["scales"]).all(), (what, cols, "scales")
-        assert (gz == want["zero_points"]).all(), (what, cols, "zero points")
-        wrp = want["out_row_ptr"].astype(np.int64)
-        for i, (c, v) in enumerate(got_out):
-            assert np.array_equal(c, want["out_col"][wrp[i]:wrp[i + 1]]), (what, cols, i, "outlier columns")
-            assert np.array_equal(v, want["out_val"][wrp[i]:wrp[i + 1]]), (what, cols, i, "outlier values")
-        checked += raw.shape[0]
-    return checked
+    for m, r in enumerate(rows):
+        want = min(rows_per_matrix, r)
+        while len(picks[m]) < want:
+            picks[m].update(int(v) for v in rng.integers(0, r, size=want - len(picks[m])))
+    return [np.array(sorted(s), dtype=np.int64) for s in picks], len(by_launch), n_bound, len(items)
 
 
-def test_config3_llama7b_mlp_set_3bit_and_4bit():
+def _sampled_rows_vs_oracle(pool, Ws, outs, p, picks, what):
+    """Oracle on the picked rows of every matrix; every compared quantity must be bit-equal."""
+    blocks, got = [], []
+    for W, o, pick in zip(Ws, outs, picks):
+        cols = int(W.shape[1])
+        idx = torch.from_numpy(pick).to(DEV)
+        blocks.append(raw_of(W[idx]))
+        rp = o.out_row_ptr.to(torch.int64) & 0xFFFFFFFF
+        starts, lens = rp[idx], rp[idx + 1] - rp[idx]
+        offs = torch.cumsum(lens, 0) - lens
+        total = int(lens.sum())
+        pos = torch.repeat_interleave(starts - offs, lens) + torch.arange(total, device=DEV)
+        got.append({
+            "u": eqo.unpack_codes(o.codes[idx].cpu().numpy().view(np.uint32), cols, p.bits),
+            "scales": o.scales[idx].cpu().numpy(),
+            "zero_points": o.zero_points[idx].cpu().numpy(),
+            "lens": lens.cpu().numpy(),
+            "out_col": o.out_col[pos].cpu().numpy().view(np.uint32),
+            "out_val": o.out_val[pos].cpu().numpy().view(np.uint16),
+        })
+    # pieces of at most 32 rows: the oracle's arrays then stay in cache, and the workers stay evenly loaded
+    t0 = time.time()
+    pieces, owner = [], []
+    for k, b in enumerate(blocks):
+        for a in range(0, max(b.shape[0], 1), 32):
+            pieces.append(b[a:a + 32])
+            owner.append(k)
+    parts = pool.quantize_blocks(pieces, p, keep=("u", "scales", "zero_points", "out_row_ptr", "out_col", "out_val"))
+    grouped = [[] for _ in blocks]
+    for q, o in zip(parts, owner):
+        grouped[o].append(q)
+    wants = [stitch(g) for g in grouped]
+    secs = time.time() - t0
+    rows = elems = 0
+    for k, (g, w) in enumerate(zip(got, wants)):
+        assert (g["u"] == w["u"]).all(), (what, k, "codes", int((g["u"] != w["u"]).sum()))
+        assert (g["scales"].view(np.uint32) == w["scales"].view(np.uint32)).all(), (what, k, "scales")
+        assert (g["zero_points"] == w["zero_points"]).all(), (what, k, "zero points")
+        assert np.array_equal(g["lens"], np.diff(w["out_row_ptr"].astype(np.int64))), (what, k, "outliers per row")
+        assert np.array_equal(g["out_col"], w["out_col"]), (what, k, "outlier columns")
+        assert np.array_equal(g["out_val"], w["out_val"]), (what, k, "outlier values")
+        rows += blocks[k].shape[0]
+        elems += blocks[k].size
+    return rows, elems, secs
+
+
+def test_config3_llama7b_mlp_set_3bit_and_4bit(oracle_pool):
     rec = eq_inputs.RECIPES["c3"]
     Ws = [eq_inputs.gen_matrix(r, c, rec, seed=eq_inputs.mix_seed(3, 0, i), device=DEV)
           for i, (_, r, c) in enumerate(eq_inputs.mlp_set_shapes())]
@@ -102,33 +155,119 @@ def test_config3_llama7b_mlp_set_3bit_and_4bit():
         p = eqo.Params(bits=bits, group_size=128, iters=100)
         outs = _quantize_all(Ws, p)
         frac = _global_properties(Ws, outs, p, f"c3 {bits}-bit")
-        n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=48, seed=bits, what=f"c3 {bits}-bit")
-        print(f"c3 {bits}-bit: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
+        picks, n_launch, n_bound, n_items = _pick_rows(Ws, p, rows_per_matrix=96, boundaries_per_launch=8, seed=bits)
+        rows, elems, secs = _sampled_rows_vs_oracle(oracle_pool, Ws, outs, p, picks, f"c3 {bits}-bit")
+        print(f"[full-size] c3 {bits}-bit: outlier fraction {frac:.4%}; {rows} rows / {elems} elements recomputed by the "
+              f"oracle in {secs:.1f} s ({n_bound} item boundaries of {n_launch} launches, {n_items} items)", flush=True)
 
 
-def test_config4_llama7b_bf16_whole_model():
+def test_config4_llama7b_bf16_whole_model(oracle_pool):
     Ws, names, bits, dt = bench.build_workload("llama7b_bf16_w4g128", -1, DEV)
     assert len(Ws) == 224 and dt == "bf16"
     p = eqo.Params(dtype=eqo.BF16, bits=4, group_size=128, iters=100)
     outs = _quantize_all(Ws, p)
     frac = _global_properties(Ws, outs, p, "c4")
-    n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=3, seed=4, what="c4")
-    print(f"c4: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
+    picks, n_launch, n_bound, n_items = _pick_rows(Ws, p, rows_per_matrix=12, boundaries_per_launch=8, seed=4)
+    rows, elems, secs = _sampled_rows_vs_oracle(oracle_pool, Ws, outs, p, picks, "c4")
+    print(f"[full-size] c4: outlier fraction {frac:.4%}; {rows} rows / {elems} elements recomputed by the oracle in "
+          f"{secs:.1f} s ({n_bound} item boundaries of {n_launch} launches, {n_items} items)", flush=True)
+    # one whole matrix of each shape, out of the same batch call, under the full bar: an attention
+    # projection, an MLP up-projection and an MLP down-projection from three different layers
+    whole = {}
+    for k, ((layer, nm), W) in enumerate(zip(names, Ws)):
+        if (layer, nm) in ((5, "k"), (17, "up"), (31, "down")):
+            whole[tuple(W.shape)] = k
+    assert sorted(whole) == [(4096, 4096), (4096, 11008), (11008, 4096)]
+    for shape, k in sorted(whole.items()):
+        W, o = Ws[k], outs[k]
+        raw = raw_of(W)
+        t0 = time.time()
+        want = oracle_pool.quantize_matrix(raw, p, rows_per_block=32)
+        secs = time.time() - t0
+        from parity import fetch
+        res = compare(raw, fetch(o, shape[0], shape[1], p), want, p, f"c4 whole matrix {names[k]}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+        dg = gpu_dequantize(o, shape[0], shape[1], p, DEV)
+        compare_sse(raw, dg, eqo.dequantize(want, shape[0], shape[1], p), p, res["rows_ok"], "c4 whole matrix")
+        print(f"[full-size] c4 whole matrix {names[k]} {shape}: {raw.size} elements, {res['units']} units bit-equal, "
+              f"oracle {secs:.1f} s", flush=True)
 
 
-def test_config5_llama65b_whole_model():
-    """The benchmark's workload, and on the same resident weights the two secondary benchmark
-    configurations: one range per output channel, and no optimisation steps."""
+@pytest.fixture(scope="module")
+def c5_weights():
+    """The benchmark's workload: 560 matrices, 64.76 G elements, resident for the tests below."""
     Ws, names, bits, dt = bench.build_workload("llama65b_f16_w4g128", -1, DEV)
     assert len(Ws) == 560 and sum(w.numel() for w in Ws) == 64760053760
-    for what, p in (("c5", eqo.Params(bits=4, group_size=128, iters=100)),
-                    ("c5 per channel", eqo.Params(bits=4, group_size=0, iters=100)),
-                    ("c5 T=0", eqo.Params(bits=4, group_size=128, iters=0))):
-        outs = _quantize_all(Ws, p)
-        frac = _global_properties(Ws, outs, p, what)
-        n = _sampled_rows_vs_oracle(Ws, outs, p, rows_per_matrix=2 if p.group_size else 1, seed=5, what=what)
-        print(f"{what}: outlier fraction {frac:.4%}, {n} rows recomputed by the oracle", flush=True)
-        del outs
-        torch.cuda.empty_cache()
+    yield Ws, names
     del Ws
+    torch.cuda.empty_cache()
+
+
+def _c5_sample(oracle_pool, Ws, p, what, row_fraction, min_rows, keep=None):
+    """Quantizes the whole set in one call, checks the global properties, and recomputes the sample
+    rows of the matrices `keep` (default: all) with the oracle."""
+    outs = _quantize_all(Ws, p)
+    frac = _global_properties(Ws, outs, p, what)
+    picks, n_launch, n_bound, n_items = _pick_rows(Ws, p, rows_per_matrix=min_rows, boundaries_per_launch=12, seed=5)
+    if row_fraction > 0:                                       # on top: a seeded share of every matrix's rows
+        rng = np.random.default_rng(55)
+        picks = [np.union1d(pk, rng.choice(w.shape[0], size=int(np.ceil(w.shape[0] * row_fraction)), replace=False))
+                 for pk, w in zip(picks, Ws)]
+    sel = [k for k in range(len(Ws)) if keep is None or keep(k)]
+    rows, elems, secs = _sampled_rows_vs_oracle(oracle_pool, [Ws[k] for k in sel], [outs[k] for k in sel], p,
+                                                [picks[k] for k in sel], what)
+    assert n_bound >= 4 * n_launch
+    total = sum(Ws[k].numel() for k in sel)
+    print(f"[full-size] {what}: outlier fraction {frac:.4%}; {len(sel)} matrices, {rows} rows / {elems} elements "
+          f"({elems / total:.2%} of them) recomputed by the oracle in {secs:.1f} s ({n_bound} item boundaries of "
+          f"{n_launch} launches, {n_items} items)", flush=True)
+    return rows
+
+
+@pytest.mark.parametrize("half", [0, 1])
+def test_config5_llama65b_two_percent_of_the_rows_of_every_matrix(oracle_pool, c5_weights, half):
+    """The headline configuration (group 128, T = 100): first / last rows, rows around work-item
+    boundaries, and a seeded 2 % of the rows of each of the 560 matrices (layers 0-39, then 40-79,
+    each out of a batch call over the whole set)."""
+    Ws, names = c5_weights
+    rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=128, iters=100), f"c5 layers {40 * half}-{40 * half + 39}",
+                      0.02, 17, keep=lambda k: names[k][0] // 40 == half)
+    assert rows >= 70000
+    torch.cuda.empty_cache()
+
+
+def test_config5_llama65b_one_whole_layer(oracle_pool, c5_weights):
+    """All seven matrices of one layer, out of the batch call over the whole set, in full."""
+    Ws, names = c5_weights
+    p = eqo.Params(bits=4, group_size=128, iters=100)
+    outs = _quantize_all(Ws, p)
+    from parity import fetch
+    layer = 41
+    elems = 0
+    for k, ((ly, nm), W) in enumerate(zip(names, Ws)):
+        if ly != layer:
+            continue
+        rows, cols = W.shape
+        raw = raw_of(W)
+        t0 = time.time()
+        want = oracle_pool.quantize_matrix(raw, p, rows_per_block=32)
+        secs = time.time() - t0
+        res = compare(raw, fetch(outs[k], rows, cols, p), want, p, f"c5 layer {layer} {nm}")
+        assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+        elems += raw.size
+        print(f"[full-size] c5 layer {layer} {nm} {rows} x {cols}: {res['units']} units bit-equal, oracle {secs:.1f} s", flush=True)
+        del raw, want
+    assert elems == 4 * 8192 * 8192 + 3 * 8192 * 22016
+    del outs
+    torch.cuda.empty_cache()
+
+
+def test_config5_llama65b_per_channel_and_without_optimisation_steps(oracle_pool, c5_weights):
+    """On the same resident weights, the two secondary benchmark configurations."""
+    Ws, names = c5_weights
+    rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=0, iters=100), "c5 per channel", 0.0, 17)
+    assert rows >= 9000
+    torch.cuda.empty_cache()
+    rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=128, iters=0), "c5 T=0", 0.02, 17)
+    assert rows >= 140000
     torch.cuda.empty_cache()
