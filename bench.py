@@ -110,6 +110,12 @@ PAPER_CONTEXT = {
 }
 
 
+def cpu_baseline_start_pool(workers):
+    """The oracle's worker processes; to be called before anything touches the GPU."""
+    from oracle.rowpool import RowPool
+    return RowPool(workers)
+
+
 def cpu_baseline_pooled(pool, Ws, gp_kwargs, single_rows, pool_rows):
     """The oracle, as it stands, on the first rows of the first matrix: `single_rows` rows in this
     process (one thread), then `pool_rows` rows as blocks of 32 rows over the worker processes."""
@@ -278,8 +284,7 @@ def main():
     # The oracle's worker processes (the cpu_baseline leg) are started before anything touches the GPU.
     pool = None
     if args.cpu_rows > 0 and args.stat_scope == "row":
-        from oracle.rowpool import RowPool
-        pool = RowPool(min(16, os.cpu_count() or 1))
+        pool = cpu_baseline_start_pool(min(16, os.cpu_count() or 1))
         log(f"[cpu] oracle pool of {pool.workers} worker processes")
 
     import torch

@@ -293,8 +293,10 @@ def set_override(which: int, value: int) -> None:
 
 
 def plan_items(rows: Sequence[int], cols: Sequence[int], capacities: Sequence[int], p: Params):
-    """The work items eq_quantize_batch would launch for these shapes: a list of
-    (matrix, first row, rows, launch index) in launch order (host only, no GPU)."""
+    """The work items eq_quantize_batch would launch for these shapes, in launch order (host only,
+    no GPU): a list of (matrix, first row, rows, stride, step, launch index).  The workgroup takes
+    rows [first, first + rows): all of them when stride == 0, else the `step` rows at first,
+    first + stride, first + 2 stride, ..."""
     n = len(rows)
     A = C.c_int64 * max(n, 1)
     cp = p.c()
@@ -302,7 +304,7 @@ def plan_items(rows: Sequence[int], cols: Sequence[int], capacities: Sequence[in
     cnt = int(lib().eq_test_plan_items(*args, None, None, 0))
     if cnt < 0:
         raise EasyQuantError(cnt, "eq_test_plan_items")
-    items = (C.c_int32 * (3 * max(cnt, 1)))()
+    items = (C.c_int32 * (5 * max(cnt, 1)))()
     launch = (C.c_int32 * max(cnt, 1))()
     lib().eq_test_plan_items(*args, items, launch, cnt)
-    return [(items[3 * i], items[3 * i + 1], items[3 * i + 2], launch[i]) for i in range(cnt)]
+    return [tuple(items[5 * i:5 * i + 5]) + (launch[i],) for i in range(cnt)]

@@ -225,7 +225,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
         lc.kind = 5;
         rpr = split == 2 ? 2 : 1;
         lc.chunks_per_thread = split;
-        lc.lds_bytes = (size_t)kChanHeader + (size_t)rpr * (size_t)c * 2;
+        lc.lds_bytes = (size_t)kChanHeader + (size_t)rpr * (size_t)c * 2 + (size_t)rpr * (size_t)c / 8;   // rows, then one mask byte per chunk
       }
       int64_t target = std::min<int64_t>(8192, std::max<int64_t>(kChanThreads, total_units / 16384));
       if (override_of(EQ_OVR_UNITS_PER_ITEM) > 0) target = override_of(EQ_OVR_UNITS_PER_ITEM);
@@ -247,10 +247,12 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
       // (per-channel rows: the same kernel with one range per row)
       lc.kind = chan_rtn ? 6 : 3;
-      // two-wavefront workgroups (four per compute unit) for rows of up to 8192: measured 4 % faster
-      // than four-wavefront ones, whose barriers hold more wavefronts; longer rows take four
-      // wavefronts (two workgroups per compute unit, 15 % faster on rows of 22016 than one of eight)
-      lc.threads = c > 8192 ? 256 : 128;
+      // longer rows take four wavefronts (two workgroups per compute unit, 15 % faster on rows of
+      // 22016 than one of eight);
+      // one-wavefront workgroups for rows of up to 8192 (a row, or a batch of short rows, per wavefront:
+      // no workgroup barrier anywhere, every wait is the wavefront's own)
+      lc.threads = c > 8192 ? 256 : 64;
+      if (override_of(EQ_OVR_RTN_THREADS) == 128 && c <= 8192) lc.threads = 128;
       // three wavefronts where the chunks per thread stay the same power of two (8 up to 12288
       // columns, 16 up to 24576): fewer idle lanes and empty load slots (11008: 90 % instead of 67 %)
       if ((c > 8192 && c <= 12288) || (c > 16384 && c <= 24576)) lc.threads = 192;
@@ -272,10 +274,17 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       rpi -= rpi % rpb;
       lc.first_item = pl.work.size();
       lc.rows_per_item = rpi;
+      lc.rows_per_step = rpb;
+      // Interleaved items: a matrix of nbatch batches gets G = ceil(nbatch / (rpi / rpb)) workgroups, and
+      // workgroup g takes batches g, g + G, g + 2 G, ...  Workgroups are dispatched in order, so at any
+      // time the chip reads one contiguous window of each of the few matrices it is working on (HBM
+      // pages and channels are used evenly), instead of a thousand streams half a megabyte apart.
       for (size_t j = k; j < e; ++j) {
         const int32_t m = order[j];
-        for (int64_t r = 0; r < rows[m]; r += rpi)
-          pl.work.push_back(WorkItem{m, (int32_t)r, (int32_t)std::min<int64_t>(rpi, rows[m] - r), 0});
+        const int64_t nbatch = (rows[m] + rpb - 1) / rpb;
+        const int64_t G = (nbatch + rpi / rpb - 1) / (rpi / rpb);
+        for (int64_t g = 0; g < G; ++g)
+          pl.work.push_back(WorkItem{m, (int32_t)(g * rpb), (int32_t)(rows[m] - g * rpb), (int32_t)(G * rpb)});
       }
       lc.n_items = pl.work.size() - lc.first_item;
       pl.classes.push_back(lc);
@@ -462,11 +471,10 @@ void release_pinned(PinnedBlock* b, hipStream_t st, bool copy_enqueued) {
 template <int DT>
 int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const std::vector<MatDesc>& h, const Plan& pl,
                const KParams& kp, hipStream_t st) {
-  int32_t max_rows = 0, max_cols = 0, gen_rows = 0, gen_cols = 0;
+  int32_t max_rows = 0, gen_rows = 0, gen_cols = 0;
   for (const MatDesc& m : h) {
     if (m.cols == 0 || m.rows == 0) continue;
     max_rows = std::max(max_rows, m.rows);
-    max_cols = std::max(max_cols, m.cols);
     if (m.path == 0) {
       gen_rows = std::max(gen_rows, m.rows);
       gen_cols = std::max(gen_cols, m.cols);
@@ -490,8 +498,9 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
     const void* fn = lk.fn;
     const LaneLaunch launch = lk.launch;
     if (!fn) return EQ_E_UNSUPPORTED;
-    if (lc.lds_bytes > 65536)
-      EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lc.lds_bytes));
+    const size_t lds_bytes = lk.lds_bytes ? lk.lds_bytes : lc.lds_bytes;
+    if (lds_bytes > 65536)
+      EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
     {
       ScopedKernelTimer tm(st);
       launch(lc, dmats, ditems, kp, st);
@@ -512,12 +521,8 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
   hipLaunchKernelGGL(scan_row_counts, dim3(n), dim3(kThreads), 0, st, dmats);
   EQ_HIP(hipGetLastError());
   if (max_rows > 0) {
-    const int rows_per_block = kWaves * kGatherRows;
-    const uint32_t wmax = (uint32_t)((max_cols + 31) / 32);
-    const size_t lds = (size_t)kWaves * 2 * wmax * sizeof(uint32_t);
-    if (lds > 65536)
-      EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gather_outliers), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(gather_outliers, dim3((max_rows + rows_per_block - 1) / rows_per_block, n), dim3(kThreads), lds, st, dmats, wmax);
+    const int rows_per_block = kWaves * kMoveRows;
+    hipLaunchKernelGGL(move_outliers, dim3((max_rows + rows_per_block - 1) / rows_per_block, n), dim3(kThreads), 0, st, dmats);
     EQ_HIP(hipGetLastError());
   }
   return EQ_OK;
@@ -624,6 +629,7 @@ struct SingleSetup {
   WorkItem* ditems;
   EQ_GLOBAL double* dtab;
   int64_t rows_per_item;
+  int64_t item_stride, rows_per_step;     // interleaved items (item_stride != 0): see make_plan
   int32_t n_items, iters;
   double b1, b2;
 };
@@ -653,12 +659,12 @@ __global__ __launch_bounds__(kThreads) void setup_single_matrix(SingleSetup s) {
   }
   const int64_t i = (int64_t)(blockIdx.x - 1) * kThreads + threadIdx.x;
   if (i < s.n_items) {
-    const int64_t r0 = i * s.rows_per_item;
+    const int64_t r0 = s.item_stride ? i * s.rows_per_step : i * s.rows_per_item;
     WorkItem it;
     it.mat = 0;
     it.row0 = (int32_t)r0;
-    it.nrows = (int32_t)(s.md.rows - r0 < s.rows_per_item ? s.md.rows - r0 : s.rows_per_item);
-    it.pad_ = 0;
+    it.nrows = (int32_t)(s.item_stride || s.md.rows - r0 < s.rows_per_item ? s.md.rows - r0 : s.rows_per_item);
+    it.stride = (int32_t)s.item_stride;
     s.ditems[i] = it;
   }
 }
@@ -711,9 +717,11 @@ int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, 
     const LaneClass& lc = pl.classes[c];
     for (size_t i = lc.first_item; i < lc.first_item + lc.n_items && (int64_t)i < max_items; ++i) {
       if (items) {
-        items[3 * i + 0] = pl.work[i].mat;
-        items[3 * i + 1] = pl.work[i].row0;
-        items[3 * i + 2] = pl.work[i].nrows;
+        items[5 * i + 0] = pl.work[i].mat;
+        items[5 * i + 1] = pl.work[i].row0;
+        items[5 * i + 2] = pl.work[i].nrows;
+        items[5 * i + 3] = pl.work[i].stride;
+        items[5 * i + 4] = (int32_t)lc.rows_per_step;
       }
       if (launch_of_item) launch_of_item[i] = (int32_t)c;
     }
@@ -831,15 +839,18 @@ int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_
   su.dtab = dev(reinterpret_cast<double*>(ws + pl.adam));
   su.n_items = (int32_t)pl.work.size();
   su.rows_per_item = pl.classes.empty() ? 0 : pl.classes[0].rows_per_item;
+  su.rows_per_step = pl.classes.empty() ? 0 : pl.classes[0].rows_per_step;
+  su.item_stride = pl.work.empty() ? 0 : pl.work[0].stride;
   su.iters = p->iters;
   su.b1 = (double)p->beta1;
   su.b2 = (double)p->beta2;
   // the kernel regenerates the plan's items from (rows, rows_per_item): make sure they are that regular
   if (pl.classes.size() > 1) return EQ_E_UNSUPPORTED;
   for (size_t i = 0; i < pl.work.size(); ++i) {
-    const int64_t r0 = (int64_t)i * su.rows_per_item;
+    const int64_t r0 = su.item_stride ? (int64_t)i * su.rows_per_step : (int64_t)i * su.rows_per_item;
     const WorkItem& w = pl.work[i];
-    if (w.mat != 0 || w.row0 != r0 || w.nrows != std::min<int64_t>(su.rows_per_item, rows - r0)) return EQ_E_UNSUPPORTED;
+    const int64_t nr = su.item_stride ? rows - r0 : std::min<int64_t>(su.rows_per_item, rows - r0);
+    if (w.mat != 0 || w.row0 != r0 || w.nrows != nr || w.stride != su.item_stride) return EQ_E_UNSUPPORTED;
   }
   hipLaunchKernelGGL(setup_single_matrix, dim3((unsigned)((su.n_items + kThreads - 1) / kThreads + 1)), dim3(kThreads), 0, st, su);
   EQ_HIP(hipGetLastError());

@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
       // opaque on purpose: with a compile-time lane count the compiler would otherwise keep every
       // thread's 16 pool addresses alive across the whole kernel, in scratch memory
       asm volatile("" : "+s"(ch0));
-      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, row0 + b, (int)min((uint32_t)RB, nr - b), pool, ch0, sc);
+      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, row0 + b, (int)min((uint32_t)RB, nr - b), pool, ch0, nullptr, sc);
     }
 
     const bool valid = my_row < nr;

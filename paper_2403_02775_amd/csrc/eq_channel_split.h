@@ -54,7 +54,8 @@ __global__ __launch_bounds__(kChanThreads) __attribute__((amdgpu_waves_per_eu(2,
     }
     if (tid == 0) cs->inexact = 0;
     // ends with a barrier, which also publishes the clears above
-    stage_rows_batch<DT, NT, RB, K, LinearLayout>(md, kp, row0, (int)nr, pool, 0u, sc);
+    // (the outlier-mask bytes of the staging, one per 16-byte chunk, sit behind the R rows)
+    stage_rows_batch<DT, NT, RB, K, LinearLayout>(md, kp, row0, (int)nr, pool, 0u, pool + (size_t)R * cols * 2u, sc);
 
     const bool valid = my_row < nr;
     RowAcc* ra = &cs->acc[valid ? my_row : 0u];

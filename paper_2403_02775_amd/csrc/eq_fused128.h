@@ -34,8 +34,12 @@ constexpr int kSlotChunks = 17;
 constexpr int kCodeOff = 128;         // packed codes are assembled in the upper half of the slot
 constexpr int kLdsHeader = 6144;      // scratch of the row staging, in front of the pool
 
+// What one workgroup does: rows [row0, row0 + nrows) of matrix `mat`, either all of them
+// (stride == 0) or, in steps of `stride` rows, only the first batch of rows of every step
+// (the kernel without optimisation steps: neighbouring workgroups then read neighbouring rows at
+// about the same time, and the whole chip moves through a matrix as one front).
 struct WorkItem {
-  int32_t mat, row0, nrows, pad_;
+  int32_t mat, row0, nrows, stride;
 };
 
 typedef short short2_t __attribute__((ext_vector_type(2)));
@@ -172,10 +176,8 @@ __device__ __forceinline__ void slot_min_max(const unsigned char* slot, float& v
 #pragma unroll
     for (int ch = 0; ch < 16; ++ch) {
       const uint4 v = *reinterpret_cast<const uint4*>(slot + ch * 16);
-      const uint32_t lo4 = pk_min_f16(pk_min_f16(v.x, v.y), pk_min_f16(v.z, v.w));
-      const uint32_t hi4 = pk_max_f16(pk_max_f16(v.x, v.y), pk_max_f16(v.z, v.w));
-      mnb = pk_min_f16(mnb, lo4);
-      mxb = pk_max_f16(mxb, hi4);
+      mnb = pk_min3_f16(pk_min3_f16(mnb, v.x, v.y), v.z, v.w);
+      mxb = pk_max3_f16(pk_max3_f16(mxb, v.x, v.y), v.z, v.w);
     }
     typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
     const half2_t mn = __builtin_bit_cast(half2_t, mnb), mx = __builtin_bit_cast(half2_t, mxb);
@@ -203,7 +205,7 @@ __device__ __forceinline__ void slot_min_max(const unsigned char* slot, float& v
 // of 8 values yields BITS whole bytes.  The zero-point rides in the rounding constant as in the
 // 4-bit form (an odd one as z + 1 so that exact ties still go to the even level; the 1 comes
 // off the gathered bytes, or off each pattern for 8 bits, where code + 1 can reach 256).
-template <int DT, int BITS>
+template <int DT, int BITS, bool NOCLAMP>
 __device__ __forceinline__ void emit_codes_bits(const KParams& kp, unsigned char* slot, float inv, int z) {
   const int zodd = z & 1;
   const uint32_t unfold = zodd ? 0x01010101u : 0u;
@@ -228,8 +230,8 @@ __device__ __forceinline__ void emit_codes_bits(const KParams& kp, unsigned char
         x0 = __uint_as_float(w[j] << 16);
         x1 = __uint_as_float(w[j] & 0xFFFF0000u);
       }
-      f[2 * j] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
-      f[2 * j + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
+      f[2 * j] = __float_as_uint(NOCLAMP ? __builtin_fmaf(x0, inv, mz) : __builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
+      f[2 * j + 1] = __float_as_uint(NOCLAMP ? __builtin_fmaf(x1, inv, mz) : __builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
       if (BITS == 8) {
         f[2 * j] -= (uint32_t)zodd;
         f[2 * j + 1] -= (uint32_t)zodd;
@@ -265,7 +267,9 @@ __device__ __forceinline__ void emit_codes_bits(const KParams& kp, unsigned char
 
 // Packed codes of the unit in `slot` at reciprocal scale `inv` (Eq. 1), assembled in the upper
 // half of the slot (the values in the lower half stay intact for 4-bit codes only).
-template <int DT>
+// NOCLAMP: the caller knows that no level can leave [l_min, l_max] (symmetric mode at the initial
+// range: |x| <= r0 gives |x / s| <= D (1 + 2^-22)), so the clamp of Eq. 1 is left out.
+template <int DT, bool NOCLAMP = false>
 __device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned char* slot, float inv, int z) {
   if (kp.bits == 4) {
     // all 16 words first (they overwrite the upper half of the values), then one store burst
@@ -293,8 +297,8 @@ __device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned c
           x0 = __uint_as_float(w[j] << 16);
           x1 = __uint_as_float(w[j] & 0xFFFF0000u);
         }
-        f[2 * j] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
-        f[2 * j + 1] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
+        f[2 * j] = __float_as_uint(NOCLAMP ? __builtin_fmaf(x0, inv, mz) : __builtin_amdgcn_fmed3f(__builtin_fmaf(x0, inv, mz), ulo, uhi));
+        f[2 * j + 1] = __float_as_uint(NOCLAMP ? __builtin_fmaf(x1, inv, mz) : __builtin_amdgcn_fmed3f(__builtin_fmaf(x1, inv, mz), ulo, uhi));
       }
       const uint32_t even = __builtin_amdgcn_perm(f[2], f[0], 0x0C0C0400u) | __builtin_amdgcn_perm(f[6], f[4], 0x04000C0Cu);
       const uint32_t odd = __builtin_amdgcn_perm(f[3], f[1], 0x0C0C0400u) | __builtin_amdgcn_perm(f[7], f[5], 0x04000C0Cu);
@@ -306,12 +310,12 @@ __device__ __forceinline__ void emit_codes_to_slot(const KParams& kp, unsigned c
     for (int wd = 0; wd < 4; ++wd) dst[wd] = make_uint4(o[4 * wd], o[4 * wd + 1], o[4 * wd + 2], o[4 * wd + 3]);
   } else {
     switch (kp.bits) {
-      case 2: emit_codes_bits<DT, 2>(kp, slot, inv, z); break;
-      case 3: emit_codes_bits<DT, 3>(kp, slot, inv, z); break;
-      case 5: emit_codes_bits<DT, 5>(kp, slot, inv, z); break;
-      case 6: emit_codes_bits<DT, 6>(kp, slot, inv, z); break;
-      case 7: emit_codes_bits<DT, 7>(kp, slot, inv, z); break;
-      default: emit_codes_bits<DT, 8>(kp, slot, inv, z); break;
+      case 2: emit_codes_bits<DT, 2, NOCLAMP>(kp, slot, inv, z); break;
+      case 3: emit_codes_bits<DT, 3, NOCLAMP>(kp, slot, inv, z); break;
+      case 5: emit_codes_bits<DT, 5, NOCLAMP>(kp, slot, inv, z); break;
+      case 6: emit_codes_bits<DT, 6, NOCLAMP>(kp, slot, inv, z); break;
+      case 7: emit_codes_bits<DT, 7, NOCLAMP>(kp, slot, inv, z); break;
+      default: emit_codes_bits<DT, 8, NOCLAMP>(kp, slot, inv, z); break;
     }
   }
 }
@@ -327,7 +331,7 @@ __device__ __forceinline__ void copy_wave_codes(const KParams& kp, const MatDesc
   EQ_GLOBAL uint32_t* gdst = md.codes + (unit_base + w_first) * (int64_t)code_words;
   for (uint32_t j = lane; j < nchunk; j += kWave) {
     const uint32_t un = j / (uint32_t)kp.bits, part = j - un * (uint32_t)kp.bits;
-    global_store128(gdst + 4 * (size_t)j, *reinterpret_cast<const uint4*>(pool + (size_t)(w_first + un) * kSlotBytes + kCodeOff + part * 16u));
+    global_store_stream128(gdst + 4 * (size_t)j, *reinterpret_cast<const uint4*>(pool + (size_t)(w_first + un) * kSlotBytes + kCodeOff + part * 16u));
   }
 }
 
@@ -433,7 +437,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         pu += upr;
         ++nb;
       }
-      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, next_row, nb, pool, pool_units * 16u, sc);
+      stage_rows_batch<DT, NT, RB, K, Padded128Layout>(md, kp, next_row, nb, pool, pool_units * 16u, nullptr, sc);
       pool_units = pu;
       next_row += nb;
     }

@@ -30,13 +30,16 @@ struct LaneClass {
   uint32_t pool_slots = 0;
   size_t lds_bytes = 0;
   size_t first_item = 0, n_items = 0;
-  int64_t rows_per_item = 0;            // every matrix of the class is cut into items of this many rows (the last one shorter)
+  int64_t rows_per_item = 0;            // every matrix of the class is cut into items of this many rows (the last one shorter),
+  int64_t item_stride = 0;              // or (item_stride != 0) into interleaved items: item g takes the batches of
+  int64_t rows_per_step = 0;            // rows_per_step rows that start at rows g * rows_per_step + k * item_stride
 };
 
 typedef void (*LaneLaunch)(const LaneClass&, const MatDesc*, const WorkItem*, const KParams&, hipStream_t);
 struct LaneKernel {
   const void* fn = nullptr;       // for hipFuncSetAttribute
   LaneLaunch launch = nullptr;
+  size_t lds_bytes = 0;           // dynamic LDS of the launch if the family sizes it itself (else LaneClass::lds_bytes)
 };
 
 template <int DT> LaneKernel pick_units_kernel(const LaneClass& lc);     // kind 1

@@ -51,105 +51,55 @@ __global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __res
   if (threadIdx.x == 0) md.out_row_ptr[md.rows] = running;
 }
 
-// Moves each row's staged run (arrival order) to its CSR position, sorted by column: the rank of
-// an entry is the number of entries of its row with a smaller column.  Columns of a row are
-// distinct, so the wavefront marks them in a bitmap of the row's columns in LDS, takes a prefix
-// sum of the population counts of its words, and an entry's rank is the prefix of its word plus
-// the marked bits below its own: linear in the row's entries and words, whatever the order they
-// arrived in.  One wavefront takes kGatherRows consecutive rows with all their loads in flight
-// together (a row's bookkeeping, then its entries: two dependent round trips to memory per row
-// otherwise); rows of more than 128 entries re-read theirs in passes of 64.
-// `wmax` = words of the widest matrix's bitmap; LDS: 2 * wmax words per wavefront.
-constexpr int kGatherRows = 4;
+// Moves each row's staged run to its CSR position.  Every producer writes a row's run in ascending
+// column order already (the batched staging per unit, the general kernel per chunk), so this is a
+// plain copy: one wavefront takes kMoveRows consecutive rows, reads their bookkeeping with one lane
+// per row, and copies the runs with all loads of a row group in flight (rows of more than 64
+// entries take further passes).
+constexpr int kMoveRows = 16;
 
-__global__ __launch_bounds__(kThreads) void gather_outliers(const MatDesc* __restrict__ mats, uint32_t wmax) {
-  extern __shared__ uint32_t gather_lds[];
+__global__ __launch_bounds__(kThreads) void move_outliers(const MatDesc* __restrict__ mats) {
   const MatDesc md = mats[blockIdx.y];
-  const int64_t row0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kGatherRows;
+  const int64_t row0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kMoveRows;
   if (row0 >= md.rows || md.cols == 0) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  uint32_t* bm = gather_lds + (threadIdx.x / kWave) * 2u * wmax;   // marked columns
-  uint32_t* pre = bm + wmax;                                       // marked columns in the words before
-  const uint32_t W = ((uint32_t)md.cols + 31u) >> 5, wpl = (W + kWave - 1) / kWave;
-  uint32_t cnt[kGatherRows], src[kGatherRows], dst[kGatherRows];
-#pragma unroll
-  for (int r = 0; r < kGatherRows; ++r) {
-    const bool in = row0 + r < md.rows;
-    cnt[r] = in ? md.row_count[row0 + r] : 0u;
-    src[r] = in ? md.row_stage[row0 + r] : 0u;
-    dst[r] = in ? md.out_row_ptr[row0 + r] : 0u;
+  // lane r: bookkeeping of row row0 + r
+  uint32_t cnt_l = 0, src_l = 0, dst_l = 0;
+  if (lane < (uint32_t)kMoveRows && row0 + lane < md.rows) {
+    cnt_l = md.row_count[row0 + lane];
+    src_l = md.row_stage[row0 + lane];
+    dst_l = md.out_row_ptr[row0 + lane];
     // a row that was not staged, or whose run does not fit the output arrays, is left out
-    if (src[r] == 0xFFFFFFFFu || (unsigned long long)dst[r] + cnt[r] > (unsigned long long)md.capacity) cnt[r] = 0;
+    if (src_l == 0xFFFFFFFFu || (unsigned long long)dst_l + cnt_l > (unsigned long long)md.capacity) cnt_l = 0;
   }
-  // rows of at most 128 entries (two per lane): all loads of all rows first
-  constexpr uint32_t kFast = 2 * kWave;
-  uint32_t col[kGatherRows][2];
-  uint16_t val[kGatherRows][2];
+  constexpr int kGroup = 4;                                // rows whose loads are in flight together
 #pragma unroll
-  for (int r = 0; r < kGatherRows; ++r) {
+  for (int g = 0; g < kMoveRows; g += kGroup) {
+    uint32_t cnt[kGroup], src[kGroup], dst[kGroup], col[kGroup];
+    uint16_t val[kGroup];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t e = lane + (uint32_t)h * kWave;
-      const bool have = cnt[r] <= kFast && e < cnt[r];
-      col[r][h] = have ? md.st_col[src[r] + e] : 0xFFFFFFFFu;
-      val[r][h] = have ? md.st_val[src[r] + e] : (uint16_t)0;
-    }
-  }
-  auto wave_sync = [] {
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-  };
-  auto rank_of = [&](uint32_t c) { return pre[c >> 5] + (uint32_t)__popc(bm[c >> 5] & ((1u << (c & 31u)) - 1u)); };
-#pragma unroll
-  for (int r = 0; r < kGatherRows; ++r) {
-    if (cnt[r] == 0) continue;                             // uniform over the wavefront
-    const bool fast = cnt[r] <= kFast;
-    for (uint32_t w = lane; w < W; w += kWave) bm[w] = 0u;
-    wave_sync();
-    if (fast) {
-      if (col[r][0] != 0xFFFFFFFFu) atomicOr(&bm[col[r][0] >> 5], 1u << (col[r][0] & 31u));
-      if (col[r][1] != 0xFFFFFFFFu) atomicOr(&bm[col[r][1] >> 5], 1u << (col[r][1] & 31u));
-    } else {
-      for (uint32_t e = lane; e < cnt[r]; e += kWave) {
-        const uint32_t c = md.st_col[src[r] + e];
-        atomicOr(&bm[c >> 5], 1u << (c & 31u));
+    for (int r = 0; r < kGroup; ++r) {
+      cnt[r] = (uint32_t)__builtin_amdgcn_readlane((int)cnt_l, g + r);
+      src[r] = (uint32_t)__builtin_amdgcn_readlane((int)src_l, g + r);
+      dst[r] = (uint32_t)__builtin_amdgcn_readlane((int)dst_l, g + r);
+      col[r] = 0;
+      val[r] = 0;
+      if (lane < cnt[r]) {
+        col[r] = md.st_col[src[r] + lane];
+        val[r] = md.st_val[src[r] + lane];
       }
     }
-    wave_sync();
-    // lane l owns words [l * wpl, (l + 1) * wpl)
-    uint32_t mine = 0;
-    for (uint32_t k = 0; k < wpl; ++k) {
-      const uint32_t w = lane * wpl + k;
-      if (w < W) mine += (uint32_t)__popc(bm[w]);
-    }
-    uint32_t run = wave_scan_inclusive(mine) - mine;
-    for (uint32_t k = 0; k < wpl; ++k) {
-      const uint32_t w = lane * wpl + k;
-      if (w < W) {
-        pre[w] = run;
-        run += (uint32_t)__popc(bm[w]);
-      }
-    }
-    wave_sync();
-    if (fast) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        if (col[r][h] != 0xFFFFFFFFu) {
-          const uint32_t rank = rank_of(col[r][h]);
-          md.out_col[dst[r] + rank] = col[r][h];
-          md.out_val[dst[r] + rank] = val[r][h];
-        }
+    for (int r = 0; r < kGroup; ++r) {
+      if (lane < cnt[r]) {
+        md.out_col[dst[r] + lane] = col[r];
+        md.out_val[dst[r] + lane] = val[r];
       }
-    } else {
-      for (uint32_t e = lane; e < cnt[r]; e += kWave) {
-        const uint32_t c = md.st_col[src[r] + e];
-        const uint16_t v = md.st_val[src[r] + e];
-        const uint32_t rank = rank_of(c);
-        md.out_col[dst[r] + rank] = c;
-        md.out_val[dst[r] + rank] = v;
+      for (uint32_t e = lane + kWave; e < cnt[r]; e += kWave) {        // long runs (uniform trip count)
+        md.out_col[dst[r] + e] = md.st_col[src[r] + e];
+        md.out_val[dst[r] + e] = md.st_val[src[r] + e];
       }
     }
-    wave_sync();                                           // the next row clears the bitmap
   }
 }
 

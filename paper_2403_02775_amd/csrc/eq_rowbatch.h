@@ -7,10 +7,15 @@
 // Outliers are rare (< 1 % of the elements, Sec. 5), so only a few 16-byte chunks per thread
 // hold one.  The bulk pass therefore does the minimum per element (the sums, and one test per
 // chunk: can anything in it reach the threshold?), and the chunks that pass the test
-// ("candidates") are queued per wavefront and dealt out evenly over its lanes, twice: to count,
-// and, once the batch's run of the staging list is reserved, to write.  Within a row the
-// outliers are written in arrival order; gather_outliers sorts each row's run by column when
-// it moves it to its final place, so the result does not depend on timing.
+// ("candidates") are queued per wavefront and dealt out evenly over its lanes, which decide
+// their elements and leave one MASK BYTE per chunk (bit j: element j is an outlier) next to the
+// data: in the 16 bytes of padding that follow every 128-element unit of the padded pool layout
+// (one byte for each of its 16 chunks), or in a separate area for the linear layout.  After that
+// the work goes per UNIT: a thread reads its unit's 16 mask bytes at once, the population counts
+// are prefix-summed over the batch (rows and units in order), one thread reserves the batch's
+// run of the staging list with a single atomic, and every thread writes its unit's outliers at
+// run start + prefix and replaces them by 0 in the pool.  A row's run therefore comes out in
+// ascending column order without any sorting, and no LDS atomic is involved.
 //
 // Statistics (Eq. 3) take a fast path and an exact path with identical results:
 //   fast  : sum x and sum x^2 by packed dot products, mean and sigma in binary32.  The outlier
@@ -40,14 +45,18 @@ struct BatchScratch {
   float part[RB][NW][2];             // per wavefront: sum x, sum x^2 of each row
   double dred[kMaxWaves];
   double mu[RB], thr[RB];            // exact mean and n*sigma of the rows that were redone
-  unsigned long long rowbase[RB];    // staging position of the row, ~0 when it does not fit
   float4 fast[RB];                   // fast mean, lower and upper end of the band around n*sigma
-  uint32_t rowcnt[RB];               // outliers of the row
-  uint32_t rowpos[RB];               // next free entry of the row's run while it is written
+  unsigned long long base;           // start of the batch's run of the staging list
+  uint32_t wtot[kMaxWaves];          // outliers found by each wavefront's units
   uint32_t slow[RB];                 // row takes the exact path
   uint32_t rowmax_bits[RB];          // for kernels with one range per row: bit patterns of max(x, 0) and
   uint32_t rownegmin_bits[RB];       // max(-x, 0) over the row's normal values
-  uint32_t queue[NW][kQueue];        // per wavefront: row << 16 | chunk of its candidate chunks
+  // first the candidate chunks of each wavefront (row << 16 | chunk); once they are dealt with,
+  // the exclusive prefix of the outlier counts of the batch's units (at most 1.5 NT + 1 of them)
+  union {
+    uint32_t queue[NW][kQueue];
+    uint32_t pre[NW * kQueue];
+  };
 };
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -64,6 +73,18 @@ __device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
 __device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
   uint32_t r;
   asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// Three-operand forms (IEEE-754 minimum / maximum: a NaN operand gives NaN, -0 < +0).
+__device__ __forceinline__ uint32_t pk_min3_f16(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_pk_minimum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ uint32_t pk_max3_f16(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_pk_maximum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
   return r;
 }
 
@@ -143,34 +164,69 @@ __device__ __forceinline__ void chunk_floats(const uint4 v, float (&x)[8]) {
 // Split in two so that a caller can have the next batch's loads in flight while it works.
 // Issues every 128-bit load of rows [row0, row0 + nrows): thread t takes chunks t, t + NT, ...
 // of each row; absent rows and chunks read as zero.
-template <int NT, int RB, int K>
+// WM ("wavefront-major", one row per batch): instead of chunks t, t + NT, ... thread t of wavefront
+// w takes chunks c0(w) + lane, c0(w) + lane + 64, ... of the contiguous part [c0(w), c0(w + 1)) of
+// the row that holds the units [w upr / NW, (w + 1) upr / NW): a wavefront then decides, writes and
+// later emits its own units only, and the wavefronts of a workgroup meet at three barriers per
+// batch (the sums, the counts, the reservation) instead of six.
+template <int NT, bool WM>
+__device__ __forceinline__ void wave_part(uint32_t nchunks, uint32_t& c0, uint32_t& c1) {
+  constexpr uint32_t NW = NT / kWave;
+  const uint32_t wave = threadIdx.x / kWave, upr = nchunks >> 4;
+  c0 = WM ? ((wave * upr) / NW) << 4 : 0u;
+  c1 = WM ? (((wave + 1u) * upr) / NW) << 4 : nchunks;
+}
+template <int NT, bool WM>
+__device__ __forceinline__ uint32_t chunk_of(int i, uint32_t c0) {
+  return WM ? c0 + (uint32_t)i * kWave + (threadIdx.x & (kWave - 1)) : (uint32_t)i * NT + threadIdx.x;
+}
+
+template <int NT, int RB, int K, bool WM = false>
 __device__ __forceinline__ void batch_issue_loads(const MatDesc& md, int64_t row0, int nrows, uint4 (&v)[RB][K]) {
+  uint32_t c0, c1;
+  wave_part<NT, WM>((uint32_t)md.cols >> 3, c0, c1);
 #pragma unroll
   for (int r = 0; r < RB; ++r) {
     const bool present = r < nrows;
-    const BufferRsrc rs = make_buffer(md.W + (present ? row0 + r : row0) * md.ld, present ? (uint32_t)md.cols * 2u : 0u);
+    // the view ends with the row, or with the wavefront's part of it: loads beyond read as zero
+    const BufferRsrc rs = make_buffer(md.W + (present ? row0 + r : row0) * md.ld, present ? (WM ? c1 * 16u : (uint32_t)md.cols * 2u) : 0u);
 #pragma unroll
-    for (int i = 0; i < K; ++i) v[r][i] = buffer_load_stream128(rs, ((uint32_t)i * NT + threadIdx.x) * 16u);
+    for (int i = 0; i < K; ++i) v[r][i] = buffer_load_stream128(rs, chunk_of<NT, WM>(i, c0) * 16u);
   }
 }
 
 // Everything after the loads (v = what batch_issue_loads returned for the same rows).  v is read
 // up to the per-chunk outlier test; everything after that works on the pool copy, and
 // `after_reservation_issued()` (called once by every thread, later than the last use of v) may
-// overwrite v.
-template <int DT, int NT, int RB, int K, class Layout, class Hook>
+// overwrite v.  The rows must be whole units (cols a multiple of 128) and ch0 a multiple of 16.
+// mask_area: one byte per chunk of the batch, 16-byte aligned, for layouts that do not keep the
+// mask bytes in the pool (ignored otherwise).
+template <int DT, int NT, int RB, int K, class Layout, bool WM = false, class Hook>
 __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
-                                                  unsigned char* pool, uint32_t ch0, BatchScratch<RB, NT / kWave>* sc,
-                                                  const uint4 (&v)[RB][K], Hook&& after_reservation_issued) {
+                                                  unsigned char* pool, uint32_t ch0, unsigned char* mask_area,
+                                                  BatchScratch<RB, NT / kWave>* sc, const uint4 (&v)[RB][K],
+                                                  Hook&& after_reservation_issued) {
   static_assert(RB * K <= 32, "candidate flags are one 32-bit word");
-  const uint32_t nchunks = (uint32_t)md.cols >> 3;
-  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int NW = NT / kWave;
+  static_assert((RB * K * NT) / 16 + 1 <= NW * kQueue, "the unit prefix must fit the space of the candidate queues");
+  static_assert(!WM || RB == 1, "wavefront-major staging takes one row per batch");
+  const uint32_t nchunks = (uint32_t)md.cols >> 3;
+  uint32_t part_c0, part_c1;                               // the chunks this thread's wavefront looks after
+  wave_part<NT, WM>(nchunks, part_c0, part_c1);
+  const uint32_t upr = nchunks >> 4;                       // units per row
+  const uint32_t nslots = (uint32_t)nrows * upr;           // units of the batch, in (row, column) order
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  unsigned char* const mb = Layout::kMaskInPool ? pool : mask_area;
 
-  if (tid < (uint32_t)RB) {
-    sc->slow[tid] = 0;
-    sc->rowcnt[tid] = 0;
-    sc->rowpos[tid] = 0;
+  if (tid < (uint32_t)RB) sc->slow[tid] = 0;
+  // no outliers anywhere yet (published by the barrier behind the sums; wavefront-major: a
+  // wavefront clears the bytes of its own units, which no other wavefront ever touches)
+  if (WM) {
+    const uint32_t s = (part_c0 >> 4) + lane;
+    if (s < (part_c1 >> 4)) *reinterpret_cast<uint4*>(mb + Layout::mask_off(ch0 + (s << 4))) = make_uint4(0, 0, 0, 0);
+  } else {
+    for (uint32_t s = tid; s < nslots; s += NT)
+      *reinterpret_cast<uint4*>(mb + Layout::mask_off(ch0 + (s << 4))) = make_uint4(0, 0, 0, 0);
   }
 
   // ---- fast sums; the values go to the pool as they are ----
@@ -184,8 +240,8 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
       pair_sums<DT>(v[r][i].y, t1, t2);
       pair_sums<DT>(v[r][i].z, s1, s2);
       pair_sums<DT>(v[r][i].w, t1, t2);
-      const uint32_t ch = (uint32_t)i * NT + tid;
-      if (r < nrows && ch < nchunks)
+      const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
+      if (r < nrows && ch < part_c1)
         *reinterpret_cast<uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)) = v[r][i];
     }
     s1 += t1;
@@ -271,10 +327,11 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
       for (int i = 0; i < K; ++i) {
         bool maybe;
         if (DT == EQ_F16) {
-          const uint32_t mx = pk_max_f16(pk_max_f16(v[r][i].x, v[r][i].y), pk_max_f16(v[r][i].z, v[r][i].w));
-          const uint32_t mn = pk_min_f16(pk_min_f16(v[r][i].x, v[r][i].y), pk_min_f16(v[r][i].z, v[r][i].w));
-          // max(mx, bound) differs from the bound exactly when a half of mx lies above it
-          maybe = ((pk_max_f16(mx, cand_hi[r]) ^ cand_hi[r]) | (pk_min_f16(mn, cand_lo[r]) ^ cand_lo[r])) != 0u;
+          // the maximum of the chunk's values and the bound differs from the bound exactly when a
+          // value lies above it (a bound of -0 with a value of +0 flags a chunk needlessly: harmless)
+          const uint32_t mx = pk_max3_f16(pk_max3_f16(cand_hi[r], v[r][i].x, v[r][i].y), v[r][i].z, v[r][i].w);
+          const uint32_t mn = pk_min3_f16(pk_min3_f16(cand_lo[r], v[r][i].x, v[r][i].y), v[r][i].z, v[r][i].w);
+          maybe = ((mx ^ cand_hi[r]) | (mn ^ cand_lo[r])) != 0u;
         } else {
           float x[8];
           chunk_floats<DT>(v[r][i], x);
@@ -283,17 +340,32 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
           for (int k = 0; k < 8; ++k) dmax = fmaxf(dmax, fabsf(x[k] - mu_f[r]));
           maybe = dmax >= thr_lo[r];
         }
-        const uint32_t ch = (uint32_t)i * NT + tid;
-        if (r < nrows && ch < nchunks && maybe) cand |= 1u << (r * K + i);
+        const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
+        if (r < nrows && ch < part_c1 && maybe) cand |= 1u << (r * K + i);
       }
     }
   }
 
-  // Runs body(row, chunk) once for every candidate chunk of the wavefront.  The lanes that found
-  // candidates found different numbers of them, so the chunks are first queued (row << 16 | chunk,
-  // in lane order) and then dealt out evenly, one per lane and pass over the queue.  A wavefront
-  // with more candidates than the queue holds lets every lane work through its own instead.
-  auto for_each_candidate = [&](auto&& body) {
+  // ---- candidates: decide their elements, leave the mask byte, notice borderline elements ----
+  // The lanes that found candidates found different numbers of them, so the chunks are first queued
+  // (row << 16 | chunk, in lane order) and then dealt out evenly, one per lane and pass over the
+  // queue.  A wavefront with more candidates than the queue holds lets every lane work through its own.
+  {
+    auto body = [&](uint32_t r, uint32_t ch) {
+      const uint4 c = *reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + r * nchunks + ch));
+      const float4 f = sc->fast[r];         // mean, lower and upper end of the band
+      float x[8];
+      chunk_floats<DT>(c, x);
+      uint32_t m_lo = 0, m_hi = 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float d = fabsf(x[k] - f.x);
+        m_lo |= (d >= f.y ? 1u : 0u) << k;
+        m_hi |= (d >= f.z ? 1u : 0u) << k;
+      }
+      if (m_lo != m_hi) sc->slow[r] = 1u;   // an element inside the band: the row is redone exactly
+      if (m_hi) mb[Layout::mask_off(ch0 + r * nchunks + ch)] = (unsigned char)m_hi;
+    };
     const uint32_t mine = (uint32_t)__popc(cand);
     const uint32_t upto = wave_scan_inclusive(mine);
     const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)upto, kWave - 1);
@@ -303,7 +375,7 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
         const int slot = __ffs((int)todo) - 1;
         todo &= todo - 1;
         const int r = slot / K, i = slot - r * K;
-        sc->queue[wave][k++] = ((uint32_t)r << 16) | ((uint32_t)i * NT + tid);
+        sc->queue[wave][k++] = ((uint32_t)r << 16) | chunk_of<NT, WM>(i, part_c0);
       }
       __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -311,8 +383,6 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
         const uint32_t id = sc->queue[wave][e];
         body(id >> 16, id & 0xFFFFu);
       }
-      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-      __builtin_amdgcn_wave_barrier();
     } else {
       uint32_t todo = cand;
       while (__any(todo != 0)) {
@@ -320,161 +390,179 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
           const int slot = __ffs((int)todo) - 1;
           todo &= todo - 1;
           const int r = slot / K, i = slot - r * K;
-          body((uint32_t)r, (uint32_t)i * NT + tid);
+          body((uint32_t)r, chunk_of<NT, WM>(i, part_c0));
+        }
+      }
+    }
+  }
+  // Interleaved chunks: the mask bytes of a unit come from several wavefronts, so all meet here.
+  // Wavefront-major: a unit's bytes were written by its own wavefront, which can go on counting.
+  if (!WM) __syncthreads();
+
+  // ---- exact statistics and masks of the rows that asked for them ----
+  // (a rare path: its loops over the thread's chunks stay rolled, which keeps its registers few)
+  auto exact_redo = [&] {
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      if (r < nrows && sc->slow[r]) {
+        double mu, sigma;
+        if (kp.scope == EQ_STAT_MATRIX) {
+          mu = md.mat_stats[0];
+          sigma = md.mat_stats[1];
+        } else {
+          double s = 0.0;
+#pragma unroll 1
+          for (int i = 0; i < K; ++i) {
+            const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
+            if (ch < part_c1) {
+              float x[8];
+              chunk_floats<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), x);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) s += (double)x[k];
+            }
+          }
+          mu = block_sum(s, sc->dred) / cnt;
+          double q = 0.0;
+#pragma unroll 1
+          for (int i = 0; i < K; ++i) {
+            const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
+            if (ch < part_c1) {
+              float x[8];
+              chunk_floats<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), x);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) {
+                const double dd = (double)x[k] - mu;
+                q += dd * dd;
+              }
+            }
+          }
+          sigma = sqrt(block_sum(q, sc->dred) / cnt);
+        }
+        const double thr = kp.n * sigma;
+        // every mask byte of the row anew (a constant scope has no outliers)
+#pragma unroll 1
+        for (int i = 0; i < K; ++i) {
+          const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
+          if (ch < part_c1) {
+            const uint32_t at = ch0 + (uint32_t)r * nchunks + ch;
+            const uint32_t mm = sigma > 0.0 ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(at)), mu, thr) : 0u;
+            mb[Layout::mask_off(at)] = (unsigned char)mm;
+          }
         }
       }
     }
   };
 
-  // ---- candidates: count the outliers, notice borderline elements ----
-  for_each_candidate([&](uint32_t r, uint32_t ch) {
-    const uint4 c = *reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + r * nchunks + ch));
-    const float4 f = sc->fast[r];         // mean, lower and upper end of the band
-    float x[8];
-    chunk_floats<DT>(c, x);
-    uint32_t n_lo = 0, n_hi = 0;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const float d = fabsf(x[k] - f.x);
-      n_lo += d >= f.y ? 1u : 0u;
-      n_hi += d >= f.z ? 1u : 0u;
+  // ---- per unit: count ----
+  // Interleaved: thread t takes the units [t q, (t + 1) q) of the batch (q = 1 unless the batch holds
+  // more units than the workgroup has threads).  Wavefront-major: lane l takes unit l of its
+  // wavefront's part.  Prefix sums over lanes, then over wavefronts.
+  const uint32_t q = WM ? 1u : (nslots + NT - 1) / NT;
+  const uint32_t s_first = WM ? min((part_c0 >> 4) + lane, part_c1 >> 4) : min(tid * q, nslots);
+  const uint32_t s_last = WM ? min(s_first + 1u, part_c1 >> 4) : min(s_first + q, nslots);
+  uint32_t mycnt, inc, before, total;
+  auto count_units = [&] {
+    mycnt = 0;
+    for (uint32_t s = s_first; s < s_last; ++s) {
+      const uint4 m = *reinterpret_cast<const uint4*>(mb + Layout::mask_off(ch0 + (s << 4)));
+      mycnt += (uint32_t)(__popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w));
     }
-    if (n_lo != n_hi) sc->slow[r] = 1u;   // an element inside the band
-    if (n_hi) atomicAdd(&sc->rowcnt[r], n_hi);
-  });
-  __syncthreads();
-
-  // ---- exact statistics and counts of the rows that asked for them (uniform branch per row) ----
+    inc = wave_scan_inclusive(mycnt);
+    before = 0;
+    total = (uint32_t)__builtin_amdgcn_readlane((int)inc, kWave - 1);
+    if (NW > 1) {
+      if (lane == kWave - 1) sc->wtot[wave] = inc;
+      __syncthreads();                                     // also publishes the rows' exact-path flags
+      total = 0;
 #pragma unroll
-  for (int r = 0; r < RB; ++r) {
-    if (r < nrows && sc->slow[r]) {
-      double mu, sigma;
-      if (kp.scope == EQ_STAT_MATRIX) {
-        mu = md.mat_stats[0];
-        sigma = md.mat_stats[1];
-      } else {
-        double s = 0.0;
-#pragma unroll
-        for (int i = 0; i < K; ++i) {
-          const uint32_t ch = (uint32_t)i * NT + tid;
-          if (ch < nchunks) {
-            float x[8];
-            chunk_floats<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), x);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) s += (double)x[k];
-          }
-        }
-        mu = block_sum(s, sc->dred) / cnt;
-        double q = 0.0;
-#pragma unroll
-        for (int i = 0; i < K; ++i) {
-          const uint32_t ch = (uint32_t)i * NT + tid;
-          if (ch < nchunks) {
-            float x[8];
-            chunk_floats<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), x);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-              const double dd = (double)x[k] - mu;
-              q += dd * dd;
-            }
-          }
-        }
-        sigma = sqrt(block_sum(q, sc->dred) / cnt);
+      for (int w = 0; w < NW; ++w) {
+        const uint32_t t = sc->wtot[w];
+        before += (uint32_t)w < wave ? t : 0u;
+        total += t;
       }
-      const double thr = kp.n * sigma;
-      if (tid == 0) {
-        sc->mu[r] = mu;
-        sc->thr[r] = sigma > 0.0 ? thr : __builtin_inf();    // a constant scope has no outliers
-        sc->rowcnt[r] = 0;
-      }
+    }
+  };
+  count_units();
+  {
+    bool any_slow = false;                                 // uniform over the workgroup
+#pragma unroll
+    for (int r = 0; r < RB; ++r) any_slow = any_slow || (r < nrows && sc->slow[r]);
+    if (any_slow) {
+      exact_redo();
       __syncthreads();
-      uint32_t n_out = 0;
-#pragma unroll
-      for (int i = 0; i < K; ++i) {
-        const uint32_t ch = (uint32_t)i * NT + tid;
-        const uint32_t mm = (ch < nchunks && sigma > 0.0)
-                                ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(ch0 + (uint32_t)r * nchunks + ch)), mu, thr)
-                                : 0u;
-        n_out += __popc(mm);
-        if (mm) cand |= 1u << (r * K + i);
-        else cand &= ~(1u << (r * K + i));
-      }
-      if (n_out) atomicAdd(&sc->rowcnt[r], n_out);
+      count_units();
     }
   }
-  __syncthreads();
+  {
+    uint32_t run = before + inc - mycnt;                   // outliers of the batch in front of this thread's units
+    for (uint32_t s = s_first; s < s_last; ++s) {
+      sc->pre[s] = run;
+      if (q > 1) {
+        const uint4 m = *reinterpret_cast<const uint4*>(mb + Layout::mask_off(ch0 + (s << 4)));
+        run += (uint32_t)(__popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w));
+      }
+    }
+  }
 
   // ---- one reservation for the batch ----
   // Thread 0 issues the atomic, the caller's hook runs (the T = 0 kernel starts the loads of its
   // next batch there: v is dead by now, and loads issued after the atomic do not delay its
-  // return, which is awaited by count), then thread 0 hands out the rows' positions.
-  uint32_t total = 0;
+  // return, which is awaited by count), then thread 0 publishes the run's start.
   unsigned long long b = 0;
   if (tid == 0) {
-    for (int r = 0; r < nrows; ++r) total += sc->rowcnt[r];
+    sc->pre[nslots] = total;
     if (total) b = global_atomic_add(md.cursor, (unsigned long long)total);
   }
   after_reservation_issued();
-  if (tid == 0) {
-    // unrolled on purpose (in front of a loop the compiler would wait for every outstanding load),
-    // and nothing but LDS stores after the first use of b (each later global store would move the
-    // count that the wait for b is expressed in)
-#pragma unroll
-    for (int r = 0; r < RB; ++r) {
-      if (r < nrows) {
-        const uint32_t t = sc->rowcnt[r];
-        sc->rowbase[r] = b + t <= (unsigned long long)md.capacity ? b : ~0ull;
-        b += t;
-      }
-    }
-  }
+  if (tid == 0) sc->base = b;            // nothing but this LDS store after the first use of b (each global
+                                         // store in between would move the count that the wait is expressed in)
   __syncthreads();
+  b = sc->base;
+  // a row fits if its last entry does: rows come in order, so everything in front of it fits as well
   if (tid < (uint32_t)nrows) {
-    const unsigned long long base = sc->rowbase[tid];
-    md.row_count[row0 + tid] = sc->rowcnt[tid];
-    md.row_stage[row0 + tid] = base != ~0ull ? (uint32_t)base : 0xFFFFFFFFu;
-    if (base == ~0ull) global_atomic_or(md.status, EQ_S_OUTLIER_OVERFLOW);
+    const uint32_t c0 = sc->pre[tid * upr], c1 = sc->pre[(tid + 1u) * upr];
+    const bool fits = b + c1 <= (unsigned long long)md.capacity;
+    md.row_count[row0 + tid] = c1 - c0;
+    md.row_stage[row0 + tid] = fits ? (uint32_t)(b + c0) : 0xFFFFFFFFu;
+    if (!fits) global_atomic_or(md.status, EQ_S_OUTLIER_OVERFLOW);
   }
 
-  // ---- candidates again: write (column, raw value), zero the pool copy ----
-  for_each_candidate([&](uint32_t r, uint32_t ch) {
-    unsigned char* cp = pool + Layout::off(ch0 + r * nchunks + ch);
-    const uint4 c = *reinterpret_cast<const uint4*>(cp);
-    uint32_t mm = 0;
-    if (sc->slow[r]) {
-      mm = chunk_mask<DT>(c, sc->mu[r], sc->thr[r]);
-    } else {
-      const float4 f = sc->fast[r];
-      float x[8];
-      chunk_floats<DT>(c, x);
+  // ---- per unit: write (column, raw value) in ascending order, put 0 in the pool ----
+  for (uint32_t s = s_first; s < s_last; ++s) {
+    const uint4 m = *reinterpret_cast<const uint4*>(mb + Layout::mask_off(ch0 + (s << 4)));
+    if ((m.x | m.y | m.z | m.w) == 0u) continue;
+    // (floor(s / upr) as a multiply-high: exact for s < 2^20, upr <= 4096; no division sequence)
+    const uint32_t r = RB > 1 ? __umulhi(s, 0xFFFFFFFFu / upr + 1u) : 0u, u = s - r * upr;   // row of the batch, unit of the row
+    const bool fits = b + sc->pre[(r + 1u) * upr] <= (unsigned long long)md.capacity;
+    unsigned long long pos = b + sc->pre[s];
+    const uint32_t words[4] = {m.x, m.y, m.z, m.w};
 #pragma unroll
-      for (int k = 0; k < 8; ++k) mm |= (fabsf(x[k] - f.x) >= f.z ? 1u : 0u) << k;
-    }
-    if (mm) {
-      const unsigned long long base = sc->rowbase[r];
-      unsigned long long pos = base + atomicAdd(&sc->rowpos[r], (uint32_t)__popc(mm));
-      unsigned short* e = reinterpret_cast<unsigned short*>(cp);
-      while (mm) {
-        const int j = __ffs((int)mm) - 1;
-        mm &= mm - 1;
-        if (base != ~0ull) {
-          md.st_col[pos] = ch * 8u + (uint32_t)j;
-          md.st_val[pos] = e[j];
+    for (int wi = 0; wi < 4; ++wi) {
+      uint32_t bits = words[wi];                           // 4 chunks of 8 elements
+      while (bits) {
+        const uint32_t bit = (uint32_t)__ffs((int)bits) - 1u;
+        bits &= bits - 1u;
+        const uint32_t chunk = 4u * (uint32_t)wi + (bit >> 3), j = bit & 7u;
+        unsigned short* e = reinterpret_cast<unsigned short*>(pool + Layout::off(ch0 + (s << 4) + chunk)) + j;
+        if (fits) {
+          md.st_col[pos] = (u << 7) + (chunk << 3) + j;
+          md.st_val[pos] = *e;
         }
         ++pos;
-        e[j] = 0;
+        *e = 0;
       }
     }
-  });
-  __syncthreads();
+  }
+  if (!WM) __syncthreads();              // wavefront-major: the units a wavefront goes on with are its own
 }
 
 template <int DT, int NT, int RB, int K, class Layout>
 __device__ __forceinline__ void stage_rows_batch(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
-                                                 unsigned char* pool, uint32_t ch0, BatchScratch<RB, NT / kWave>* sc) {
+                                                 unsigned char* pool, uint32_t ch0, unsigned char* mask_area,
+                                                 BatchScratch<RB, NT / kWave>* sc) {
   uint4 v[RB][K];
   batch_issue_loads<NT, RB, K>(md, row0, nrows, v);     // every load of the batch in flight
-  stage_loaded_rows<DT, NT, RB, K, Layout>(md, kp, row0, nrows, pool, ch0, sc, v, [] {});
+  stage_loaded_rows<DT, NT, RB, K, Layout>(md, kp, row0, nrows, pool, ch0, mask_area, sc, v, [] {});
 }
 
 }  // namespace eq

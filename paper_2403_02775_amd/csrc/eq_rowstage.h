@@ -15,11 +15,19 @@ namespace eq {
 //   Linear : chunk ch at byte 16*ch.
 //   Padded : every 128-element unit (16 chunks) is followed by one empty chunk, so that
 //            lanes that each own one unit (stride 272 B) hit distinct banks on 128-bit reads.
+// The batched staging keeps one outlier-mask byte per chunk (eq_rowbatch.h): mask_off(ch) is its
+// place, in the pool itself (the padding chunk of the unit: 16 bytes for its 16 chunks) or in a
+// separate area of one byte per chunk that the caller provides.  Either way the 16 bytes of a
+// unit are contiguous and 16-byte aligned.
 struct LinearLayout {
+  static constexpr bool kMaskInPool = false;
   static __device__ __forceinline__ uint32_t off(uint32_t ch) { return ch * 16u; }
+  static __device__ __forceinline__ uint32_t mask_off(uint32_t ch) { return ch; }
 };
 struct Padded128Layout {
+  static constexpr bool kMaskInPool = true;
   static __device__ __forceinline__ uint32_t off(uint32_t ch) { return ch * 16u + (ch >> 4) * 16u; }
+  static __device__ __forceinline__ uint32_t mask_off(uint32_t ch) { return (ch >> 4) * 272u + 256u + (ch & 15u); }
 };
 
 struct StageScratch {      // small LDS block used by the staging steps

@@ -18,8 +18,8 @@ extern "C" {
 enum {
   EQ_OVR_UNITS_PER_ITEM = 0, /* n > 0: units a workgroup walks through (how the work is cut up) */
   EQ_OVR_FORCE_GENERAL = 1,  /* 1: every matrix goes to the general kernel */
-  EQ_OVR_RTN_THREADS = 2,    /* 256 | 512: workgroup size of the kernel without optimisation steps
-                                (512 only for rows longer than 8192) */
+  EQ_OVR_RTN_THREADS = 2,    /* 128 | 256 | 512: workgroup size of the kernel without optimisation steps
+                                (128 only for rows of up to 8192 columns, 512 only for longer ones) */
   EQ_OVR_CHANNEL_KERNEL = 3, /* 128: per-channel rows stay on the kernel with 128-element segments
                                 where another one would serve them */
   EQ_OVR_MATVEC_ARITHMETIC = 4, /* 1: eq_dequant_matvec takes the plain arithmetic for grouped 4-bit
@@ -29,10 +29,13 @@ enum {
 EQ_API int eq_test_set_override(int which, int64_t value);   /* EQ_OK or EQ_E_PARAM */
 
 /* The launch plan of eq_quantize_batch for these shapes (host only, no GPU): writes up to
- * max_items work items as (matrix, first row, rows) triples into `items` and returns the number
- * of items of the plan (which may exceed max_items), or a negative EQ_E_* code.  Matrices that
- * the general kernel serves (one workgroup per row) have no items.  `launch_of_item`, if not
- * NULL, receives for each written item the index of the launch (row-length class) it belongs to. */
+ * max_items work items, five numbers each, into `items` and returns the number of items of the
+ * plan (which may exceed max_items), or a negative EQ_E_* code.  An item is (matrix, first row,
+ * rows, stride, step): the workgroup takes rows [first, first + rows) of the matrix, all of them
+ * when stride == 0, else the `step` rows at first, first + stride, first + 2 stride, ...
+ * Matrices that the general kernel serves (one workgroup per row) have no items.
+ * `launch_of_item`, if not NULL, receives for each written item the index of the launch
+ * (row-length class) it belongs to. */
 EQ_API int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
                                   const eq_params* p, int32_t* items, int32_t* launch_of_item, int64_t max_items);
 

@@ -83,9 +83,11 @@ def _pick_rows(Ws, p, rows_per_matrix, boundaries_per_launch, seed):
     picks = [set([0, r - 1]) for r in rows]
     items = eqg.plan_items(rows, cols, _capacities(Ws), to_gpu_params(p))
     by_launch = {}
-    for m, r0, nr, launch in items:
+    for m, r0, nr, stride, step, launch in items:
         if r0 > 0:                                         # the cut between two items of one matrix
             by_launch.setdefault(launch, []).append((m, r0))
+        if stride and r0 + stride < rows[m]:               # interleaved items: where the item's second step starts
+            by_launch.setdefault(launch, []).append((m, r0 + stride))
     n_bound = 0
     for launch, cuts in sorted(by_launch.items()):
         take = np.unique(np.linspace(0, len(cuts) - 1, min(boundaries_per_launch, len(cuts))).round().astype(int))
@@ -224,19 +226,20 @@ def _c5_sample(oracle_pool, Ws, p, what, row_fraction, min_rows, keep=None):
     return rows
 
 
-@pytest.mark.parametrize("half", [0, 1])
-def test_config5_llama65b_two_percent_of_the_rows_of_every_matrix(oracle_pool, c5_weights, half):
+@pytest.mark.parametrize("quarter", [0, 1, 2, 3])
+def test_config5_llama65b_two_percent_of_the_rows_of_every_matrix(oracle_pool, c5_weights, quarter):
     """The headline configuration (group 128, T = 100): first / last rows, rows around work-item
-    boundaries, and a seeded 2 % of the rows of each of the 560 matrices (layers 0-39, then 40-79,
-    each out of a batch call over the whole set)."""
+    boundaries, and a seeded 2 % of the rows of each of the 560 matrices (20 layers per test, each
+    out of a batch call over the whole set, so that no single test keeps the host busy for long)."""
     Ws, names = c5_weights
-    rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=128, iters=100), f"c5 layers {40 * half}-{40 * half + 39}",
-                      0.02, 17, keep=lambda k: names[k][0] // 40 == half)
-    assert rows >= 70000
+    rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=128, iters=100),
+                      f"c5 layers {20 * quarter}-{20 * quarter + 19}", 0.02, 17, keep=lambda k: names[k][0] // 20 == quarter)
+    assert rows >= 35000
     torch.cuda.empty_cache()
 
 
-def test_config5_llama65b_one_whole_layer(oracle_pool, c5_weights):
+@pytest.mark.parametrize("part", ["attention", "mlp"])
+def test_config5_llama65b_one_whole_layer(oracle_pool, c5_weights, part):
     """All seven matrices of one layer, out of the batch call over the whole set, in full."""
     Ws, names = c5_weights
     p = eqo.Params(bits=4, group_size=128, iters=100)
@@ -245,7 +248,7 @@ def test_config5_llama65b_one_whole_layer(oracle_pool, c5_weights):
     layer = 41
     elems = 0
     for k, ((ly, nm), W) in enumerate(zip(names, Ws)):
-        if ly != layer:
+        if ly != layer or (nm in ("q", "k", "v", "o")) != (part == "attention"):
             continue
         rows, cols = W.shape
         raw = raw_of(W)
@@ -257,7 +260,7 @@ def test_config5_llama65b_one_whole_layer(oracle_pool, c5_weights):
         elems += raw.size
         print(f"[full-size] c5 layer {layer} {nm} {rows} x {cols}: {res['units']} units bit-equal, oracle {secs:.1f} s", flush=True)
         del raw, want
-    assert elems == 4 * 8192 * 8192 + 3 * 8192 * 22016
+    assert elems == (4 * 8192 * 8192 if part == "attention" else 3 * 8192 * 22016)
     del outs
     torch.cuda.empty_cache()
 
