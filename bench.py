@@ -430,8 +430,11 @@ def main():
                                              out_row_ptr=o.out_row_ptr, out_col=o.out_col, out_val=o.out_val, status=o.status)
                                  for o, w in zip(outs, Ws)]
                 q_outs = chan_outs
-            r = timed(q, q_outs, args.sweep_steps, 1, label)
-            sweep.append({"config": label, "iters": iters, "group_size": group, "lr": lr, "steps": args.sweep_steps,
+            # short steps need more of them: the first few calls of a configuration run a few percent
+            # slower than the steady state (clocks, address translation of 180 GB of buffers)
+            n_steps, n_warm = (10 * args.sweep_steps, 5) if iters <= 10 else (args.sweep_steps, 1)
+            r = timed(q, q_outs, n_steps, n_warm, label)
+            sweep.append({"config": label, "iters": iters, "group_size": group, "lr": lr, "steps": n_steps, "warmup": n_warm,
                           "ms_per_step": r["ms_per_step"], "seconds_per_model": r["ms_per_step"] * 1e-3,
                           "weight_GBps": r["weight_GBps"], "weight_hbm_frac": r["weight_GBps"] * 1e9 / HBM_PEAK,
                           "hbm_frac": r["step_hbm_frac"], "useful_op_frac": r["step_useful_op_frac"],

@@ -439,12 +439,26 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
           sigma = sqrt(block_sum(q, sc->dred) / cnt);
         }
         const double thr = kp.n * sigma;
-        // every mask byte of the row anew (a constant scope has no outliers)
+        if ((slow_rows >> r) & 1u) {
+          // the row took the exact path from the start (no chunk test was made): every mask byte of
+          // the row (a constant scope has no outliers)
 #pragma unroll 1
-        for (int i = 0; i < K; ++i) {
-          const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
-          if (ch < part_c1) {
-            const uint32_t at = ch0 + (uint32_t)r * nchunks + ch;
+          for (int i = 0; i < K; ++i) {
+            const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
+            if (ch < part_c1) {
+              const uint32_t at = ch0 + (uint32_t)r * nchunks + ch;
+              const uint32_t mm = sigma > 0.0 ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(at)), mu, thr) : 0u;
+              mb[Layout::mask_off(at)] = (unsigned char)mm;
+            }
+          }
+        } else {
+          // the row has an element inside the band: its candidate chunks anew (every other chunk lies
+          // strictly inside the band's lower end, where the fast and the exact decision agree)
+          uint32_t todo = (cand >> (r * K)) & ((1u << K) - 1u);
+          while (todo) {
+            const int i = __ffs((int)todo) - 1;
+            todo &= todo - 1;
+            const uint32_t at = ch0 + (uint32_t)r * nchunks + chunk_of<NT, WM>(i, part_c0);
             const uint32_t mm = sigma > 0.0 ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(at)), mu, thr) : 0u;
             mb[Layout::mask_off(at)] = (unsigned char)mm;
           }
@@ -531,8 +545,9 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   for (uint32_t s = s_first; s < s_last; ++s) {
     const uint4 m = *reinterpret_cast<const uint4*>(mb + Layout::mask_off(ch0 + (s << 4)));
     if ((m.x | m.y | m.z | m.w) == 0u) continue;
-    // (floor(s / upr) as a multiply-high: exact for s < 2^20, upr <= 4096; no division sequence)
-    const uint32_t r = RB > 1 ? __umulhi(s, 0xFFFFFFFFu / upr + 1u) : 0u, u = s - r * upr;   // row of the batch, unit of the row
+    // (floor(s / upr) as a multiply-high: exact for s < 2^20, 2 <= upr <= 4096; no division sequence)
+    const uint32_t r = RB == 1 ? 0u : upr == 1u ? s : __umulhi(s, 0xFFFFFFFFu / upr + 1u);   // row of the batch,
+    const uint32_t u = s - r * upr;                                                           // unit of the row
     const bool fits = b + sc->pre[(r + 1u) * upr] <= (unsigned long long)md.capacity;
     unsigned long long pos = b + sc->pre[s];
     const uint32_t words[4] = {m.x, m.y, m.z, m.w};
