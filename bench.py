@@ -192,6 +192,8 @@ def bench_matvec(args):
     G = args.matvec_group                            # 0: one range per row (the paper's setting)
     upr = cols // G if G else 1
     gp = eqg.Params(dtype=eqg.EQ_F16, bits=4, group_size=G)
+    if args.matvec_lookup:
+        eqg.set_override(eqg.OVR_MATVEC_LOOKUP, args.matvec_lookup)
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (rows, cols * 4 // 32), dtype=torch.int32, device=dev, generator=g)
@@ -272,6 +274,10 @@ def main():
     ap.add_argument("--dequant", action="store_true", help="measure eq_dequantize instead (secondary benchmark, own JSON line)")
     ap.add_argument("--outlier-pct", type=float, default=1.0, help="outlier ratio in percent for --matvec")
     ap.add_argument("--matvec-group", type=int, default=0, help="group size for --dequant and --matvec (0 = one range per row)")
+    ap.add_argument("--matvec-lookup", type=int, default=0,
+                    help="measurement override for --matvec with one range per row: 1 = half of the weight pairs from the "
+                         "table of pairs, half from the table of single values, 2 = table of single values only "
+                         "(default 0: the library's choice, the table of pairs)")
     ap.add_argument("--matvec", action="store_true", help="measure eq_dequant_matvec instead (secondary benchmark, own JSON line)")
     args = ap.parse_args()
     if args.dequant:

@@ -267,7 +267,7 @@ def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tens
 
 
 # ---- hooks for tests and measurements (csrc/eq_testing.h; not part of the C ABI) ----------------
-OVR_UNITS_PER_ITEM, OVR_FORCE_GENERAL, OVR_RTN_THREADS, OVR_CHANNEL_KERNEL, OVR_MATVEC_ARITHMETIC = range(5)
+OVR_UNITS_PER_ITEM, OVR_FORCE_GENERAL, OVR_RTN_THREADS, OVR_CHANNEL_KERNEL, OVR_MATVEC_ARITHMETIC, OVR_MATVEC_LOOKUP = range(6)
 
 
 class override:

@@ -913,6 +913,19 @@ int eq_dequant_matvec(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_
     const bool tables = d.G >= 64 && (d.G & (d.G - 1)) == 0 && (seg_cols % d.G == 0 || d.G % seg_cols == 0) &&
                         override_of(EQ_OVR_MATVEC_ARITHMETIC) != 1;   // test / measurement override
     const int mode = p->bits != 4 ? 0 : d.upr == 1 ? 2 : tables ? (d.G == 64 ? 4 : 3) : 1;
+    if (mode == 2 && cols % 32 == 0) {
+      // the paper's format: one range per row (a kernel of its own, 128-bit code loads)
+      const int64_t lk = override_of(EQ_OVR_MATVEC_LOOKUP);
+#define EQ_MVR(DT_, LK_) hipLaunchKernelGGL((dequant_matvec_rows4<DT_, LK_>), grid, block, 0, st, d, xd, yd)
+      if (p->dtype == EQ_F16) {
+        if (lk == 1) EQ_MVR(EQ_F16, kLookupMixed); else if (lk == 2) EQ_MVR(EQ_F16, kLookupSingles); else EQ_MVR(EQ_F16, kLookupPairs);
+      } else {
+        if (lk == 1) EQ_MVR(EQ_BF16, kLookupMixed); else if (lk == 2) EQ_MVR(EQ_BF16, kLookupSingles); else EQ_MVR(EQ_BF16, kLookupPairs);
+      }
+#undef EQ_MVR
+      EQ_HIP(hipGetLastError());
+      return EQ_OK;
+    }
 #define EQ_MV(DT_, MODE_) hipLaunchKernelGGL((dequant_matvec<DT_, MODE_>), grid, block, 0, st, d, xd, yd)
     if (p->dtype == EQ_F16) {
       if (mode == 4) EQ_MV(EQ_F16, 4); else if (mode == 3) EQ_MV(EQ_F16, 3); else if (mode == 2) EQ_MV(EQ_F16, 2);

@@ -330,19 +330,21 @@ __device__ __forceinline__ float dot8(const uint4 w, const uint4 x, float acc) {
   const uint32_t a[4] = {w.x, w.y, w.z, w.w}, b[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
+    // one packed dot-product instruction per pair, accumulating in binary32 (both formats)
     if (DT == EQ_F16) {
       typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
       acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a[k]), __builtin_bit_cast(half2_t, b[k]), acc, false);
     } else {
-      acc = __builtin_fmaf(widen16<DT>(a[k] & 0xFFFFu), widen16<DT>(b[k] & 0xFFFFu), acc);
-      acc = __builtin_fmaf(widen16<DT>(a[k] >> 16), widen16<DT>(b[k] >> 16), acc);
+      typedef __bf16 bfloat2_t __attribute__((ext_vector_type(2)));
+      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bfloat2_t, a[k]), __builtin_bit_cast(bfloat2_t, b[k]), acc, false);
     }
   }
   return acc;
 }
 
 // MODE 0: any code width (dequantize_chunk).  MODE 1: 4-bit codes, one code word per chunk
-// (dequantize_chunk4).  MODE 2: 4-bit codes and one range per row: the 16 values a weight of a row
+// (dequantize_chunk4).  MODE 2: 4-bit codes and one range per row (rows whose length is not a
+// multiple of 32; the others take dequant_matvec_rows4 below): the 16 values a weight of a row
 // can take, fl16(fl32(s (u - z))) for u = 0..15, are tabulated in LDS once and every weight is
 // one 16-bit LDS read (two address instructions) instead of five arithmetic instructions.
 // MODE 3: 4-bit codes with groups of 128 or more elements that tile the 4096-column segments (or
@@ -565,5 +567,165 @@ __global__ __launch_bounds__(kThreads) void dequant_matvec(DeqDesc d, const EQ_G
     y[row0 + tid] = t;
   }
 }
+
+// ---- the same for the paper's own format: 4-bit codes, one range per row ---------------------
+// (cols a multiple of 32).  A thread takes 32 consecutive columns of a segment of 8192: one
+// 128-bit load of codes per row (a wavefront reads 1 KB of a row's stream at a time) and four
+// chunks of x that serve all kMvRows rows of the workgroup.  Weights come from tables in LDS: the
+// 16 values a weight of the row can take, fl16(fl32(s (u - z))), and from them the 256 PAIRS of
+// values that a byte of the code stream (two neighbouring weights) can stand for, as packed words
+// (1 KB per row).  LOOKUP selects how the four pairs of a code word are fetched: all from the table
+// of pairs (one random 32-bit read per pair: few vector instructions, but 64 lanes spread over 256
+// words collide in the LDS banks), all from the table of single values (two 16-bit reads that never
+// collide, five vector instructions per pair), or two and two.
+enum { kLookupPairs = 0, kLookupMixed = 1, kLookupSingles = 2 };
+constexpr int kMvRowChunks = 4;          // chunks of 8 columns per thread and segment
+
+template <int DT, int LOOKUP>
+__global__ __launch_bounds__(kThreads) void dequant_matvec_rows4(DeqDesc d, const EQ_GLOBAL uint16_t* __restrict__ x,
+                                                                  EQ_GLOBAL float* __restrict__ y) {
+  __shared__ float red[kMvRows][kWaves];
+  __shared__ __align__(16) uint16_t lut[kMvRows][16];
+  __shared__ uint32_t lut_pair[kMvRows][256];
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int64_t row0 = (int64_t)blockIdx.x * kMvRows;
+  const int nrows = (int)min((int64_t)kMvRows, (int64_t)d.rows - row0);
+  const uint32_t nchunks = (uint32_t)d.cols >> 3;
+  uint32_t rp[kMvRows + 1];                              // the rows' sparse ranges (loaded early, used last)
+#pragma unroll
+  for (int r = 0; r <= kMvRows; ++r) rp[r] = d.out_col ? d.out_row_ptr[row0 + min(r, nrows)] : 0u;   // absent rows: empty
+  if (tid < (uint32_t)(kMvRows * 16)) {
+    const int r = (int)(tid >> 4), u = (int)(tid & 15u);
+    const int64_t row = row0 + (r < nrows ? r : 0);
+    float prod = d.scales[row] * ((float)u - (float)d.zps[row]);
+    asm volatile("" : "+v"(prod));        // two roundings, as in dequantize_chunk
+    lut[r][u] = (uint16_t)narrow16<DT>(prod);
+  }
+  __syncthreads();
+  static_assert(kThreads == 256, "one thread per byte value");
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r)        // low nibble = the even column (low half of the pair), high nibble = the odd one
+    lut_pair[r][tid] = (uint32_t)lut[r][tid & 15u] | ((uint32_t)lut[r][tid >> 4] << 16);
+  __syncthreads();
+  // range-checked views of the rows' code words: words past the end of a row and rows past the
+  // end of the matrix read as zero without touching memory (their x chunk is zero too)
+  BufferRsrc crow[kMvRows];
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r)
+    crow[r] = make_buffer(d.codes + (r < nrows ? row0 + r : row0) * (int64_t)d.words_per_row,
+                          r < nrows ? (uint32_t)d.words_per_row * 4u : 0u);
+  float acc[kMvRows];
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r) acc[r] = 0.0f;
+  // ---- the rows' sparse lists: every wavefront takes those of two rows, one contiguous stretch of
+  // the CSR arrays, in a strided walk (see dequant_matvec) ----
+  auto sparse_part = [&] {
+    if (!d.out_col) return;
+    static_assert(kMvRows == 2 * kWaves, "two rows per wavefront");
+    const uint32_t w2 = 2u * (uint32_t)__builtin_amdgcn_readfirstlane((int)wave);
+    uint32_t b = 0, m = 0, e = 0;
+#pragma unroll
+    for (int r = 0; r <= kMvRows; ++r) {
+      if ((uint32_t)r == w2) b = rp[r];
+      if ((uint32_t)r == w2 + 1u) m = rp[r];
+      if ((uint32_t)r == w2 + 2u) e = rp[r];
+    }
+    float sa = 0.0f, sb = 0.0f;
+    constexpr int kAhead = 4;                            // entries per thread in flight (two dependent loads each)
+    for (uint32_t i0 = b + lane; i0 < e; i0 += kAhead * kWave) {
+      uint32_t col[kAhead];
+      float val[kAhead], xg[kAhead];
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        const uint32_t i = i0 + (uint32_t)a * kWave;
+        col[a] = i < e ? d.out_col[i] : 0xFFFFFFFFu;
+        val[a] = i < e ? widen16<DT>(d.out_val[i]) : 0.0f;
+      }
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) xg[a] = col[a] < (uint32_t)d.cols ? widen16<DT>(x[col[a]]) : 0.0f;
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        const uint32_t i = i0 + (uint32_t)a * kWave;
+        const float prod = val[a] * xg[a];
+        sa += i < m ? prod : 0.0f;
+        sb += i < m ? 0.0f : prod;
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kMvRows; ++r) acc[r] += (uint32_t)r == w2 ? sa : ((uint32_t)r == w2 + 1u ? sb : 0.0f);
+  };
+  // The walk is a chain of dependent loads (entry, then x at its column) with little to do in
+  // between.  Workgroups start together and would all reach it together at the end, with nothing
+  // left to hide it behind: every other workgroup takes it first, under its neighbours' dense part.
+  const bool sparse_first = (blockIdx.x & 1u) != 0u;
+  if (sparse_first) sparse_part();
+  // Rolling prefetch: a row's code words for the next segment are requested as soon as this
+  // segment's have been used (same registers), and the next chunks of x at the top of the segment,
+  // so that every wavefront has loads in flight while it computes (without this the wavefronts of a
+  // SIMD fall into step: all wait for memory, then all compute).
+  constexpr uint32_t kSeg = kMvRowChunks * kThreads;     // chunks per segment
+  auto load_x = [&](uint32_t ch0, uint4 (&xv)[kMvRowChunks]) {
+    const uint32_t c0 = ch0 + kMvRowChunks * tid;
+#pragma unroll
+    for (int j = 0; j < kMvRowChunks; ++j)
+      xv[j] = c0 + (uint32_t)j < nchunks ? global_load128(x + 8 * (size_t)(c0 + j)) : make_uint4(0, 0, 0, 0);
+  };
+  uint4 xv[kMvRowChunks], xn[kMvRowChunks], wq[kMvRows];
+  load_x(0u, xv);
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r) wq[r] = buffer_load_stream128(crow[r], kMvRowChunks * tid * 4u);
+  for (uint32_t ch0 = 0; ch0 < nchunks; ch0 += kSeg) {
+    const uint32_t c_next = ch0 + kSeg + kMvRowChunks * tid;   // this thread's first chunk (= code word) of the next segment
+    load_x(ch0 + kSeg, xn);                                     // (past the end: zeros, no load)
+#pragma unroll
+    for (int r = 0; r < kMvRows; ++r) {
+      const unsigned char* tab2 = reinterpret_cast<const unsigned char*>(&lut_pair[r][0]);
+      const unsigned char* tab1 = reinterpret_cast<const unsigned char*>(&lut[r][0]);
+      const uint32_t words[4] = {wq[r].x, wq[r].y, wq[r].z, wq[r].w};
+      wq[r] = buffer_load_stream128(crow[r], c_next * 4u);     // beyond the row: zeros, no memory access
+#pragma unroll
+      for (int j = 0; j < kMvRowChunks; ++j) {
+        const uint32_t w = words[j];
+        typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+        uint32_t pr[4];
+        constexpr int kFromPairs = LOOKUP == kLookupPairs ? 4 : LOOKUP == kLookupMixed ? 2 : 0;
+#pragma unroll
+        for (int k = 0; k < kFromPairs; ++k)
+          pr[k] = *reinterpret_cast<const uint32_t*>(tab2 + (((w >> (8 * k)) & 0xFFu) << 2));
+        if (kFromPairs < 4) {
+          // byte offsets into the table of single values, four at a time: even elements, odd elements
+          uint32_t ev = (w << 1) & 0x1E1E1E1Eu, od = (w >> 3) & 0x1E1E1E1Eu;
+          asm("" : "+v"(ev), "+v"(od));       // keep the two words: a byte of them is one bit-field extract away
+#pragma unroll
+          for (int k = kFromPairs; k < 4; ++k) {
+            ushort2_t h;
+            h.x = *reinterpret_cast<const unsigned short*>(tab1 + ((ev >> (8 * k)) & 0xFFu));
+            h.y = *reinterpret_cast<const unsigned short*>(tab1 + ((od >> (8 * k)) & 0xFFu));
+            pr[k] = __builtin_bit_cast(uint32_t, h);
+          }
+        }
+        acc[r] = dot8<DT>(make_uint4(pr[0], pr[1], pr[2], pr[3]), xv[j], acc[r]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kMvRowChunks; ++j) xv[j] = xn[j];
+  }
+  if (!sparse_first) sparse_part();
+#pragma unroll
+  for (int r = 0; r < kMvRows; ++r) {
+    float v = acc[r];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (lane == 0) red[r][wave] = v;
+  }
+  __syncthreads();
+  if (tid < (uint32_t)nrows) {
+    float t = red[tid][0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) t += red[tid][w];
+    y[row0 + tid] = t;
+  }
+}
+
 
 }  // namespace eq

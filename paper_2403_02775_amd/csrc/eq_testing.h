@@ -24,7 +24,10 @@ enum {
                                 where another one would serve them */
   EQ_OVR_MATVEC_ARITHMETIC = 4, /* 1: eq_dequant_matvec takes the plain arithmetic for grouped 4-bit
                                    codes instead of the per-group tables (same weights either way) */
-  EQ_OVR_COUNT = 5
+  EQ_OVR_MATVEC_LOOKUP = 5,  /* eq_dequant_matvec, 4-bit codes with one range per row: 1 = half of the pairs of
+                                weights from the table of pairs and half from the table of single values,
+                                2 = all from the table of single values (default: all from the table of pairs) */
+  EQ_OVR_COUNT = 6
 };
 EQ_API int eq_test_set_override(int which, int64_t value);   /* EQ_OK or EQ_E_PARAM */
 

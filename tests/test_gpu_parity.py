@@ -238,6 +238,36 @@ def test_fused_dequantize_matvec(rows, cols, bits, G, dtype):
     assert (err2 <= bound).all()
 
 
+@pytest.mark.parametrize("rows,cols,dtype", [(21, 9248, "f16"), (8, 57344, "f16"), (13, 4104, "f16"), (9, 8192 + 32, "bf16"),
+                                             (3, 32, "f16")])
+def test_per_row_matvec_lookup_variants(rows, cols, dtype, eq_override):
+    """4-bit codes with one range per row: the kernel for rows of a multiple of 32 columns with its
+    three ways of fetching weights from the tables (pairs, mixed, single values), a ragged last
+    segment, and the general kernel for the other row lengths: all within the header's bar of the
+    oracle, and the three lookups bit-identical to one another (same weights, same order of sums)."""
+    rec = eq_inputs.RECIPES["c2"] if dtype == "f16" else eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16")
+    W = eq_inputs.gen_matrix(rows, cols, rec, seed=rows + cols, device=DEV)
+    p = eqo.Params(dtype=eqo.F16 if dtype == "f16" else eqo.BF16, bits=4, group_size=0, iters=2, mode=eqo.ASYMMETRIC)
+    outs, got = run_gpu([W], p)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(cols)
+    x = torch.randn(cols, device=DEV, generator=g).to(W.dtype)
+    x_raw = raw_of(x.view(1, -1)).reshape(-1)
+    want = eqo.dequant_matvec(got[0], rows, cols, p, x_raw)
+    Wd = np.abs(eqo.widen(eqo.dequantize(got[0], rows, cols, p), p.dtype).astype(np.float64))
+    bound = 3e-5 * (Wd @ np.abs(eqo.widen(x_raw, p.dtype).astype(np.float64))) + 1e-30
+    ys = []
+    for lookup in (0, 1, 2):
+        eq_override(eqg.OVR_MATVEC_LOOKUP, lookup)
+        y = torch.full((rows,), float("nan"), dtype=torch.float32, device=DEV)
+        eqg.eq_dequant_matvec(outs[0], rows, cols, to_gpu_params(p), x, y)
+        torch.cuda.synchronize()
+        err = np.abs(y.cpu().numpy().astype(np.float64) - want)
+        assert (err <= bound).all(), (lookup, float((err / bound).max()))
+        ys.append(y)
+    assert torch.equal(ys[0].view(torch.int32), ys[1].view(torch.int32)) and torch.equal(ys[0].view(torch.int32), ys[2].view(torch.int32))
+
+
 @pytest.mark.parametrize("G", [128, 64, 1024])
 def test_grouped_matvec_tables_give_the_bits_of_the_arithmetic(G, eq_override):
     """Groups of 64 and up with 4-bit codes: the per-group tables hold exactly the weights the plain
