@@ -141,6 +141,13 @@ struct Plan {
   std::vector<size_t> cursor, row_count, row_stage, st_col, st_val, mat_stats, mat_partial;
   std::vector<int32_t> path;            // per matrix: 0 = general kernel, 1 = unit-per-lane kernel, 2 = per-channel lane kernel
   std::vector<LaneClass> classes;
+  // The CSR finish (row pointers, then the move of the staged runs) goes group by group: the matrices
+  // of each launch class in launch order, then everything else.  finish_ids lists the matrices in
+  // that order (uploaded behind the work items), a group is [first, first + count) of it.
+  struct FinishGroup { size_t first = 0, count = 0; int32_t max_rows = 0; };
+  std::vector<int32_t> finish_ids;
+  std::vector<FinishGroup> finish_groups;   // classes.size() + 1 of them
+  size_t ids = 0;                       // int32_t[n]
   std::vector<WorkItem> work;
   bool any_general = false;
   size_t total = 0;
@@ -355,12 +362,40 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     pl.classes.push_back(lc);
     k = e;
   }
+  // ---- finish groups ----
+  {
+    std::vector<char> taken((size_t)n, 0);
+    size_t k = 0;
+    for (const LaneClass& lc : pl.classes) {
+      Plan::FinishGroup g;
+      g.first = pl.finish_ids.size();
+      while (k < order.size() && cols[order[k]] == lc.cols) {
+        pl.finish_ids.push_back(order[k]);
+        g.max_rows = std::max<int32_t>(g.max_rows, (int32_t)rows[order[k]]);
+        taken[(size_t)order[k]] = 1;
+        ++k;
+      }
+      g.count = pl.finish_ids.size() - g.first;
+      pl.finish_groups.push_back(g);
+    }
+    Plan::FinishGroup rest;
+    rest.first = pl.finish_ids.size();
+    for (int32_t i = 0; i < n; ++i)
+      if (!taken[(size_t)i]) {
+        pl.finish_ids.push_back(i);
+        if (cols[i] > 0) rest.max_rows = std::max<int32_t>(rest.max_rows, (int32_t)rows[i]);
+      }
+    rest.count = pl.finish_ids.size() - rest.first;
+    pl.finish_groups.push_back(rest);
+  }
   // ---- workspace layout ----
   size_t off = 0;
   pl.descs = off;
   off = align_up(off + sizeof(MatDesc) * (size_t)n, 256);
   pl.items = off;
   off = align_up(off + sizeof(WorkItem) * pl.work.size(), 256);
+  pl.ids = off;
+  off = align_up(off + sizeof(int32_t) * (size_t)n, 256);
   pl.adam = off;
   off = align_up(off + sizeof(double) * 4 * (size_t)std::max(p->iters, 1), 256);
   for (int32_t i = 0; i < n; ++i) {
@@ -468,9 +503,40 @@ void release_pinned(PinnedBlock* b, hipStream_t st, bool copy_enqueued) {
   b->in_use = false;
 }
 
+// A second stream per device (default priority), on which the CSR finish of one launch class runs
+// while the next class's main kernel occupies the caller's stream.  Ordered by events on both sides.
+std::mutex g_aux_lock;
+hipStream_t g_aux_stream[kMaxDevices] = {};
+
+int aux_stream_of_current_device(hipStream_t* out) {
+  int device = -1;
+  EQ_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= kMaxDevices) return EQ_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> hold(g_aux_lock);
+  if (!g_aux_stream[device]) EQ_HIP(hipStreamCreateWithFlags(&g_aux_stream[device], hipStreamNonBlocking));
+  *out = g_aux_stream[device];
+  return EQ_OK;
+}
+
+// Row pointers and the move of the staged runs for one group of matrices.
+int launch_finish(const MatDesc* dmats, const int32_t* dids, const Plan::FinishGroup& g, hipStream_t st) {
+  if (g.count == 0) return EQ_OK;
+  const int32_t* ids = dids ? dids + g.first : nullptr;
+  hipLaunchKernelGGL(scan_row_counts, dim3((unsigned)g.count), dim3(kThreads), 0, st, dmats, ids);
+  EQ_HIP(hipGetLastError());
+  if (g.max_rows > 0) {
+    const int rows_per_block = kWaves * kMoveRows;
+    hipLaunchKernelGGL(move_outliers, dim3((unsigned)((g.max_rows + rows_per_block - 1) / rows_per_block), (unsigned)g.count),
+                       dim3(kThreads), 0, st, dmats, ids);
+    EQ_HIP(hipGetLastError());
+  }
+  return EQ_OK;
+}
+
+// dids: the plan's finish_ids on the device, or null for a single matrix (its id is the block index).
 template <int DT>
-int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const std::vector<MatDesc>& h, const Plan& pl,
-               const KParams& kp, hipStream_t st) {
+int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const int32_t* dids, const std::vector<MatDesc>& h,
+               const Plan& pl, const KParams& kp, hipStream_t st) {
   int32_t max_rows = 0, gen_rows = 0, gen_cols = 0;
   for (const MatDesc& m : h) {
     if (m.cols == 0 || m.rows == 0) continue;
@@ -490,42 +556,75 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const st
       EQ_HIP(hipGetLastError());
     }
   }
-  for (const LaneClass& lc : pl.classes) {
+  // The finish of a group is hidden under the main kernel of the next one (it moves a few GB and
+  // would otherwise stand alone at the end): it goes to the second stream whenever another main
+  // kernel follows on the caller's stream.
+  const bool have_general = gen_rows > 0;
+  hipStream_t aux = nullptr;
+  bool aux_used = false;
+  int rc = EQ_OK;
+  for (size_t ci = 0; ci < pl.classes.size() && rc == EQ_OK; ++ci) {
+    const LaneClass& lc = pl.classes[ci];
     if (lc.n_items == 0) continue;
     // the kernels of each family are instantiated in a translation unit of their own (eq_launch.h)
     const LaneKernel lk = (lc.kind == 3 || lc.kind == 6) ? pick_rtn_kernel<DT>(lc)
                           : (lc.kind == 2 || lc.kind == 5 || lc.kind == 7) ? pick_channel_kernel<DT>(lc) : pick_units_kernel<DT>(lc);
     const void* fn = lk.fn;
     const LaneLaunch launch = lk.launch;
-    if (!fn) return EQ_E_UNSUPPORTED;
+    if (!fn) { rc = EQ_E_UNSUPPORTED; break; }
     const size_t lds_bytes = lk.lds_bytes ? lk.lds_bytes : lc.lds_bytes;
-    if (lds_bytes > 65536)
-      EQ_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    if (lds_bytes > 65536 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) {
+      g_last_hip_error = (int)hipGetLastError();
+      rc = EQ_E_HIP;
+      break;
+    }
     {
       ScopedKernelTimer tm(st);
       launch(lc, dmats, ditems, kp, st);
     }
-    EQ_HIP(hipGetLastError());
-  }
-  if (gen_rows > 0) {
-    const size_t lds = 256 + (size_t)gen_cols * 2 + (size_t)gen_cols / 8;
-    if (lds > 65536)
-      EQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_rows_generic<DT>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    {
-      ScopedKernelTimer tm(st);
-      hipLaunchKernelGGL(quantize_rows_generic<DT>, dim3(gen_rows, n), dim3(kThreads), lds, st, dmats, kp);
+    if (hipGetLastError() != hipSuccess) { rc = EQ_E_HIP; break; }
+    bool more_main = have_general;
+    for (size_t cj = ci + 1; cj < pl.classes.size(); ++cj) more_main = more_main || pl.classes[cj].n_items != 0;
+    hipEvent_t ev = nullptr;
+    if (dids && more_main && (aux || aux_stream_of_current_device(&aux) == EQ_OK) &&
+        hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) {
+      const bool ok = hipEventRecord(ev, st) == hipSuccess && hipStreamWaitEvent(aux, ev, 0) == hipSuccess;
+      (void)hipEventDestroy(ev);                       // released once it has completed
+      if (ok) {
+        aux_used = true;
+        rc = launch_finish(dmats, dids, pl.finish_groups[ci], aux);
+        continue;
+      }
     }
-    EQ_HIP(hipGetLastError());
+    rc = launch_finish(dmats, dids, pl.finish_groups[ci], st);
   }
-  hipLaunchKernelGGL(scan_row_counts, dim3(n), dim3(kThreads), 0, st, dmats);
-  EQ_HIP(hipGetLastError());
-  if (max_rows > 0) {
-    const int rows_per_block = kWaves * kMoveRows;
-    hipLaunchKernelGGL(move_outliers, dim3((max_rows + rows_per_block - 1) / rows_per_block, n), dim3(kThreads), 0, st, dmats);
-    EQ_HIP(hipGetLastError());
+  if (rc == EQ_OK && gen_rows > 0) {
+    const size_t lds = 256 + (size_t)gen_cols * 2 + (size_t)gen_cols / 8;
+    if (lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_rows_generic<DT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      rc = EQ_E_HIP;
+    if (rc == EQ_OK) {
+      {
+        ScopedKernelTimer tm(st);
+        hipLaunchKernelGGL(quantize_rows_generic<DT>, dim3(gen_rows, n), dim3(kThreads), lds, st, dmats, kp);
+      }
+      if (hipGetLastError() != hipSuccess) rc = EQ_E_HIP;
+    }
   }
-  return EQ_OK;
+  if (rc == EQ_OK) rc = launch_finish(dmats, dids, pl.finish_groups.back(), st);
+  // whatever went to the second stream is part of this call: the caller's stream waits for it
+  if (aux_used) {
+    hipEvent_t ev = nullptr;
+    bool joined = false;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) {
+      joined = hipEventRecord(ev, aux) == hipSuccess && hipStreamWaitEvent(st, ev, 0) == hipSuccess;
+      (void)hipEventDestroy(ev);
+    }
+    if (!joined) {
+      (void)hipStreamSynchronize(aux);                 // no event: wait on the host instead
+    }
+  }
+  return rc;
 }
 
 // Argument checks and the descriptor shared by the two consumers of a quantized matrix.
@@ -800,20 +899,23 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   // Descriptors, work items and Adam's table lead the workspace in that order: they are packed
   // with the same offsets into one pinned host block and go up in a single copy.
   const std::vector<double> tab = make_adam_table(p);
+  static_assert(sizeof(int32_t) == 4, "");
   const size_t head_bytes = pl.adam + sizeof(double) * tab.size();
   PinnedBlock* blk = acquire_pinned(head_bytes);
   if (!blk) return EQ_E_HIP;
   unsigned char* hb = static_cast<unsigned char*>(blk->host);
   std::memcpy(hb + pl.descs, h.data(), sizeof(MatDesc) * (size_t)n);
   if (!pl.work.empty()) std::memcpy(hb + pl.items, pl.work.data(), sizeof(WorkItem) * pl.work.size());
+  std::memcpy(hb + pl.ids, pl.finish_ids.data(), sizeof(int32_t) * pl.finish_ids.size());
   std::memcpy(hb + pl.adam, tab.data(), sizeof(double) * tab.size());
   hipError_t ce = hipMemcpyAsync(ws, hb, head_bytes, hipMemcpyHostToDevice, st);
   release_pinned(blk, st, ce == hipSuccess);
   EQ_HIP(ce);
   KParams kp = make_kparams(p);
   kp.adam_tab = dev(dtab);
-  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, h, pl, kp, st)
-                            : launch_all<EQ_BF16>(n, dmats, ditems, h, pl, kp, st);
+  const int32_t* dids = reinterpret_cast<const int32_t*>(ws + pl.ids);
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, dids, h, pl, kp, st)
+                            : launch_all<EQ_BF16>(n, dmats, ditems, dids, h, pl, kp, st);
 }
 
 int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,
@@ -856,8 +958,8 @@ int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_
   EQ_HIP(hipGetLastError());
   KParams kp = make_kparams(p);
   kp.adam_tab = su.dtab;
-  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(1, su.dmats, su.ditems, h, pl, kp, st)
-                            : launch_all<EQ_BF16>(1, su.dmats, su.ditems, h, pl, kp, st);
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(1, su.dmats, su.ditems, nullptr, h, pl, kp, st)
+                            : launch_all<EQ_BF16>(1, su.dmats, su.ditems, nullptr, h, pl, kp, st);
 }
 
 int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,

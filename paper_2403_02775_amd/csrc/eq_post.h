@@ -20,9 +20,10 @@ __global__ void reset_state(const MatDesc* __restrict__ mats, int n) {
 }
 
 // out_row_ptr = exclusive prefix sum of the per-row outlier counts.  One workgroup per matrix.
-__global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __restrict__ mats) {
+// `ids` (may be null): the matrices this launch looks after, one per workgroup.
+__global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __restrict__ mats, const int32_t* __restrict__ ids) {
   __shared__ uint32_t wtot[kWaves];
-  const MatDesc md = mats[blockIdx.x];
+  const MatDesc md = mats[ids ? ids[blockIdx.x] : (int32_t)blockIdx.x];
   if (md.cols == 0) return;
   const uint32_t lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   uint32_t running = 0;
@@ -58,8 +59,8 @@ __global__ __launch_bounds__(kThreads) void scan_row_counts(const MatDesc* __res
 // entries take further passes).
 constexpr int kMoveRows = 16;
 
-__global__ __launch_bounds__(kThreads) void move_outliers(const MatDesc* __restrict__ mats) {
-  const MatDesc md = mats[blockIdx.y];
+__global__ __launch_bounds__(kThreads) void move_outliers(const MatDesc* __restrict__ mats, const int32_t* __restrict__ ids) {
+  const MatDesc md = mats[ids ? ids[blockIdx.y] : (int32_t)blockIdx.y];
   const int64_t row0 = ((int64_t)blockIdx.x * kWaves + threadIdx.x / kWave) * kMoveRows;
   if (row0 >= md.rows || md.cols == 0) return;
   const uint32_t lane = threadIdx.x & (kWave - 1);
