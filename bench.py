@@ -199,8 +199,9 @@ def bench_matvec(args):
     codes = torch.randint(-2 ** 31, 2 ** 31 - 1, (rows, cols * 4 // 32), dtype=torch.int32, device=dev, generator=g)
     scales = torch.rand((rows, upr), device=dev, generator=g) * 0.01 + 0.001
     zps = torch.full((rows, upr), 7, dtype=torch.uint8, device=dev)
-    k = max(1, int(round(cols * args.outlier_pct / 100.0)))
-    stride = cols // k                              # one outlier in every stride-wide stretch: ascending, no duplicates
+    k = int(round(cols * args.outlier_pct / 100.0)) if args.outlier_pct > 0 else 0   # 0: no outlier list at all
+    k = max(1, k) if args.outlier_pct > 0 else 0
+    stride = cols // max(k, 1)                      # one outlier in every stride-wide stretch: ascending, no duplicates
     col = (torch.arange(k, device=dev, dtype=torch.int32) * stride).view(1, -1) + \
         torch.randint(stride, (rows, k), device=dev, generator=g, dtype=torch.int32)
     col = col.contiguous()
