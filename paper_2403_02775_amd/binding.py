@@ -267,7 +267,9 @@ def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tens
 
 
 # ---- hooks for tests and measurements (csrc/eq_testing.h; not part of the C ABI) ----------------
-OVR_UNITS_PER_ITEM, OVR_FORCE_GENERAL, OVR_RTN_THREADS, OVR_CHANNEL_KERNEL, OVR_MATVEC_ARITHMETIC, OVR_MATVEC_LOOKUP = range(6)
+(OVR_UNITS_PER_ITEM, OVR_FORCE_GENERAL, OVR_RTN_THREADS, OVR_CHANNEL_KERNEL, OVR_MATVEC_ARITHMETIC, OVR_MATVEC_LOOKUP,
+ OVR_SORTED_ROWS, OVR_SORT_CHUNK_ROWS) = range(8)
+OVR_COUNT = 8
 
 
 class override:

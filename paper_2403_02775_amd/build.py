@@ -26,7 +26,7 @@ HIPCC_FLAGS = [
 ]
 
 # (source file, EQ_TU_DT or None): EQ_TU_DT is the input type a family unit is instantiated for
-UNITS = [("easyquant_api.hip", None)] + [(f, dt) for f in ("eq_tu_units.hip", "eq_tu_channels.hip", "eq_tu_rtn.hip")
+UNITS = [("easyquant_api.hip", None)] + [(f, dt) for f in ("eq_tu_units.hip", "eq_tu_channels.hip", "eq_tu_rtn.hip", "eq_tu_sorted.hip")
                                          for dt in (0, 1)]
 
 

@@ -149,9 +149,22 @@ struct Plan {
   std::vector<FinishGroup> finish_groups;   // classes.size() + 1 of them
   size_t ids = 0;                       // int32_t[n]
   std::vector<WorkItem> work;
+  // sorted evaluation of per-channel rows (eq_sorted.h): the segments of all chunks (uploaded behind
+  // the ids), the chunks, the per-row ranges of each matrix and the one region that holds a chunk's records
+  std::vector<SortSeg> segs;
+  std::vector<SortChunk> chunks;
+  size_t segs_off = 0;
+  std::vector<size_t> range;            // per matrix: float[rows], or 0
+  size_t sort_ws = 0, sort_ws_bytes = 0;
   bool any_general = false;
   size_t total = 0;
 };
+
+// Records of the sorted evaluation that a launch may hold at once: the rows of a class are cut into
+// chunks of at most this many bytes (some 87 000 rows of 8192 elements: enough wavefronts of
+// sorted_iterate to fill the chip several times over).
+constexpr size_t kSortBudgetBytes = (size_t)2 << 30;
+constexpr int64_t kSortMinCols = 2048;
 
 int64_t clamp_capacity(int64_t c) { return c < 0 ? 0 : (c > 0xFFFFFFFEll ? 0xFFFFFFFEll : c); }
 
@@ -183,9 +196,11 @@ double lane_use_of_rounds(int64_t upr, int64_t nt, int64_t slots) {
   return (double)used / (double)offered;
 }
 
-Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* cap, const eq_params* p) {
+Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* cap, const eq_params* p,
+               bool allow_sorted) {
   Plan pl;
   pl.path.assign((size_t)n, 0);
+  std::vector<char> wants_range((size_t)n, 0);
   // ---- launch plan ----
   std::vector<int32_t> order;
   const bool force_general = override_of(EQ_OVR_FORCE_GENERAL) == 1;   // test / measurement override
@@ -213,7 +228,11 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     lc.cols = (int32_t)c;
     lc.upr = (int32_t)upr;
     const bool chan_keep128 = override_of(EQ_OVR_CHANNEL_KERNEL) == 128;
-    const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && p->iters == 0 && !chan_keep128;
+    // one range per row, at most 4 bits, optimisation steps: Adam runs on the sorted rows (eq_sorted.h)
+    // and the kernel without optimisation steps emits at the ranges it leaves
+    const bool chan_sorted = pl.path[(size_t)order[k]] == 2 && p->iters > 0 && p->bits <= 4 && allow_sorted &&
+                             !chan_keep128 && c >= kSortMinCols && override_of(EQ_OVR_SORTED_ROWS) != 1;
+    const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && (p->iters == 0 || chan_sorted) && !chan_keep128;
     if (pl.path[(size_t)order[k]] == 2 && !chan_rtn) {
       // per-channel: a round is floor(256 / segments) whole rows; items are multiples of that
       lc.kind = 2;
@@ -250,10 +269,47 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       k = e;
       continue;
     }
-    if (p->iters == 0) {
+    if (p->iters == 0 || chan_sorted) {
       // no optimisation steps: the HBM-bound kernel, one round per batch of 16 / K rows
       // (per-channel rows: the same kernel with one range per row)
       lc.kind = chan_rtn ? 6 : 3;
+      if (chan_sorted) {
+        lc.sorted = true;
+        lc.first_chunk = pl.chunks.size();
+        const size_t rec = sort_record_bytes(c);
+        int64_t chunk_rows = std::max<int64_t>(4, (int64_t)(kSortBudgetBytes / rec) & ~(int64_t)3);
+        if (override_of(EQ_OVR_SORT_CHUNK_ROWS) > 0)
+          chunk_rows = std::max<int64_t>(4, std::min<int64_t>(chunk_rows, override_of(EQ_OVR_SORT_CHUNK_ROWS)) & ~(int64_t)3);
+        SortChunk ch;
+        ch.first_seg = pl.segs.size();
+        for (size_t j = k; j < e; ++j) {
+          const int32_t m = order[j];
+          wants_range[(size_t)m] = 1;
+          for (int64_t r = 0; r < rows[m];) {
+            if (ch.rows == chunk_rows) {
+              ch.n_segs = pl.segs.size() - ch.first_seg;
+              pl.chunks.push_back(ch);
+              ch = SortChunk();
+              ch.first_seg = pl.segs.size();
+            }
+            const int64_t take = std::min<int64_t>(rows[m] - r, chunk_rows - ch.rows);
+            SortSeg sg;
+            sg.mat = m; sg.row0 = (int32_t)r; sg.nrows = (int32_t)take;
+            sg.first_group = (int32_t)ch.groups;
+            sg.first_row = ch.rows;
+            sg.ws_off = (int64_t)((size_t)ch.rows * rec);
+            pl.segs.push_back(sg);
+            ch.rows += take;
+            ch.groups += (take + 3) / 4;
+            r += take;
+          }
+        }
+        ch.n_segs = pl.segs.size() - ch.first_seg;
+        if (ch.n_segs) pl.chunks.push_back(ch);
+        lc.n_chunks = pl.chunks.size() - lc.first_chunk;
+        for (size_t q = lc.first_chunk; q < pl.chunks.size(); ++q)
+          pl.sort_ws_bytes = std::max(pl.sort_ws_bytes, (size_t)pl.chunks[q].rows * rec);
+      }
       // longer rows take four wavefronts (two workgroups per compute unit, 15 % faster on rows of
       // 22016 than one of eight);
       // one-wavefront workgroups for rows of up to 8192 (a row, or a batch of short rows, per wavefront:
@@ -396,6 +452,8 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
   off = align_up(off + sizeof(WorkItem) * pl.work.size(), 256);
   pl.ids = off;
   off = align_up(off + sizeof(int32_t) * (size_t)n, 256);
+  pl.segs_off = off;
+  off = align_up(off + sizeof(SortSeg) * pl.segs.size(), 256);
   pl.adam = off;
   off = align_up(off + sizeof(double) * 4 * (size_t)std::max(p->iters, 1), 256);
   for (int32_t i = 0; i < n; ++i) {
@@ -413,7 +471,14 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       pl.mat_stats.push_back(0);
       pl.mat_partial.push_back(0);
     }
+    if (wants_range[(size_t)i]) {
+      pl.range.push_back(off);       off = align_up(off + 4 * r, 256);
+    } else {
+      pl.range.push_back(0);
+    }
   }
+  pl.sort_ws = off;
+  off = align_up(off + pl.sort_ws_bytes, 256);
   pl.total = off;
   return pl;
 }
@@ -535,8 +600,8 @@ int launch_finish(const MatDesc* dmats, const int32_t* dids, const Plan::FinishG
 
 // dids: the plan's finish_ids on the device, or null for a single matrix (its id is the block index).
 template <int DT>
-int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const int32_t* dids, const std::vector<MatDesc>& h,
-               const Plan& pl, const KParams& kp, hipStream_t st) {
+int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const int32_t* dids, const SortSeg* dsegs,
+               unsigned char* dsort, const std::vector<MatDesc>& h, const Plan& pl, const KParams& kp, hipStream_t st) {
   int32_t max_rows = 0, gen_rows = 0, gen_cols = 0;
   for (const MatDesc& m : h) {
     if (m.cols == 0 || m.rows == 0) continue;
@@ -580,7 +645,30 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
     }
     {
       ScopedKernelTimer tm(st);
-      launch(lc, dmats, ditems, kp, st);
+      KParams kq = kp;
+      if (lc.sorted) {
+        // chunk by chunk: the records, then Adam on them; the ranges go to MatDesc::range
+        const SortKernels sk = pick_sorted_kernels<DT>(lc);
+        if (!sk.prepare || !sk.iterate || !dsegs || !dsort) { rc = EQ_E_UNSUPPORTED; break; }
+        if (sk.prepare_lds > 160u * 1024u - 64u) { rc = EQ_E_UNSUPPORTED; break; }
+        if (sk.prepare_lds > 65536 &&
+            hipFuncSetAttribute(sk.prepare_fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk.prepare_lds) != hipSuccess) {
+          g_last_hip_error = (int)hipGetLastError();
+          rc = EQ_E_HIP;
+          break;
+        }
+        for (size_t q = lc.first_chunk; q < lc.first_chunk + lc.n_chunks; ++q) {
+          const SortChunk& ch = pl.chunks[q];
+          SortLaunchArgs a;
+          a.mats = dmats; a.segs = dsegs + ch.first_seg; a.nsegs = (int32_t)ch.n_segs;
+          a.rows = ch.rows; a.groups = ch.groups; a.ws = dsort;
+          sk.prepare(lc, a, kp, st);
+          sk.iterate(lc, a, kp, st);
+        }
+        if (hipGetLastError() != hipSuccess) { rc = EQ_E_HIP; break; }
+        kq.range_given = 1;
+      }
+      launch(lc, dmats, ditems, kq, st);
     }
     if (hipGetLastError() != hipSuccess) { rc = EQ_E_HIP; break; }
     bool more_main = have_general;
@@ -659,7 +747,7 @@ int make_deq_desc(const eq_qmatrix* q, int64_t rows, int64_t cols, const eq_para
 
 // Host-visible checks of a batch and its launch plan (no HIP call).
 int check_and_plan(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols, const int64_t* ld,
-                   const eq_params* p, const eq_qmatrix* outs, Plan& pl) {
+                   const eq_params* p, const eq_qmatrix* outs, bool allow_sorted, Plan& pl) {
   if (!W || !rows || !cols || !ld || !p || !outs) return EQ_E_NULL;
   if (!params_ok(p)) return EQ_E_PARAM;
   std::vector<int64_t> caps((size_t)n);
@@ -678,7 +766,7 @@ int check_and_plan(int32_t n, const void* const* W, const int64_t* rows, const i
       return EQ_E_ALIGN;
     caps[(size_t)i] = o.out_capacity;
   }
-  pl = make_plan(n, rows, cols, caps.data(), p);
+  pl = make_plan(n, rows, cols, caps.data(), p, allow_sorted);
   return EQ_OK;
 }
 
@@ -702,6 +790,7 @@ int fill_descriptors(int32_t n, const void* const* W, const int64_t* rows, const
       m.mat_stats = dev(reinterpret_cast<double*>(ws + pl.mat_stats[(size_t)i]));
       m.mat_partial = dev(reinterpret_cast<double*>(ws + pl.mat_partial[(size_t)i]));
     }
+    if (pl.range[(size_t)i]) m.range = dev(reinterpret_cast<float*>(ws + pl.range[(size_t)i]));
     m.ld = ld[i];
     m.capacity = clamp_capacity(o.out_capacity);
     m.rows = (int32_t)rows[i];
@@ -811,7 +900,7 @@ int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, 
   if (!params_ok(p)) return EQ_E_PARAM;
   for (int32_t i = 0; i < n; ++i)
     if (rows[i] < 0 || cols[i] < 0 || rows[i] > 0x7FFFFFFF) return EQ_E_SHAPE;
-  const Plan pl = make_plan(n, rows, cols, out_capacity, p);
+  const Plan pl = make_plan(n, rows, cols, out_capacity, p, true);
   for (size_t c = 0; c < pl.classes.size(); ++c) {
     const LaneClass& lc = pl.classes[c];
     for (size_t i = lc.first_item; i < lc.first_item + lc.n_items && (int64_t)i < max_items; ++i) {
@@ -876,7 +965,7 @@ size_t eq_workspace_bytes(int32_t n, const int64_t* rows, const int64_t* cols, c
   if (!params_ok(p)) return 0;
   for (int32_t i = 0; i < n; ++i)
     if (rows[i] < 0 || cols[i] < 0 || rows[i] > 0x7FFFFFFF) return 0;
-  return make_plan(n, rows, cols, out_capacity, p).total + 256;
+  return make_plan(n, rows, cols, out_capacity, p, true).total + 256;
 }
 
 int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, const int64_t* cols, const int64_t* ld,
@@ -886,7 +975,7 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   if (n == 0) return EQ_OK;
   Plan pl;
   std::vector<MatDesc> h;
-  int rc = check_and_plan(n, W, rows, cols, ld, p, outs, pl);
+  int rc = check_and_plan(n, W, rows, cols, ld, p, outs, true, pl);
   if (rc != EQ_OK) return rc;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < pl.total) return EQ_E_WORKSPACE;
   unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -907,6 +996,7 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   std::memcpy(hb + pl.descs, h.data(), sizeof(MatDesc) * (size_t)n);
   if (!pl.work.empty()) std::memcpy(hb + pl.items, pl.work.data(), sizeof(WorkItem) * pl.work.size());
   std::memcpy(hb + pl.ids, pl.finish_ids.data(), sizeof(int32_t) * pl.finish_ids.size());
+  if (!pl.segs.empty()) std::memcpy(hb + pl.segs_off, pl.segs.data(), sizeof(SortSeg) * pl.segs.size());
   std::memcpy(hb + pl.adam, tab.data(), sizeof(double) * tab.size());
   hipError_t ce = hipMemcpyAsync(ws, hb, head_bytes, hipMemcpyHostToDevice, st);
   release_pinned(blk, st, ce == hipSuccess);
@@ -914,8 +1004,10 @@ int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* rows, cons
   KParams kp = make_kparams(p);
   kp.adam_tab = dev(dtab);
   const int32_t* dids = reinterpret_cast<const int32_t*>(ws + pl.ids);
-  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, dids, h, pl, kp, st)
-                            : launch_all<EQ_BF16>(n, dmats, ditems, dids, h, pl, kp, st);
+  const SortSeg* dsegs = reinterpret_cast<const SortSeg*>(ws + pl.segs_off);
+  unsigned char* dsort = ws + pl.sort_ws;
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(n, dmats, ditems, dids, dsegs, dsort, h, pl, kp, st)
+                            : launch_all<EQ_BF16>(n, dmats, ditems, dids, dsegs, dsort, h, pl, kp, st);
 }
 
 int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,
@@ -923,7 +1015,8 @@ int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_
   if (!out) return EQ_E_NULL;
   Plan pl;
   std::vector<MatDesc> h;
-  int rc = check_and_plan(1, &W, &rows, &cols, &ld, p, out, pl);
+  // (the sorted evaluation of per-channel rows needs gigabytes of records: not from this entry point)
+  int rc = check_and_plan(1, &W, &rows, &cols, &ld, p, out, false, pl);
   if (rc != EQ_OK) return rc;
   if (pl.total > (size_t)EQ_STATIC_SCRATCH_BYTES) return EQ_E_SCRATCH;
   if (p->iters > kNoallocMaxIters) return EQ_E_UNSUPPORTED;
@@ -958,8 +1051,8 @@ int eq_quantize_matrix_noalloc(const void* W, int64_t rows, int64_t cols, int64_
   EQ_HIP(hipGetLastError());
   KParams kp = make_kparams(p);
   kp.adam_tab = su.dtab;
-  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(1, su.dmats, su.ditems, nullptr, h, pl, kp, st)
-                            : launch_all<EQ_BF16>(1, su.dmats, su.ditems, nullptr, h, pl, kp, st);
+  return p->dtype == EQ_F16 ? launch_all<EQ_F16>(1, su.dmats, su.ditems, nullptr, nullptr, nullptr, h, pl, kp, st)
+                            : launch_all<EQ_BF16>(1, su.dmats, su.ditems, nullptr, nullptr, nullptr, h, pl, kp, st);
 }
 
 int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld, const eq_params* p,

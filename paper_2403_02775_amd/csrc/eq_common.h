@@ -47,6 +47,7 @@ struct MatDesc {
   EQ_GLOBAL uint16_t* st_val;
   EQ_GLOBAL double* mat_stats;            // [0] mean, [1] sigma of the whole matrix (EQ_STAT_MATRIX)
   EQ_GLOBAL double* mat_partial;          // per-workgroup partial sums of the pre-pass
+  EQ_GLOBAL float* range;                 // per row: the range chosen by the sorted evaluation (eq_sorted.h), else null
   int64_t ld;
   int64_t capacity;
   int32_t rows, cols;
@@ -62,7 +63,7 @@ struct KParams {
   int32_t L;        // 2^bits - 1
   int32_t zsym;     // 2^(bits-1) - 1
   float D;          // level the range maps to: zsym (symmetric) or L (asymmetric)
-  float pad_;
+  int32_t range_given;   // the kernel without optimisation steps emits at MatDesc::range[row] instead of the initial range
   double n;         // threshold of Eq. 3
   double lr, b1, b2, eps;
   double rD64;      // RN(1 / D) in binary64
@@ -70,6 +71,27 @@ struct KParams {
   float pad2_;
   const EQ_GLOBAL double* adam_tab;   // device: per step t (0-based) {1 - b1^(t+1), RN(1 / that), 1 - b2^(t+1), RN(1 / that)}
 };
+
+// ---- the sorted evaluation of rows with one range each (eq_sorted.h) ----
+// A run of rows of one matrix whose records lie one after the other in the workspace of a launch.
+struct SortSeg {
+  int32_t mat, row0, nrows;
+  int32_t first_group;      // index of the run's first group of 4 rows among the launch's groups
+  int64_t first_row;        // index of its first row among the launch's rows
+  int64_t ws_off;           // byte offset of its first record
+};
+// A row's record: header, the cols 16-bit values in ascending order (outliers as 0), and the exact
+// binary64 sums of the first 8 j values for j = 0 .. cols / 8.
+struct SortRecHeader {
+  float r0;                 // initial range
+  int32_t z;                // zero-point
+  uint32_t flags;           // kRecExactSums | kRecSorted
+  uint32_t pad;
+};
+constexpr size_t kSortRecHeader = 32;
+__host__ __device__ inline size_t sort_record_bytes(int64_t cols) {
+  return (kSortRecHeader + (size_t)cols * 2 + ((size_t)cols / 8 + 1) * 8 + 63) & ~(size_t)63;
+}
 
 // Relaxed device-scope atomics on global memory (the HIP wrappers take generic pointers).
 __device__ __forceinline__ unsigned long long global_atomic_add(EQ_GLOBAL unsigned long long* p, unsigned long long v) {

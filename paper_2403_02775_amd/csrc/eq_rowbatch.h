@@ -201,7 +201,9 @@ __device__ __forceinline__ void batch_issue_loads(const MatDesc& md, int64_t row
 // overwrite v.  The rows must be whole units (cols a multiple of 128) and ch0 a multiple of 16.
 // mask_area: one byte per chunk of the batch, 16-byte aligned, for layouts that do not keep the
 // mask bytes in the pool (ignored otherwise).
-template <int DT, int NT, int RB, int K, class Layout, bool WM = false, class Hook>
+// WRITE = false: statistics, mask and zeroing only; nothing goes to the staging list (a caller that
+// only needs the normal values, the list being written by a later pass over the same rows).
+template <int DT, int NT, int RB, int K, class Layout, bool WM = false, bool WRITE = true, class Hook>
 __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KParams& kp, int64_t row0, int nrows,
                                                   unsigned char* pool, uint32_t ch0, unsigned char* mask_area,
                                                   BatchScratch<RB, NT / kWave>* sc, const uint4 (&v)[RB][K],
@@ -439,29 +441,22 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
           sigma = sqrt(block_sum(q, sc->dred) / cnt);
         }
         const double thr = kp.n * sigma;
+        // a row that took the exact path from the start (no chunk test was made): every chunk of the
+        // thread; a row with an element inside the band: its candidate chunks anew (every other chunk
+        // lies strictly inside the band's lower end, where the fast and the exact decision agree).
+        // A constant scope has no outliers.
+        uint32_t todo = (cand >> (r * K)) & ((1u << K) - 1u);
         if ((slow_rows >> r) & 1u) {
-          // the row took the exact path from the start (no chunk test was made): every mask byte of
-          // the row (a constant scope has no outliers)
-#pragma unroll 1
-          for (int i = 0; i < K; ++i) {
-            const uint32_t ch = chunk_of<NT, WM>(i, part_c0);
-            if (ch < part_c1) {
-              const uint32_t at = ch0 + (uint32_t)r * nchunks + ch;
-              const uint32_t mm = sigma > 0.0 ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(at)), mu, thr) : 0u;
-              mb[Layout::mask_off(at)] = (unsigned char)mm;
-            }
-          }
-        } else {
-          // the row has an element inside the band: its candidate chunks anew (every other chunk lies
-          // strictly inside the band's lower end, where the fast and the exact decision agree)
-          uint32_t todo = (cand >> (r * K)) & ((1u << K) - 1u);
-          while (todo) {
-            const int i = __ffs((int)todo) - 1;
-            todo &= todo - 1;
-            const uint32_t at = ch0 + (uint32_t)r * nchunks + chunk_of<NT, WM>(i, part_c0);
-            const uint32_t mm = sigma > 0.0 ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(at)), mu, thr) : 0u;
-            mb[Layout::mask_off(at)] = (unsigned char)mm;
-          }
+          todo = 0;
+#pragma unroll
+          for (int i = 0; i < K; ++i) todo |= chunk_of<NT, WM>(i, part_c0) < part_c1 ? 1u << i : 0u;
+        }
+        while (todo) {
+          const int i = __ffs((int)todo) - 1;
+          todo &= todo - 1;
+          const uint32_t at = ch0 + (uint32_t)r * nchunks + chunk_of<NT, WM>(i, part_c0);
+          const uint32_t mm = sigma > 0.0 ? chunk_mask<DT>(*reinterpret_cast<const uint4*>(pool + Layout::off(at)), mu, thr) : 0u;
+          mb[Layout::mask_off(at)] = (unsigned char)mm;
         }
       }
     }
@@ -525,7 +520,7 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   unsigned long long b = 0;
   if (tid == 0) {
     sc->pre[nslots] = total;
-    if (total) b = global_atomic_add(md.cursor, (unsigned long long)total);
+    if (WRITE && total) b = global_atomic_add(md.cursor, (unsigned long long)total);
   }
   after_reservation_issued();
   if (tid == 0) sc->base = b;            // nothing but this LDS store after the first use of b (each global
@@ -533,7 +528,7 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
   __syncthreads();
   b = sc->base;
   // a row fits if its last entry does: rows come in order, so everything in front of it fits as well
-  if (tid < (uint32_t)nrows) {
+  if (WRITE && tid < (uint32_t)nrows) {
     const uint32_t c0 = sc->pre[tid * upr], c1 = sc->pre[(tid + 1u) * upr];
     const bool fits = b + c1 <= (unsigned long long)md.capacity;
     md.row_count[row0 + tid] = c1 - c0;
@@ -548,7 +543,7 @@ __device__ __forceinline__ void stage_loaded_rows(const MatDesc& md, const KPara
     // (floor(s / upr) as a multiply-high: exact for s < 2^20, 2 <= upr <= 4096; no division sequence)
     const uint32_t r = RB == 1 ? 0u : upr == 1u ? s : __umulhi(s, 0xFFFFFFFFu / upr + 1u);   // row of the batch,
     const uint32_t u = s - r * upr;                                                           // unit of the row
-    const bool fits = b + sc->pre[(r + 1u) * upr] <= (unsigned long long)md.capacity;
+    const bool fits = WRITE && b + sc->pre[(r + 1u) * upr] <= (unsigned long long)md.capacity;
     unsigned long long pos = b + sc->pre[s];
     const uint32_t words[4] = {m.x, m.y, m.z, m.w};
 #pragma unroll

@@ -86,11 +86,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(rtn_waves_pe
     int z;
     const bool active = init_unit(kp, vmin, vmax, r0, z);
     float s32, inv;
-    scale_of(kp, active ? r0 : kp.D, s32, inv);            // an all-zero unit keeps s = 1
+    // the range: the initial one (an all-zero unit keeps s = 1), or the one an optimisation that ran
+    // before this kernel left for the row
+    const bool given = PER_ROW && kp.range_given;
+    scale_of(kp, given ? md.range[row0 + my_row] : active ? r0 : kp.D, s32, inv);
     if (valid) {
       // symmetric mode at the initial range: |x| <= r0, so no level leaves [-D, D] and Eq. 1's clamp
       // is the identity (uniform branch)
-      if (kp.mode == EQ_SYMMETRIC) emit_codes_to_slot<DT, true>(kp, slot, inv, z);
+      if (kp.mode == EQ_SYMMETRIC && !given) emit_codes_to_slot<DT, true>(kp, slot, inv, z);
       else emit_codes_to_slot<DT, false>(kp, slot, inv, z);
       if (!PER_ROW) {
         const int64_t gu = row0 * (int64_t)upr + slot_i;

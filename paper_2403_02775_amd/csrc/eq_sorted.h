@@ -1,0 +1,427 @@
+// One range per row (the paper's per-channel setting, Sec. 5) with the two sums of Eq. 2 taken from
+// the row's SORTED normal values instead of from every element.
+//
+// The level of an element, rint(x / s) clamped to [clo, chi] (Eq. 1), never decreases with x.  In
+// ascending order the elements with level <= l are therefore a prefix of the row, of length n_l,
+// and with P[n] = x_(1) + ... + x_(n) (the n smallest values), summation by parts gives
+//     A = sum c^2 = chi^2 N - sum_{l = clo}^{chi - 1} (2 l + 1) n_l
+//     B = sum x c = chi P[N] - sum_{l = clo}^{chi - 1} P[n_l]
+// over the 2^bits - 1 boundaries between neighbouring levels.  One optimisation step then costs a
+// search for each n_l and one prefix sum apiece, whatever the row's length, instead of a visit of all
+// N elements; n_l moves by a few positions per step, so the search starts where it ended last time.
+// The sums are the same integers (A) and the same exactly representable binary64 values (B) as the
+// direct evaluation gives, the scalar recurrence is the one of eq_common.h: same bits.
+//
+//   sorted_prepare : stages a row as every other kernel does (eq_rowbatch.h: statistics, outlier
+//                    mask, outliers replaced by 0; nothing written to the outlier list here), then
+//                    sorts the 16-bit values in LDS (counting sort into 2048 value-linear buckets,
+//                    ranks inside a bucket by counting) and writes a record per row to the
+//                    workspace: header, sorted values, exact prefix sums at every 8th position.
+//   sorted_iterate : 16 lanes per row, one per boundary, 4 rows per wavefront; Adam on the range
+//                    (Algorithm 1, second step); leaves the chosen range of every row.
+// The codes, scales, zero-points and the outlier list are then written by the kernel without
+// optimisation steps (eq_rtn128.h), which takes the range it is given instead of the initial one.
+//
+// A row whose prefix sums might not be exact in binary64 (values spread over more than some 35 binary
+// orders of magnitude), or whose values pile up in one bucket (hundreds of equal values), is
+// evaluated element by element from its record instead, like the general kernel does.
+#pragma once
+
+#include "eq_fused128.h"
+
+namespace eq {
+
+constexpr int kSortThreads = 256;
+constexpr int kSortBuckets = 2048;             // value-linear buckets; +2: zero has a bucket of its own
+constexpr int kSortCounters = kSortBuckets + 8;
+constexpr uint32_t kSortBigBucket = 512;       // a larger bucket (other than zero's) leaves the row unsorted
+constexpr uint32_t kRecExactSums = 1u, kRecSorted = 2u;
+
+struct SortScratch {
+  double wsum[kMaxWaves];
+  uint32_t wcnt[kMaxWaves];
+  uint32_t minnz_bits;                         // smallest non-zero |x| of the row (bit pattern)
+  uint32_t big_bucket;
+};
+
+template <int K>
+constexpr size_t sort_header_bytes() {
+  return (sizeof(BatchScratch<1, kSortThreads / kWave>) + sizeof(SortScratch) + 255u) & ~(size_t)255u;
+}
+// dynamic LDS of sorted_prepare for rows of `cols` elements
+inline size_t sort_prepare_lds(size_t header, int64_t cols) {
+  return header + (size_t)(cols / 128) * kSlotBytes + (size_t)cols * 2 + 2 * (size_t)kSortCounters * 4;
+}
+
+// Can every sum the sorted evaluation forms be exact in binary64?  All values are multiples of
+// 2^ue (the unit in the last place of the smallest non-zero |x|) and smaller than 2^ea; the largest
+// sum is below 32 N times that.
+template <int DT>
+__device__ __forceinline__ bool sorted_sums_exact(float amax, uint32_t minnz_bits, uint32_t cols) {
+  if (!(amax > 0.0f)) return true;
+  int ea = 0;
+  (void)frexpf(amax, &ea);
+  const int e = DT == EQ_F16 ? (int)(minnz_bits >> 10) : (int)(minnz_bits >> 7);
+  const int ue = DT == EQ_F16 ? max(e, 1) - 15 - 10 : max(e, 1) - 127 - 7;
+  const int lc = 32 - __clz((int)cols - 1);
+  return lc + 5 + ea <= 53 + ue;
+}
+
+// Segment and row of the chunk's row j.
+__device__ __forceinline__ int find_seg_by_row(const SortSeg* __restrict__ segs, int nsegs, int64_t j) {
+  int lo = 0, hi = nsegs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (segs[mid].first_row <= j) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+template <int DT, int K>
+__global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __restrict__ mats, const SortSeg* __restrict__ segs,
+                                                               int nsegs, int64_t total_rows, EQ_GLOBAL unsigned char* __restrict__ ws,
+                                                               KParams kp) {
+  constexpr int NT = kSortThreads, NW = NT / kWave;
+  typedef BatchScratch<1, NW> Scratch;
+  extern __shared__ __align__(16) unsigned char smem[];
+  Scratch* sc = reinterpret_cast<Scratch*>(smem);
+  SortScratch* ss = reinterpret_cast<SortScratch*>(smem + sizeof(Scratch));
+  unsigned char* pool = smem + sort_header_bytes<K>();
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+
+  int64_t j = blockIdx.x;
+  if (j >= total_rows) return;
+  SortSeg sg = segs[find_seg_by_row(segs, nsegs, j)];
+  MatDesc md = mats[sg.mat];
+  const uint32_t cols = (uint32_t)md.cols, nchunks = cols >> 3, upr = cols >> 7;   // the same for every row of the launch
+  uint16_t* tmp = reinterpret_cast<uint16_t*>(pool + (size_t)upr * kSlotBytes);
+  uint32_t* start = reinterpret_cast<uint32_t*>(tmp + cols);
+  uint32_t* cur = start + kSortCounters;
+  uint16_t* out = reinterpret_cast<uint16_t*>(pool);        // the pool is free once its values sit in tmp
+  const size_t rec_bytes = sort_record_bytes(cols);
+
+  uint4 v[1][K];
+  int64_t row = sg.row0 + (j - sg.first_row);
+  batch_issue_loads<NT, 1, K, true>(md, row, 1, v);
+  for (;;) {
+    const int64_t jn = j + gridDim.x;
+    const bool more = jn < total_rows;
+    SortSeg sgn = sg;
+    if (more && jn >= sg.first_row + sg.nrows) sgn = segs[find_seg_by_row(segs, nsegs, jn)];
+    const MatDesc mdn = (more && sgn.mat != sg.mat) ? mats[sgn.mat] : md;
+    const int64_t rown = more ? sgn.row0 + (jn - sgn.first_row) : row;
+
+    if (tid == 0) {
+      sc->rowmax_bits[0] = 0;
+      sc->rownegmin_bits[0] = 0;
+      ss->minnz_bits = 0xFFFFFFFFu;
+      ss->big_bucket = 0;
+    }
+    for (uint32_t i = tid; i < (uint32_t)kSortCounters; i += NT) cur[i] = 0;
+    stage_loaded_rows<DT, NT, 1, K, Padded128Layout, true, false>(md, kp, row, 1, pool, 0u, nullptr, sc, v, [&] {
+      batch_issue_loads<NT, 1, K, true>(mdn, rown, more ? 1 : 0, v);
+    });
+    __syncthreads();                                         // wavefront-major staging ends without one
+
+    // ---- extremes of the normal values (0 included, as everywhere) ----
+    if (tid < upr) {
+      float vmin, vmax;
+      slot_min_max<DT>(pool + (size_t)tid * kSlotBytes, vmin, vmax);
+      atomicMax(&sc->rowmax_bits[0], __float_as_uint(vmax));
+      atomicMax(&sc->rownegmin_bits[0], __float_as_uint(0.0f - vmin));
+    }
+    __syncthreads();
+    const float vmax = __uint_as_float(sc->rowmax_bits[0]);
+    const float vmin = -__uint_as_float(sc->rownegmin_bits[0]);
+    const float bscale = vmax > vmin ? (float)(kSortBuckets - 1) / (vmax - vmin) : 0.0f;
+    // monotone in x; zeros (of either sign) alone in the bucket between the negative and the positive values
+    auto bucket = [&](float x) {
+      int b = (int)((x - vmin) * bscale);
+      b = b < 0 ? 0 : (b > kSortBuckets - 1 ? kSortBuckets - 1 : b);
+      return (uint32_t)b + (x > 0.0f ? 2u : x == 0.0f ? 1u : 0u);
+    };
+    const uint32_t zero_bucket = bucket(0.0f);
+
+    // ---- histogram ----
+    uint32_t minnz = 0xFFFFFFFFu;
+#pragma unroll 1
+    for (int i = 0; i < K; ++i) {
+      const uint32_t ch = (uint32_t)i * NT + tid;
+      if (ch < nchunks) {
+        const uint4 q = *reinterpret_cast<const uint4*>(pool + Padded128Layout::off(ch));
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const uint32_t h = (w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
+          atomicAdd(&cur[bucket(widen16<DT>(h))], 1u);
+          const uint32_t a = h & 0x7FFFu;
+          minnz = min(minnz, a ? a : 0xFFFFFFFFu);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) minnz = min(minnz, (uint32_t)__shfl_xor((int)minnz, o));
+    if (lane == 0) atomicMin(&ss->minnz_bits, minnz);
+    __syncthreads();
+
+    // ---- exclusive scan of the bucket counts: 8 consecutive counters per thread (the last thread takes the rest) ----
+    {
+      constexpr int per = kSortBuckets / NT;                 // 8
+      constexpr int last_extra = kSortCounters - kSortBuckets;
+      uint32_t c[per + last_extra], s = 0;
+      const int mine = tid == NT - 1 ? per + last_extra : per;
+#pragma unroll
+      for (int k = 0; k < per + last_extra; ++k) {
+        c[k] = k < mine ? cur[tid * per + k] : 0u;
+        s += c[k];
+        if (c[k] > kSortBigBucket && tid * per + k != zero_bucket) ss->big_bucket = 1u;   // benign race: every writer stores 1
+      }
+      const uint32_t inc = wave_scan_inclusive(s);
+      if (lane == kWave - 1) ss->wcnt[wave] = inc;
+      __syncthreads();
+      uint32_t a = inc - s;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) a += (uint32_t)w < wave ? ss->wcnt[w] : 0u;
+#pragma unroll
+      for (int k = 0; k < per + last_extra; ++k) {
+        if (k < mine) {
+          start[tid * per + k] = a;
+          cur[tid * per + k] = a;
+          a += c[k];
+        }
+      }
+    }
+    __syncthreads();
+    const bool ranked = ss->big_bucket == 0u;
+
+    // ---- scatter into the buckets (any order inside a bucket) ----
+#pragma unroll 1
+    for (int i = 0; i < K; ++i) {
+      const uint32_t ch = (uint32_t)i * NT + tid;
+      if (ch < nchunks) {
+        const uint4 q = *reinterpret_cast<const uint4*>(pool + Padded128Layout::off(ch));
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const uint32_t h = (w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
+          const uint32_t pos = atomicAdd(&cur[bucket(widen16<DT>(h))], 1u);
+          tmp[pos] = (uint16_t)h;
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- rank inside the bucket: the values below, and the equal ones that arrived earlier ----
+    for (uint32_t p = tid; p < cols; p += NT) {
+      const uint32_t h = tmp[p];
+      const float x = widen16<DT>(h);
+      const uint32_t b = bucket(x);
+      uint32_t at = p;
+      if (ranked && b != zero_bucket) {
+        const uint32_t a = start[b], e = start[b + 1];
+        uint32_t rank = 0;
+        for (uint32_t q = a; q < e; ++q) {
+          const float y = widen16<DT>(tmp[q]);
+          rank += (y < x || (y == x && q < p)) ? 1u : 0u;
+        }
+        at = a + rank;
+      }
+      out[at] = (uint16_t)h;
+    }
+    __syncthreads();
+
+    // ---- the record: header, values, exact prefix sums at every 8th position ----
+    EQ_GLOBAL unsigned char* rec = ws + sg.ws_off + (size_t)(j - sg.first_row) * rec_bytes;
+    {
+      for (uint32_t c = tid; c < nchunks; c += NT) global_store128(rec + kSortRecHeader + (size_t)c * 16, reinterpret_cast<const uint4*>(out)[c]);
+      const uint32_t cpt = (nchunks + NT - 1) / NT;
+      const uint32_t c0 = min(tid * cpt, nchunks), c1 = min(c0 + cpt, nchunks);
+      auto chunk_sum = [&](uint32_t c) {
+        const uint4 q = reinterpret_cast<const uint4*>(out)[c];
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+        double s = 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s += (double)widen16<DT>((w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+        return s;
+      };
+      double s = 0.0;
+      for (uint32_t c = c0; c < c1; ++c) s += chunk_sum(c);
+      double inc = s;                                        // inclusive scan over the wavefront
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const double t = __shfl_up(inc, o);
+        if (lane >= (uint32_t)o) inc += t;
+      }
+      if (lane == kWave - 1) ss->wsum[wave] = inc;
+      __syncthreads();
+      double a = inc - s;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) a += (uint32_t)w < wave ? ss->wsum[w] : 0.0;
+      EQ_GLOBAL double* P = (EQ_GLOBAL double*)(rec + kSortRecHeader + (size_t)cols * 2);
+      for (uint32_t c = c0; c < c1; ++c) {
+        P[c] = a;
+        a += chunk_sum(c);
+      }
+      if (c1 == nchunks && c0 < c1) P[nchunks] = a;
+      if (tid == 0) {
+        float r0;
+        int z;
+        (void)init_unit(kp, vmin, vmax, r0, z);
+        const bool exact = sorted_sums_exact<DT>(fmaxf(-vmin, vmax), ss->minnz_bits, cols);
+        // the header (SortRecHeader) as one 128-bit store
+        global_store128(rec, make_uint4(__float_as_uint(r0), (uint32_t)z,
+                                        (exact ? kRecExactSums : 0u) | (ranked ? kRecSorted : 0u), 0u));
+      }
+    }
+    if (!more) break;
+    __syncthreads();                                         // the pool and the counters are refilled
+    j = jn;
+    sg = sgn;
+    md = mdn;
+    row = rown;
+  }
+}
+
+// ---- sums over the 16 lanes of a row (lanes 16 k .. 16 k + 15), result in every one of them ----
+__device__ __forceinline__ int row16_sum(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false);   // row_ror:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false);   // row_ror:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x122, 0xF, 0xF, false);   // row_ror:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x121, 0xF, 0xF, false);   // row_ror:1
+  return v;
+}
+template <int CTRL>
+__device__ __forceinline__ double row_ror(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double row16_sum(double v) {
+  v += row_ror<0x128>(v);
+  v += row_ror<0x124>(v);
+  v += row_ror<0x122>(v);
+  v += row_ror<0x121>(v);
+  return v;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restrict__ mats, const SortSeg* __restrict__ segs,
+                                                         int nsegs, int total_groups, const EQ_GLOBAL unsigned char* __restrict__ ws,
+                                                         KParams kp) {
+  const int lane = (int)threadIdx.x;
+  const int group = (int)blockIdx.x;
+  if (group >= total_groups) return;
+  int lo = 0, hi = nsegs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (segs[mid].first_group <= group) lo = mid; else hi = mid - 1;
+  }
+  const SortSeg sg = segs[lo];
+  const MatDesc md = mats[sg.mat];
+  const int rin = 4 * (group - sg.first_group) + (lane >> 4);
+  const bool live = rin < sg.nrows;
+  const int N = md.cols, nblk = N >> 3;
+  const EQ_GLOBAL unsigned char* rec = ws + sg.ws_off + (size_t)(live ? rin : sg.nrows - 1) * sort_record_bytes(N);
+  SortRecHeader hd;
+  {
+    const uint4 q = global_load128(rec);
+    hd.r0 = __uint_as_float(q.x); hd.z = (int32_t)q.y; hd.flags = q.z; hd.pad = 0;
+  }
+  const EQ_GLOBAL unsigned char* srow = rec + kSortRecHeader;
+  const EQ_GLOBAL double* P = (const EQ_GLOBAL double*)(rec + kSortRecHeader + (size_t)N * 2);
+
+  const int b = lane & 15;
+  const int nbound = kp.L;                                   // boundaries between neighbouring levels (<= 15)
+  const int clo = -hd.z, chi = kp.L - hd.z;
+  const int lev = clo + min(b, nbound - 1);                  // this lane's boundary lies between lev and lev + 1
+  const bool counts = b < nbound;
+  const int wA = counts ? 2 * lev + 1 : 0;
+  const float thr = kMagic + (float)lev;                     // exact: a small integer next to 1.5 * 2^23
+  const bool fast = (hd.flags & (kRecExactSums | kRecSorted)) == (kRecExactSums | kRecSorted);
+  const double PN = P[nblk];
+  const bool act = hd.r0 > 0.0f;
+
+  float r32 = act ? hd.r0 : kp.D, r_sel = r32;               // an all-zero row keeps s = 1
+  double J_best = __builtin_inf();
+  const double floor_r = (double)hd.r0 * 0.0009765625;
+  Adam ad;
+  ad.init();
+  int n = N >> 1;
+
+  for (int t = 0;; ++t) {
+    const bool last = t == kp.iters;
+    if (last && kp.select == EQ_SELECT_LAST) break;
+    double bc[4];
+    if (!last) load_bias_corrections(kp, t, bc);
+    float s32, inv;
+    scale_of(kp, r32, s32, inv);
+    int ia = 0;
+    double db = 0.0;
+    if (fast) {
+      // ---- n = number of elements whose level is <= lev, and P[n] ----
+      // Probes of whole 8-element chunks, starting with the one that held the boundary last time:
+      // inside the chunk the boundary is found at once; a chunk entirely on one side moves the search
+      // on, by doubling steps until the boundary is bracketed, then by halving.
+      int nlo = 0, nhi = N, d = 1;
+      int j = min(n >> 3, nblk - 1);
+      bool have_lo = false, have_hi = false, done = false;
+      double Pn = 0.0;
+      while (!__all(done)) {
+        if (!done) {
+          const uint4 q = global_load128(srow + (size_t)j * 16);
+          const double Pj = P[j];
+          const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+          int cnt = 0;
+          double part = 0.0;
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const float xv = widen16<DT>((w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+            const bool le = __builtin_fmaf(xv, inv, kMagic) <= thr;
+            cnt += le ? 1 : 0;
+            part += le ? (double)xv : 0.0;
+          }
+          if (cnt > 0 && cnt < 8) { n = 8 * j + cnt; Pn = Pj + part; done = true; }
+          else if (cnt == 8) { nlo = 8 * j + 8; have_lo = true; Pn = Pj + part; }
+          else { nhi = 8 * j; have_hi = true; Pn = Pj; }
+          if (!done && nlo >= nhi) { n = nlo; done = true; }
+          if (!done) {
+            if (have_lo && have_hi) j = (nlo + nhi) >> 4;
+            else if (have_lo) { j = min(j + d, nblk - 1); d <<= 1; }
+            else { j = max(j - d, 0); d <<= 1; }
+          }
+        }
+      }
+      ia = wA * n;
+      db = counts ? Pn : 0.0;
+    } else {
+      // ---- element by element (binary64 accumulation of exact products, like the general kernel) ----
+      const float fclo = (float)clo, fchi = (float)chi;
+      for (int ch = b; ch < nblk; ch += 16) {
+        const uint4 q = global_load128(srow + (size_t)ch * 16);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const float xv = widen16<DT>((w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+          const float c = level_of(xv, inv, fclo, fchi);
+          const int ci = (int)c;
+          ia += ci * ci;
+          db += (double)(xv * c);
+        }
+      }
+    }
+    const int SA = row16_sum(ia);
+    const double SB = row16_sum(db);
+    const double A = fast ? (double)(chi * chi * N - SA) : (double)SA;
+    const double B = fast ? (double)chi * PN - SB : SB;
+    double J, g;
+    loss_and_grad(kp, s32, A, B, J, g);
+    if (J < J_best) { J_best = J; r_sel = r32; }
+    if (last) break;
+    const float r_new = ad.step(kp, bc, r32, g, floor_r);
+    if (act) r32 = r_new;
+  }
+  if (kp.select == EQ_SELECT_LAST) r_sel = r32;
+  if (live && b == 0) md.range[sg.row0 + rin] = r_sel;
+}
+
+}  // namespace eq

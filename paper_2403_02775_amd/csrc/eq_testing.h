@@ -27,7 +27,11 @@ enum {
   EQ_OVR_MATVEC_LOOKUP = 5,  /* eq_dequant_matvec, 4-bit codes with one range per row: 1 = half of the pairs of
                                 weights from the table of pairs and half from the table of single values,
                                 2 = all from the table of single values (default: all from the table of pairs) */
-  EQ_OVR_COUNT = 6
+  EQ_OVR_SORTED_ROWS = 6,    /* 1: rows with one range each and at most 4 bits are optimised element by element
+                                (the per-channel lane kernels) instead of from their sorted values */
+  EQ_OVR_SORT_CHUNK_ROWS = 7, /* n > 0: at most n rows (rounded down to a multiple of 4) per chunk of the sorted
+                                 evaluation, instead of as many as 2 GiB of records hold */
+  EQ_OVR_COUNT = 8
 };
 EQ_API int eq_test_set_override(int which, int64_t value);   /* EQ_OK or EQ_E_PARAM */
 

@@ -1,0 +1,46 @@
+// Instantiations of the sorted evaluation of rows with one range each, for one input type, EQ_TU_DT.
+#ifndef EQ_TU_DT
+#define EQ_TU_DT 0   // the build compiles this file once per input type (0: fp16, 1: bf16)
+#endif
+#include "eq_launch.h"
+#include "eq_sorted.h"
+
+namespace eq {
+
+// workgroups of sorted_prepare: as many as the chip holds at once (its LDS decides), each walking
+// through rows j, j + G, j + 2 G, ... of the chunk
+static unsigned prepare_grid(int64_t rows, size_t lds) {
+  const int64_t per_cu = (int64_t)std::max<size_t>(1, std::min<size_t>(8, (160u * 1024u) / lds));
+  return (unsigned)std::min<int64_t>(rows, 256 * per_cu);
+}
+
+template <int DT>
+SortKernels pick_sorted_kernels(const LaneClass& lc) {
+  SortKernels k;
+  const int64_t per_thread = ((int64_t)lc.cols / 8 + kSortThreads - 1) / kSortThreads;
+#define EQ_SORT_VARIANT(K_)                                                                                          \
+  {                                                                                                                  \
+    k.prepare_fn = reinterpret_cast<const void*>(&sorted_prepare<DT, K_>);                                           \
+    k.prepare_lds = sort_prepare_lds(sort_header_bytes<K_>(), lc.cols);                                              \
+    k.prepare = [](const LaneClass& c, const SortLaunchArgs& a, const KParams& kp, hipStream_t s) {                  \
+      const size_t lds = sort_prepare_lds(sort_header_bytes<K_>(), c.cols);                                          \
+      hipLaunchKernelGGL((sorted_prepare<DT, K_>), dim3(prepare_grid(a.rows, lds)), dim3(kSortThreads), lds, s,      \
+                         a.mats, a.segs, (int)a.nsegs, a.rows, (EQ_GLOBAL unsigned char*)a.ws, kp);                  \
+    };                                                                                                               \
+  }
+  if (per_thread <= 1) EQ_SORT_VARIANT(1)
+  else if (per_thread <= 2) EQ_SORT_VARIANT(2)
+  else if (per_thread <= 4) EQ_SORT_VARIANT(4)
+  else if (per_thread <= 8) EQ_SORT_VARIANT(8)
+  else if (per_thread <= 16) EQ_SORT_VARIANT(16)
+#undef EQ_SORT_VARIANT
+  k.iterate = [](const LaneClass&, const SortLaunchArgs& a, const KParams& kp, hipStream_t s) {
+    hipLaunchKernelGGL((sorted_iterate<DT>), dim3((unsigned)a.groups), dim3(kWave), 0, s, a.mats, a.segs, (int)a.nsegs,
+                       (int)a.groups, (const EQ_GLOBAL unsigned char*)a.ws, kp);
+  };
+  return k;
+}
+
+template SortKernels pick_sorted_kernels<EQ_TU_DT>(const LaneClass&);
+
+}  // namespace eq

@@ -55,5 +55,5 @@ def eq_override():
     """Sets kernel-selection overrides of the library (csrc/eq_testing.h) and clears them all afterwards."""
     import paper_2403_02775_amd as eqg
     yield eqg.set_override
-    for which in range(6):
+    for which in range(eqg.OVR_COUNT):
         eqg.set_override(which, 0)

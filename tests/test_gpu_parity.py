@@ -28,7 +28,10 @@ def _check(W, p, what, batch=True, deq=True):
     return res
 
 
-def test_config1_per_channel_symmetric_and_asymmetric():
+@pytest.mark.parametrize("evaluation", ["sorted", "direct"])
+def test_config1_per_channel_symmetric_and_asymmetric(evaluation, eq_override):
+    if evaluation == "direct":
+        eq_override(eqg.OVR_SORTED_ROWS, 1)
     (_, W), = eq_inputs.gen_config_small("c1", DEV)
     for mode in (eqo.ASYMMETRIC, eqo.SYMMETRIC):
         p = eqo.Params(bits=4, group_size=0, mode=mode, iters=100)
@@ -68,19 +71,26 @@ def test_unit_per_lane_kernel_row_shapes_and_carry_over(rows, cols, units_per_it
 @pytest.mark.parametrize("rows,cols,units_per_item", [(37, 4096, 0), (21, 8192, 300), (5, 22016, 0), (11, 11008, 0),
                                                       (13, 5120, 0), (40, 2048, 512), (3, 32768, 0), (4, 13824, 0),
                                                       (3, 17920, 0), (7, 11008, 200)])
-def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, eq_override):
-    # one range per row, the row spread over cols / 128 lanes: rounds of 8, 4, 1, 2, 6, 16 and 1
-    # rows, a ragged last round, several rounds per work item, staging in one or several batches
+@pytest.mark.parametrize("evaluation", ["sorted", "direct"])
+def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, evaluation, eq_override):
+    # one range per row.  "direct": the row spread over cols / 128 lanes: rounds of 8, 4, 1, 2, 6, 16 and 1
+    # rows, a ragged last round, several rounds per work item, staging in one or several batches.
+    # "sorted" (the library's choice for at most 4 bits): the sums from the row's sorted values.
     if units_per_item:
         eq_override(eqg.OVR_UNITS_PER_ITEM, units_per_item)
+    if evaluation == "direct":
+        eq_override(eqg.OVR_SORTED_ROWS, 1)
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows * 7 + cols, device=DEV)
     for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
         res = _check(W, eqo.Params(bits=bits, group_size=0, mode=mode, iters=12), f"channel kernel {rows}x{cols}")
         assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
 
+@pytest.mark.parametrize("evaluation", ["sorted", "direct"])
 @pytest.mark.parametrize("cols", [22016, 11008])
-def test_per_channel_rows_cut_into_equal_pieces(cols, eq_override):
+def test_per_channel_rows_cut_into_equal_pieces(cols, evaluation, eq_override):
+    if evaluation == "direct":
+        eq_override(eqg.OVR_SORTED_ROWS, 1)
     # rows of 86 * 256 or 86 * 128 values with 4-bit codes take the kernel that cuts a row into
     # equal pieces over all 256 lanes: its variants, its binary64 fallback, and the 128-element
     # kernel it replaces on the same input
@@ -130,7 +140,10 @@ def test_per_channel_without_optimisation_steps(rows, cols, eq_override):
     assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
 
 
-def test_per_channel_lane_kernel_variants():
+@pytest.mark.parametrize("evaluation", ["sorted", "direct"])
+def test_per_channel_lane_kernel_variants(evaluation, eq_override):
+    if evaluation == "direct":
+        eq_override(eqg.OVR_SORTED_ROWS, 1)
     W = eq_inputs.gen_matrix(19, 4096, eq_inputs.RECIPES["c5"], seed=77, device=DEV)
     _check(W, eqo.Params(bits=4, group_size=0, iters=0), "channel T=0")
     _check(W, eqo.Params(bits=4, group_size=0, iters=1), "channel T=1")
@@ -143,6 +156,45 @@ def test_per_channel_lane_kernel_variants():
     Wz[4] = 0                                            # an all-zero row keeps scale 1
     Wz[7, 100:] = 0
     _check(Wz, eqo.Params(bits=4, group_size=0, iters=10), "channel zero rows")
+
+
+@pytest.mark.parametrize("chunk_rows", [0, 8, 36])
+def test_sorted_rows_in_chunks_and_rows_it_evaluates_directly(chunk_rows, eq_override):
+    # one range per row from the sorted values: a batch of three matrices of one row length and one of
+    # another (two launches), cut into chunks of a few rows (segments that start and end inside a matrix,
+    # groups of 4 rows with absent rows), and the rows the sorted evaluation does not take: many equal
+    # values (left unsorted), sums that binary64 cannot hold exactly, all-zero rows
+    if chunk_rows:
+        eq_override(eqg.OVR_SORT_CHUNK_ROWS, chunk_rows)
+    Ws = [eq_inputs.gen_matrix(r, c, eq_inputs.RECIPES["c5"], seed=900 + r, device=DEV) for r, c in ((21, 4096), (7, 4096), (30, 4096), (10, 5120))]
+    Ws[0][3] = 0
+    Ws[0][4, ::3] = 0.125                                # a third of the row is one value: its bucket overflows
+    Ws[0][5] = Ws[0][5].abs()                            # no negative value
+    Ws[0][6] = -Ws[0][6].abs()                           # no positive value
+    Ws[2][0] = Ws[2][0] * 30000.0                        # |x| up to some 2^12 next to
+    Ws[2][0, 17] = 6e-8                                  # the smallest subnormal: 36 bits apart, exact in binary64
+    Ws[2][29, :] = 0.5                                   # a constant row: sigma = 0, no outliers
+    for mode, bits, select in ((eqo.SYMMETRIC, 4, eqo.SELECT_BEST), (eqo.ASYMMETRIC, 4, eqo.SELECT_BEST),
+                               (eqo.ASYMMETRIC, 3, eqo.SELECT_LAST), (eqo.SYMMETRIC, 2, eqo.SELECT_BEST)):
+        p = eqo.Params(bits=bits, group_size=0, mode=mode, iters=25, select=select)
+        print(f"[case] sorted rows chunk_rows={chunk_rows} mode={mode} bits={bits} select={select}", flush=True)
+        outs, got = run_gpu(Ws, p, batch=True)
+        for i, W in enumerate(Ws):
+            raw = raw_of(W)
+            res = compare(raw, got[i], eqo.quantize_matrix(raw, p), p, f"sorted rows matrix {i}")
+            assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+    if chunk_rows == 0:
+        # statistics of the whole matrix (every row decided by the exact path) at each number of chunks per thread
+        for rows, cols in ((4, 2048), (5, 4096), (3, 8192), (3, 11008), (2, 22016)):
+            Wm = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=cols, device=DEV)
+            res = _check(Wm, eqo.Params(bits=4, group_size=0, iters=3, stat_scope=eqo.STAT_MATRIX), f"sorted rows matrix scope {cols}", deq=False)
+            assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
+    Wb = eq_inputs.gen_matrix(9, 4096, eq_inputs.with_dtype(eq_inputs.RECIPES["c2"], "bf16"), seed=77, device=DEV)
+    Wb[1, 5] = 1e-12                                     # 2^-40 next to 2^-3: exact
+    Wb[2] = Wb[2] * 1e30
+    Wb[2, 9] = 1e-20                                     # 2^100 next to 2^-66: evaluated element by element
+    res = _check(Wb, eqo.Params(dtype=eqo.BF16, bits=4, group_size=0, iters=10), "sorted rows bf16 wide span")
+    assert res["excused_elems"] == 0
 
 
 @pytest.mark.parametrize("G", [128, 0])
