@@ -317,7 +317,8 @@ def main():
     if args.sweep and args.group_size == 128 and args.iters == 100:
         sweep_cfgs = [("T=0", 0, 128, args.lr), ("T=1", 1, 128, args.lr), ("T=10", 10, 128, args.lr),
                       ("T=500, lr=1e-4 (the paper's LLaMA setting)", 500, 128, 1e-4),
-                      ("per channel, T=100 (the paper's granularity)", 100, 0, args.lr)]
+                      ("per channel, T=100 (the paper's granularity)", 100, 0, args.lr),
+                      ("per channel, T=500, lr=1e-4 (the paper's LLaMA setting at its granularity)", 500, 0, 1e-4)]
     caps = [int(w.numel() * args.capacity_frac) for w in Ws]
     outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, dev) for w, c in zip(Ws, caps)]
     shape_r, shape_c = [w.shape[0] for w in Ws], [w.shape[1] for w in Ws]
@@ -337,8 +338,11 @@ def main():
         del src, dst
 
     def kernel_name(q):
+        # one range per row, at most 4 bits, 64 steps or more: Adam runs on the sorted rows (sorted_prepare,
+        # sorted_iterate), the kernel without optimisation steps emits
         return ("quantize_rtn128" if q.iters == 0 and q.group_size in (0, 128) else "quantize_units128" if q.group_size == 128
-                else "quantize_channels" if q.group_size == 0 else "quantize_rows_generic")
+                else ("sorted_rows" if q.iters >= 64 and q.bits <= 4 else "quantize_channels") if q.group_size == 0
+                else "quantize_rows_generic")
 
     def timed(q, q_outs, steps, warmup, label):
         """`steps` calls of eq_quantize_batch over the whole set; timing by events on the stream the
@@ -454,7 +458,10 @@ def main():
                 f"hbm {r['step_hbm_frac']:.3f}, useful-op {r['step_useful_op_frac']:.3f}")
         out["sweep"] = sweep
         out["sweep_note"] = ("hbm_frac / useful_op_frac of a sweep entry are over the WHOLE step (every kernel of the call): "
-                             "algorithmic bytes, resp. elements x (5 x passes + 12) lane-operations, over the step time and the peak")
+                             "algorithmic bytes, resp. elements x (5 x passes + 12) lane-operations, over the step time and the peak. "
+                             "The lane-operations are those of an evaluation that visits every element in every pass; the per-channel "
+                             "entries (kernel sorted_rows) take the sums from the sorted row instead, so their useful_op_frac is the "
+                             "work such an evaluation would have done over the time taken, and may exceed 1")
 
     if pool is not None:
         kw = dict(dtype=gp.dtype, bits=bits, group_size=args.group_size, mode=0, stat_scope=0, n_sigma=3.0, iters=args.iters,

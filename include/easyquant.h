@@ -132,8 +132,10 @@ typedef struct eq_qmatrix {
  * one unit per lane (without optimisation steps, iters == 0, a load-pipelined variant of it);
  * one range per row with cols a multiple of 128 in 2048..32768 spreads the row over
  * cols / 128 lanes (rows of 11008, 13824, 17920 or 22016 columns with 4-bit codes: in
- * equal pieces over 128 or 256 lanes); everything else goes to a general kernel (one
- * workgroup per row, one wavefront per unit). */
+ * equal pieces over 128 or 256 lanes; with at most 4 bits and 64 steps or more the rows are
+ * sorted first and every step takes its two sums from the sorted row and its exact prefix
+ * sums, which needs up to 2 GiB more workspace, counted by eq_workspace_bytes()); everything
+ * else goes to a general kernel (one workgroup per row, one wavefront per unit). */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,
                        const eq_params* p, const eq_qmatrix* out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -157,7 +159,8 @@ EQ_API int eq_quantize_batch(int32_t n, const void* const* W, const int64_t* row
  *   EQ_STATIC_SCRATCH_BYTES (32 MiB), else EQ_E_SCRATCH (nothing is enqueued).  The need is
  *   about 6 bytes per entry of out_capacity plus 8 bytes per row: a 22016 x 8192 matrix with a
  *   capacity of 2 % of its elements takes 21 MiB, a 4096 x 4096 one with the never-overflowing
- *   capacity of eq_outlier_capacity_bound 11 MiB.
+ *   capacity of eq_outlier_capacity_bound 11 MiB.  (Rows with one range each are always
+ *   optimised element by element here: the records of their sorted form would not fit.)
  *   The device that is current when the call is made must be the one hip_stream belongs to;
  *   the address of that device's array is looked up on the first call per device.
  *   All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams,

@@ -91,6 +91,9 @@ def lib() -> C.CDLL:
         L.eq_test_plan_items.restype = C.c_int64
         L.eq_test_plan_items.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                          C.POINTER(_CParams), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int64]
+        L.eq_test_plan_sort_segments.restype = C.c_int64
+        L.eq_test_plan_sort_segments.argtypes = [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                                 C.POINTER(_CParams), C.POINTER(C.c_int64), C.c_int64, C.POINTER(C.c_int64)]
         L.eq_profile_enable.restype = C.c_int
         L.eq_profile_enable.argtypes = [C.c_int]
         L.eq_profile_read.restype = C.c_int
@@ -310,3 +313,21 @@ def plan_items(rows: Sequence[int], cols: Sequence[int], capacities: Sequence[in
     launch = (C.c_int32 * max(cnt, 1))()
     lib().eq_test_plan_items(*args, items, launch, cnt)
     return [tuple(items[5 * i:5 * i + 5]) + (launch[i],) for i in range(cnt)]
+
+
+def plan_sort_segments(rows: Sequence[int], cols: Sequence[int], capacities: Sequence[int], p: Params):
+    """The chunks of the sorted evaluation of rows with one range each for these shapes (host only, no
+    GPU): (list of (chunk, matrix, first row, rows, first group, first row in chunk, byte offset of the
+    first record), bytes of the record region)."""
+    n = len(rows)
+    A = C.c_int64 * max(n, 1)
+    cp = p.c()
+    args = (n, A(*rows), A(*cols), A(*capacities), C.byref(cp))
+    region = C.c_int64(0)
+    cnt = int(lib().eq_test_plan_sort_segments(*args, None, 0, C.byref(region)))
+    if cnt < 0:
+        raise EasyQuantError(cnt, "eq_test_plan_sort_segments")
+    segs = (C.c_int64 * (7 * max(cnt, 1)))()
+    lib().eq_test_plan_sort_segments(*args, segs, cnt, C.byref(region))
+    return [tuple(segs[7 * i:7 * i + 7]) for i in range(cnt)], int(region.value)
+

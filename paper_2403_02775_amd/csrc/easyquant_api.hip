@@ -165,6 +165,7 @@ struct Plan {
 // sorted_iterate to fill the chip several times over).
 constexpr size_t kSortBudgetBytes = (size_t)2 << 30;
 constexpr int64_t kSortMinCols = 2048;
+constexpr int kSortMinIters = 64;
 
 int64_t clamp_capacity(int64_t c) { return c < 0 ? 0 : (c > 0xFFFFFFFEll ? 0xFFFFFFFEll : c); }
 
@@ -230,8 +231,11 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     const bool chan_keep128 = override_of(EQ_OVR_CHANNEL_KERNEL) == 128;
     // one range per row, at most 4 bits, optimisation steps: Adam runs on the sorted rows (eq_sorted.h)
     // and the kernel without optimisation steps emits at the ranges it leaves
-    const bool chan_sorted = pl.path[(size_t)order[k]] == 2 && p->iters > 0 && p->bits <= 4 && allow_sorted &&
-                             !chan_keep128 && c >= kSortMinCols && override_of(EQ_OVR_SORTED_ROWS) != 1;
+    // (sorting costs about as much as 60 to 90 direct evaluations of the row, an evaluation from the
+    // sorted row a sixth to a half of a direct one: from 64 steps on)
+    const bool chan_sorted = pl.path[(size_t)order[k]] == 2 && p->bits <= 4 && allow_sorted && !chan_keep128 &&
+                             c >= kSortMinCols && override_of(EQ_OVR_SORTED_ROWS) != 1 &&
+                             (p->iters >= kSortMinIters || (p->iters > 0 && override_of(EQ_OVR_SORTED_ROWS) == 2));
     const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && (p->iters == 0 || chan_sorted) && !chan_keep128;
     if (pl.path[(size_t)order[k]] == 2 && !chan_rtn) {
       // per-channel: a round is floor(256 / segments) whole rows; items are multiples of that
@@ -915,6 +919,26 @@ int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, 
     }
   }
   return (int64_t)pl.work.size();
+}
+
+int64_t eq_test_plan_sort_segments(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
+                                   const eq_params* p, int64_t* segs, int64_t max_segs, int64_t* record_region_bytes) {
+  if (n < 0 || !p || (n > 0 && (!rows || !cols || !out_capacity))) return EQ_E_NULL;
+  if (!params_ok(p)) return EQ_E_PARAM;
+  for (int32_t i = 0; i < n; ++i)
+    if (rows[i] < 0 || cols[i] < 0 || rows[i] > 0x7FFFFFFF) return EQ_E_SHAPE;
+  const Plan pl = make_plan(n, rows, cols, out_capacity, p, true);
+  for (size_t c = 0; c < pl.chunks.size(); ++c) {
+    const SortChunk& ch = pl.chunks[c];
+    for (size_t i = ch.first_seg; i < ch.first_seg + ch.n_segs && (int64_t)i < max_segs; ++i) {
+      if (!segs) break;
+      const SortSeg& sg = pl.segs[i];
+      int64_t* o = segs + 7 * i;
+      o[0] = (int64_t)c; o[1] = sg.mat; o[2] = sg.row0; o[3] = sg.nrows; o[4] = sg.first_group; o[5] = sg.first_row; o[6] = sg.ws_off;
+    }
+  }
+  if (record_region_bytes) *record_region_bytes = (int64_t)pl.sort_ws_bytes;
+  return (int64_t)pl.segs.size();
 }
 
 int eq_profile_enable(int on) {

@@ -31,9 +31,10 @@
 
 namespace eq {
 
-constexpr int kSortThreads = 256;
-constexpr int kSortBuckets = 2048;             // value-linear buckets; +2: zero has a bucket of its own
-constexpr int kSortCounters = kSortBuckets + 8;
+constexpr int kSortThreads = 256;              // workgroup of sorted_prepare for rows of up to 8192 elements (512 beyond)
+// NB value-linear buckets (+2: zero has a bucket of its own): 4096 for rows of up to 8192 elements,
+// 8192 beyond.  16-bit counters, two to a word (a row has at most 32768 elements).
+constexpr int sort_counters(int nb) { return nb + 16; }
 constexpr uint32_t kSortBigBucket = 512;       // a larger bucket (other than zero's) leaves the row unsorted
 constexpr uint32_t kRecExactSums = 1u, kRecSorted = 2u;
 
@@ -44,13 +45,14 @@ struct SortScratch {
   uint32_t big_bucket;
 };
 
-template <int K>
+template <int NT>
 constexpr size_t sort_header_bytes() {
-  return (sizeof(BatchScratch<1, kSortThreads / kWave>) + sizeof(SortScratch) + 255u) & ~(size_t)255u;
+  return (sizeof(BatchScratch<1, NT / kWave>) + sizeof(SortScratch) + 255u) & ~(size_t)255u;
 }
-// dynamic LDS of sorted_prepare for rows of `cols` elements
-inline size_t sort_prepare_lds(size_t header, int64_t cols) {
-  return header + (size_t)(cols / 128) * kSlotBytes + (size_t)cols * 2 + 2 * (size_t)kSortCounters * 4;
+// dynamic LDS of sorted_prepare for rows of `cols` elements: staging pool (reused for the sorted
+// values), the values bucket by bucket, the bucket counters
+inline size_t sort_prepare_lds(size_t header, int64_t cols, int nb) {
+  return header + (size_t)(cols / 128) * kSlotBytes + (size_t)cols * 2 + (size_t)sort_counters(nb) * 2;
 }
 
 // Can every sum the sorted evaluation forms be exact in binary64?  All values are multiples of
@@ -67,7 +69,7 @@ __device__ __forceinline__ bool sorted_sums_exact(float amax, uint32_t minnz_bit
   return lc + 5 + ea <= 53 + ue;
 }
 
-// Segment and row of the chunk's row j.
+// Segment of the chunk's row j.
 __device__ __forceinline__ int find_seg_by_row(const SortSeg* __restrict__ segs, int nsegs, int64_t j) {
   int lo = 0, hi = nsegs - 1;
   while (lo < hi) {
@@ -77,16 +79,25 @@ __device__ __forceinline__ int find_seg_by_row(const SortSeg* __restrict__ segs,
   return lo;
 }
 
-template <int DT, int K>
-__global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __restrict__ mats, const SortSeg* __restrict__ segs,
-                                                               int nsegs, int64_t total_rows, EQ_GLOBAL unsigned char* __restrict__ ws,
-                                                               KParams kp) {
-  constexpr int NT = kSortThreads, NW = NT / kWave;
+// NT threads (256 for rows of up to 8192 elements, three workgroups per compute unit; 512 beyond, one),
+// K 16-byte chunks of the row per thread.  A workgroup walks through rows j, j + G, j + 2 G, ... of the
+// launch, the loads of its next row in flight while it sorts this one.
+// Wavefronts per SIMD the kernel is compiled for: what its LDS lets a compute unit hold (three
+// 256-thread workgroups; one 512-thread workgroup for the longest rows).
+template <int NT, int K>
+constexpr int sort_waves_per_simd() { return NT == 256 ? 3 : 2; }
+
+template <int DT, int NT, int K, int NB>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(sort_waves_per_simd<NT, K>(), sort_waves_per_simd<NT, K>()))) void sorted_prepare(const MatDesc* __restrict__ mats, const SortSeg* __restrict__ segs,
+                                                     int nsegs, int64_t total_rows, EQ_GLOBAL unsigned char* __restrict__ ws,
+                                                     KParams kp) {
+  constexpr int NW = NT / kWave;
+  constexpr int kSortBuckets = NB, kSortCounters = sort_counters(NB);
   typedef BatchScratch<1, NW> Scratch;
   extern __shared__ __align__(16) unsigned char smem[];
   Scratch* sc = reinterpret_cast<Scratch*>(smem);
   SortScratch* ss = reinterpret_cast<SortScratch*>(smem + sizeof(Scratch));
-  unsigned char* pool = smem + sort_header_bytes<K>();
+  unsigned char* pool = smem + sort_header_bytes<NT>();
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
   int64_t j = blockIdx.x;
@@ -95,8 +106,8 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
   MatDesc md = mats[sg.mat];
   const uint32_t cols = (uint32_t)md.cols, nchunks = cols >> 3, upr = cols >> 7;   // the same for every row of the launch
   uint16_t* tmp = reinterpret_cast<uint16_t*>(pool + (size_t)upr * kSlotBytes);
-  uint32_t* start = reinterpret_cast<uint32_t*>(tmp + cols);
-  uint32_t* cur = start + kSortCounters;
+  uint32_t* cntw = reinterpret_cast<uint32_t*>(tmp + cols); // 16-bit counts, then the buckets' first positions, in pairs
+  const uint16_t* cnt = reinterpret_cast<const uint16_t*>(cntw);
   uint16_t* out = reinterpret_cast<uint16_t*>(pool);        // the pool is free once its values sit in tmp
   const size_t rec_bytes = sort_record_bytes(cols);
 
@@ -117,7 +128,7 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
       ss->minnz_bits = 0xFFFFFFFFu;
       ss->big_bucket = 0;
     }
-    for (uint32_t i = tid; i < (uint32_t)kSortCounters; i += NT) cur[i] = 0;
+    for (uint32_t i = tid; i < (uint32_t)kSortCounters / 2; i += NT) cntw[i] = 0;
     stage_loaded_rows<DT, NT, 1, K, Padded128Layout, true, false>(md, kp, row, 1, pool, 0u, nullptr, sc, v, [&] {
       batch_issue_loads<NT, 1, K, true>(mdn, rown, more ? 1 : 0, v);
     });
@@ -125,10 +136,10 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
 
     // ---- extremes of the normal values (0 included, as everywhere) ----
     if (tid < upr) {
-      float vmin, vmax;
-      slot_min_max<DT>(pool + (size_t)tid * kSlotBytes, vmin, vmax);
-      atomicMax(&sc->rowmax_bits[0], __float_as_uint(vmax));
-      atomicMax(&sc->rownegmin_bits[0], __float_as_uint(0.0f - vmin));
+      float umin, umax;
+      slot_min_max<DT>(pool + (size_t)tid * kSlotBytes, umin, umax);
+      atomicMax(&sc->rowmax_bits[0], __float_as_uint(umax));
+      atomicMax(&sc->rownegmin_bits[0], __float_as_uint(0.0f - umin));
     }
     __syncthreads();
     const float vmax = __uint_as_float(sc->rowmax_bits[0]);
@@ -142,18 +153,23 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
     };
     const uint32_t zero_bucket = bucket(0.0f);
 
-    // ---- histogram ----
+    // ---- histogram; every element remembers its arrival number in its bucket ----
+    uint32_t slots[K][4];                                    // 16 bits each, two to a register
     uint32_t minnz = 0xFFFFFFFFu;
-#pragma unroll 1
+#pragma unroll
     for (int i = 0; i < K; ++i) {
       const uint32_t ch = (uint32_t)i * NT + tid;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) slots[i][k] = 0;
       if (ch < nchunks) {
         const uint4 q = *reinterpret_cast<const uint4*>(pool + Padded128Layout::off(ch));
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const uint32_t h = (w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
-          atomicAdd(&cur[bucket(widen16<DT>(h))], 1u);
+          const uint32_t bk = bucket(widen16<DT>(h));
+          const uint32_t old = atomicAdd(&cntw[bk >> 1], 1u << ((bk & 1u) * 16));   // (no carry: a count stays below 2^16)
+          slots[i][k >> 1] |= ((old >> ((bk & 1u) * 16)) & 0xFFFFu) << ((k & 1) * 16);
           const uint32_t a = h & 0x7FFFu;
           minnz = min(minnz, a ? a : 0xFFFFFFFFu);
         }
@@ -164,17 +180,20 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
     if (lane == 0) atomicMin(&ss->minnz_bits, minnz);
     __syncthreads();
 
-    // ---- exclusive scan of the bucket counts: 8 consecutive counters per thread (the last thread takes the rest) ----
+    // ---- exclusive scan of the bucket counts: consecutive counters per thread (the last thread takes the rest) ----
     {
-      constexpr int per = kSortBuckets / NT;                 // 8
+      constexpr int per = kSortBuckets / NT;                 // counters per thread: 32 or 16
       constexpr int last_extra = kSortCounters - kSortBuckets;
-      uint32_t c[per + last_extra], s = 0;
+      constexpr int words = (per + last_extra) / 2;
+      uint32_t cw[words], s = 0;
       const int mine = tid == NT - 1 ? per + last_extra : per;
 #pragma unroll
-      for (int k = 0; k < per + last_extra; ++k) {
-        c[k] = k < mine ? cur[tid * per + k] : 0u;
-        s += c[k];
-        if (c[k] > kSortBigBucket && tid * per + k != zero_bucket) ss->big_bucket = 1u;   // benign race: every writer stores 1
+      for (int k = 0; k < words; ++k) {
+        cw[k] = 2 * k < mine ? cntw[(tid * per) / 2 + k] : 0u;
+        const uint32_t c0 = cw[k] & 0xFFFFu, c1 = cw[k] >> 16;
+        s += c0 + c1;
+        if ((c0 > kSortBigBucket && tid * per + 2 * k != zero_bucket) || (c1 > kSortBigBucket && tid * per + 2 * k + 1 != zero_bucket))
+          ss->big_bucket = 1u;                               // benign race: every writer stores 1
       }
       const uint32_t inc = wave_scan_inclusive(s);
       if (lane == kWave - 1) ss->wcnt[wave] = inc;
@@ -183,19 +202,19 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
 #pragma unroll
       for (int w = 0; w < NW; ++w) a += (uint32_t)w < wave ? ss->wcnt[w] : 0u;
 #pragma unroll
-      for (int k = 0; k < per + last_extra; ++k) {
-        if (k < mine) {
-          start[tid * per + k] = a;
-          cur[tid * per + k] = a;
-          a += c[k];
+      for (int k = 0; k < words; ++k) {
+        if (2 * k < mine) {
+          const uint32_t c0 = cw[k] & 0xFFFFu, c1 = cw[k] >> 16;
+          cntw[(tid * per) / 2 + k] = a | ((a + c0) << 16);  // first positions: at most cols <= 32768, 16 bits hold them
+          a += c0 + c1;
         }
       }
     }
     __syncthreads();
     const bool ranked = ss->big_bucket == 0u;
 
-    // ---- scatter into the buckets (any order inside a bucket) ----
-#pragma unroll 1
+    // ---- into the buckets, in arrival order ----
+#pragma unroll
     for (int i = 0; i < K; ++i) {
       const uint32_t ch = (uint32_t)i * NT + tid;
       if (ch < nchunks) {
@@ -204,8 +223,8 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const uint32_t h = (w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
-          const uint32_t pos = atomicAdd(&cur[bucket(widen16<DT>(h))], 1u);
-          tmp[pos] = (uint16_t)h;
+          const uint32_t slot = (slots[i][k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
+          tmp[cnt[bucket(widen16<DT>(h))] + slot] = (uint16_t)h;
         }
       }
     }
@@ -218,7 +237,7 @@ __global__ __launch_bounds__(kSortThreads) void sorted_prepare(const MatDesc* __
       const uint32_t b = bucket(x);
       uint32_t at = p;
       if (ranked && b != zero_bucket) {
-        const uint32_t a = start[b], e = start[b + 1];
+        const uint32_t a = cnt[b], e = cnt[b + 1];
         uint32_t rank = 0;
         for (uint32_t q = a; q < e; ++q) {
           const float y = widen16<DT>(tmp[q]);
@@ -304,10 +323,23 @@ __device__ __forceinline__ double row16_sum(double v) {
   return v;
 }
 
+// The window of the row's record that a lane keeps in LDS: kWinChunks consecutive chunks (8 values
+// and the prefix sum in front of them each) around its boundary, as a ring (chunk c sits in slot
+// c mod kWinChunks).  A step of Adam moves a boundary by a few dozen positions at most, so nearly
+// every probe is served from the window.  After each search the window is moved by up to kWinFetch
+// chunks towards where the boundary is heading (its chunk plus the last move): their loads are issued
+// before the scalar recurrence and land in the ring at the start of the next search, so their latency
+// stays off the critical path.  A probe
+// outside the window (the first steps, when the range still moves fast) refills it whole.
+constexpr int kWinChunks = 4;
+constexpr int kWinFetch = 2;
+constexpr int kWinStride = kWinChunks * 24 + 16;             // bytes per lane (a multiple of 16)
+
 template <int DT>
 __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restrict__ mats, const SortSeg* __restrict__ segs,
                                                          int nsegs, int total_groups, const EQ_GLOBAL unsigned char* __restrict__ ws,
                                                          KParams kp) {
+  __shared__ __align__(16) unsigned char win_all[kWave * kWinStride];
   const int lane = (int)threadIdx.x;
   const int group = (int)blockIdx.x;
   if (group >= total_groups) return;
@@ -329,6 +361,15 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
   }
   const EQ_GLOBAL unsigned char* srow = rec + kSortRecHeader;
   const EQ_GLOBAL double* P = (const EQ_GLOBAL double*)(rec + kSortRecHeader + (size_t)N * 2);
+  unsigned char* win = win_all + lane * kWinStride;          // values at 0, prefix sums at 16 * kWinChunks
+  int wj0 = 0;                                               // the window holds chunks [wj0, wj0 + kWinChunks)
+  bool wvalid = false;
+  int pf_shift = 0;                                          // chunks on their way: up to +-kWinFetch towards higher / lower positions
+  int j_last = 0;                                            // chunk of the boundary at the last search
+  uint4 pf_q[kWinFetch];
+  double pf_P[kWinFetch];
+  auto win_q = [&](int c) -> uint4& { return *reinterpret_cast<uint4*>(win + (c & (kWinChunks - 1)) * 16); };
+  auto win_P = [&](int c) -> double& { return *reinterpret_cast<double*>(win + kWinChunks * 16 + (c & (kWinChunks - 1)) * 8); };
 
   const int b = lane & 15;
   const int nbound = kp.L;                                   // boundaries between neighbouring levels (<= 15)
@@ -361,15 +402,70 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
       // ---- n = number of elements whose level is <= lev, and P[n] ----
       // Probes of whole 8-element chunks, starting with the one that held the boundary last time:
       // inside the chunk the boundary is found at once; a chunk entirely on one side moves the search
-      // on, by doubling steps until the boundary is bracketed, then by halving.
+      // on, by doubling steps until the boundary is bracketed, then by halving.  The first search of a
+      // row halves from the start and reads the record itself.
+      const bool first = t == 0;
       int nlo = 0, nhi = N, d = 1;
       int j = min(n >> 3, nblk - 1);
-      bool have_lo = false, have_hi = false, done = false;
+      bool have_lo = first, have_hi = first, done = false;
       double Pn = 0.0;
+      if (pf_shift != 0) {
+        // the chunks asked for after the last search have arrived: into the ring
+        const int m = pf_shift > 0 ? pf_shift : -pf_shift;
+#pragma unroll
+        for (int k = 0; k < kWinFetch; ++k) {
+          if (k < m) {
+            const int c = pf_shift > 0 ? wj0 + kWinChunks + k : wj0 - 1 - k;
+            win_q(c) = pf_q[k];
+            win_P(c) = pf_P[k];
+          }
+        }
+        wj0 += pf_shift;
+        pf_shift = 0;
+      }
+      if (wvalid) {
+        // the window first: the levels of its chunks' first values tell which chunk holds the boundary
+        // (c of them are on the lower side, whatever their order in the ring), or that it lies outside
+        int c = 0;
+#pragma unroll
+        for (int k = 0; k < kWinChunks; ++k) {
+          const float x0 = widen16<DT>(*reinterpret_cast<const uint16_t*>(win + k * 16));   // slot k, some chunk of the window
+          c += __builtin_fmaf(x0, inv, kMagic) <= thr ? 1 : 0;
+        }
+        if (c > 0) {
+          j = wj0 + c - 1;
+          nlo = 8 * j;
+          have_lo = true;
+          if (c < kWinChunks) { nhi = 8 * j + 8; have_hi = true; }
+        } else {
+          nhi = 8 * wj0;                                     // P[nhi] = 0 if this is the row's start, else found by the probes
+          have_hi = true;
+          j = max(wj0 - 1, 0);
+          if (wj0 == 0) { n = 0; done = true; }
+        }
+      }
       while (!__all(done)) {
         if (!done) {
-          const uint4 q = global_load128(srow + (size_t)j * 16);
-          const double Pj = P[j];
+          uint4 q;
+          double Pj;
+          if (first) {
+            q = global_load128(srow + (size_t)j * 16);
+            Pj = P[j];
+          } else {
+            if (!wvalid || j < wj0 || j >= wj0 + kWinChunks) {
+              // refill, with j in the middle
+              wj0 = max(0, min(j - kWinChunks / 2 + 1, nblk - kWinChunks));
+              wvalid = true;
+#pragma unroll
+              for (int k = 0; k < kWinChunks; ++k) {
+                const int c = wj0 + k;
+                win_q(c) = global_load128(srow + (size_t)c * 16);
+                win_P(c) = P[c];
+              }
+            }
+            q = win_q(j);
+            Pj = win_P(j);
+          }
           const uint32_t w[4] = {q.x, q.y, q.z, q.w};
           int cnt = 0;
           double part = 0.0;
@@ -393,6 +489,25 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
       }
       ia = wA * n;
       db = counts ? Pn : 0.0;
+      const int j_now = min(n, N - 1) >> 3;
+      const int j_next = j_now + (t > 0 ? j_now - j_last : 0);
+      j_last = j_now;
+      if (wvalid && !last) {
+        // the window's middle goes where the boundary is heading: ask for the next chunks on that side
+        // now, they are stored when the next search begins
+        const int want0 = max(0, min(j_next - kWinChunks / 2 + 1, nblk - kWinChunks));
+        const int shift = want0 - wj0;
+        pf_shift = shift > kWinFetch ? kWinFetch : shift < -kWinFetch ? -kWinFetch : shift;
+        if (pf_shift != 0) {
+#pragma unroll
+          for (int k = 0; k < kWinFetch; ++k) {
+            int c = pf_shift > 0 ? wj0 + kWinChunks + k : wj0 - 1 - k;
+            c = max(0, min(c, nblk - 1));                    // (those beyond the shift are not used)
+            pf_q[k] = global_load128(srow + (size_t)c * 16);
+            pf_P[k] = P[c];
+          }
+        }
+      }
     } else {
       // ---- element by element (binary64 accumulation of exact products, like the general kernel) ----
       const float fclo = (float)clo, fchi = (float)chi;

@@ -27,8 +27,9 @@ enum {
   EQ_OVR_MATVEC_LOOKUP = 5,  /* eq_dequant_matvec, 4-bit codes with one range per row: 1 = half of the pairs of
                                 weights from the table of pairs and half from the table of single values,
                                 2 = all from the table of single values (default: all from the table of pairs) */
-  EQ_OVR_SORTED_ROWS = 6,    /* 1: rows with one range each and at most 4 bits are optimised element by element
-                                (the per-channel lane kernels) instead of from their sorted values */
+  EQ_OVR_SORTED_ROWS = 6,    /* rows with one range each and at most 4 bits: 1 = always optimised element by element
+                                (the per-channel lane kernels), 2 = from their sorted values whatever the number of
+                                steps (default: from 64 steps on) */
   EQ_OVR_SORT_CHUNK_ROWS = 7, /* n > 0: at most n rows (rounded down to a multiple of 4) per chunk of the sorted
                                  evaluation, instead of as many as 2 GiB of records hold */
   EQ_OVR_COUNT = 8
@@ -45,6 +46,16 @@ EQ_API int eq_test_set_override(int which, int64_t value);   /* EQ_OK or EQ_E_PA
  * (row-length class) it belongs to. */
 EQ_API int64_t eq_test_plan_items(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
                                   const eq_params* p, int32_t* items, int32_t* launch_of_item, int64_t max_items);
+
+/* The chunks of the sorted evaluation of rows with one range each for these shapes (host only):
+ * writes up to max_segs segments, seven numbers each, into `segs` and returns the number of
+ * segments of the plan, or a negative EQ_E_* code.  A segment is (chunk, matrix, first row, rows,
+ * index of its first group of 4 rows in the chunk, index of its first row in the chunk, byte offset
+ * of its first record in the chunk's region of the workspace): a run of rows of one matrix whose
+ * records lie one after the other.  `record_region_bytes`, if not NULL, receives the size of that
+ * region (the largest chunk). */
+EQ_API int64_t eq_test_plan_sort_segments(int32_t n, const int64_t* rows, const int64_t* cols, const int64_t* out_capacity,
+                                          const eq_params* p, int64_t* segs, int64_t max_segs, int64_t* record_region_bytes);
 
 /* The library divides by values whose correctly rounded reciprocal it knows (Adam's bias
  * corrections, the level count D) with a short multiply-add sequence instead of a hardware

@@ -17,22 +17,27 @@ static unsigned prepare_grid(int64_t rows, size_t lds) {
 template <int DT>
 SortKernels pick_sorted_kernels(const LaneClass& lc) {
   SortKernels k;
-  const int64_t per_thread = ((int64_t)lc.cols / 8 + kSortThreads - 1) / kSortThreads;
-#define EQ_SORT_VARIANT(K_)                                                                                          \
+  const int64_t nchunks = (int64_t)lc.cols / 8;
+  const int nt = lc.cols <= 8192 ? 256 : 512;
+  const int64_t per_thread = (nchunks + nt - 1) / nt;
+#define EQ_SORT_VARIANT(NT_, K_, NB_)                                                                                  \
   {                                                                                                                  \
-    k.prepare_fn = reinterpret_cast<const void*>(&sorted_prepare<DT, K_>);                                           \
-    k.prepare_lds = sort_prepare_lds(sort_header_bytes<K_>(), lc.cols);                                              \
+    k.prepare_fn = reinterpret_cast<const void*>(&sorted_prepare<DT, NT_, K_, NB_>);                                      \
+    k.prepare_lds = sort_prepare_lds(sort_header_bytes<NT_>(), lc.cols, NB_);                                             \
     k.prepare = [](const LaneClass& c, const SortLaunchArgs& a, const KParams& kp, hipStream_t s) {                  \
-      const size_t lds = sort_prepare_lds(sort_header_bytes<K_>(), c.cols);                                          \
-      hipLaunchKernelGGL((sorted_prepare<DT, K_>), dim3(prepare_grid(a.rows, lds)), dim3(kSortThreads), lds, s,      \
+      const size_t lds = sort_prepare_lds(sort_header_bytes<NT_>(), c.cols, NB_);                                         \
+      hipLaunchKernelGGL((sorted_prepare<DT, NT_, K_, NB_>), dim3(prepare_grid(a.rows, lds)), dim3(NT_), lds, s,          \
                          a.mats, a.segs, (int)a.nsegs, a.rows, (EQ_GLOBAL unsigned char*)a.ws, kp);                  \
     };                                                                                                               \
   }
-  if (per_thread <= 1) EQ_SORT_VARIANT(1)
-  else if (per_thread <= 2) EQ_SORT_VARIANT(2)
-  else if (per_thread <= 4) EQ_SORT_VARIANT(4)
-  else if (per_thread <= 8) EQ_SORT_VARIANT(8)
-  else if (per_thread <= 16) EQ_SORT_VARIANT(16)
+  if (nt == 256) {
+    if (per_thread <= 1) EQ_SORT_VARIANT(256, 1, 4096)
+    else if (per_thread <= 2) EQ_SORT_VARIANT(256, 2, 4096)
+    else EQ_SORT_VARIANT(256, 4, 4096)
+  } else {
+    if (per_thread <= 4) EQ_SORT_VARIANT(512, 4, 8192)
+    else if (per_thread <= 8) EQ_SORT_VARIANT(512, 8, 8192)
+  }
 #undef EQ_SORT_VARIANT
   k.iterate = [](const LaneClass&, const SortLaunchArgs& a, const KParams& kp, hipStream_t s) {
     hipLaunchKernelGGL((sorted_iterate<DT>), dim3((unsigned)a.groups), dim3(kWave), 0, s, a.mats, a.segs, (int)a.nsegs,

@@ -30,8 +30,7 @@ def _check(W, p, what, batch=True, deq=True):
 
 @pytest.mark.parametrize("evaluation", ["sorted", "direct"])
 def test_config1_per_channel_symmetric_and_asymmetric(evaluation, eq_override):
-    if evaluation == "direct":
-        eq_override(eqg.OVR_SORTED_ROWS, 1)
+    eq_override(eqg.OVR_SORTED_ROWS, 1 if evaluation == "direct" else 2)
     (_, W), = eq_inputs.gen_config_small("c1", DEV)
     for mode in (eqo.ASYMMETRIC, eqo.SYMMETRIC):
         p = eqo.Params(bits=4, group_size=0, mode=mode, iters=100)
@@ -78,8 +77,7 @@ def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, evaluati
     # "sorted" (the library's choice for at most 4 bits): the sums from the row's sorted values.
     if units_per_item:
         eq_override(eqg.OVR_UNITS_PER_ITEM, units_per_item)
-    if evaluation == "direct":
-        eq_override(eqg.OVR_SORTED_ROWS, 1)
+    eq_override(eqg.OVR_SORTED_ROWS, 1 if evaluation == "direct" else 2)
     W = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=rows * 7 + cols, device=DEV)
     for bits, mode in ((4, eqo.SYMMETRIC), (3, eqo.ASYMMETRIC)):
         res = _check(W, eqo.Params(bits=bits, group_size=0, mode=mode, iters=12), f"channel kernel {rows}x{cols}")
@@ -89,8 +87,7 @@ def test_per_channel_lane_kernel_row_shapes(rows, cols, units_per_item, evaluati
 @pytest.mark.parametrize("evaluation", ["sorted", "direct"])
 @pytest.mark.parametrize("cols", [22016, 11008])
 def test_per_channel_rows_cut_into_equal_pieces(cols, evaluation, eq_override):
-    if evaluation == "direct":
-        eq_override(eqg.OVR_SORTED_ROWS, 1)
+    eq_override(eqg.OVR_SORTED_ROWS, 1 if evaluation == "direct" else 2)
     # rows of 86 * 256 or 86 * 128 values with 4-bit codes take the kernel that cuts a row into
     # equal pieces over all 256 lanes: its variants, its binary64 fallback, and the 128-element
     # kernel it replaces on the same input
@@ -142,8 +139,7 @@ def test_per_channel_without_optimisation_steps(rows, cols, eq_override):
 
 @pytest.mark.parametrize("evaluation", ["sorted", "direct"])
 def test_per_channel_lane_kernel_variants(evaluation, eq_override):
-    if evaluation == "direct":
-        eq_override(eqg.OVR_SORTED_ROWS, 1)
+    eq_override(eqg.OVR_SORTED_ROWS, 1 if evaluation == "direct" else 2)
     W = eq_inputs.gen_matrix(19, 4096, eq_inputs.RECIPES["c5"], seed=77, device=DEV)
     _check(W, eqo.Params(bits=4, group_size=0, iters=0), "channel T=0")
     _check(W, eqo.Params(bits=4, group_size=0, iters=1), "channel T=1")
@@ -164,6 +160,7 @@ def test_sorted_rows_in_chunks_and_rows_it_evaluates_directly(chunk_rows, eq_ove
     # another (two launches), cut into chunks of a few rows (segments that start and end inside a matrix,
     # groups of 4 rows with absent rows), and the rows the sorted evaluation does not take: many equal
     # values (left unsorted), sums that binary64 cannot hold exactly, all-zero rows
+    eq_override(eqg.OVR_SORTED_ROWS, 2)                  # also with few steps
     if chunk_rows:
         eq_override(eqg.OVR_SORT_CHUNK_ROWS, chunk_rows)
     Ws = [eq_inputs.gen_matrix(r, c, eq_inputs.RECIPES["c5"], seed=900 + r, device=DEV) for r, c in ((21, 4096), (7, 4096), (30, 4096), (10, 5120))]

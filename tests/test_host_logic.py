@@ -85,6 +85,57 @@ def test_plan_items_cover_every_row_exactly_once(lib):
             assert (covered[m] == (1 if served_by_lanes else 0)).all(), (m, r, c, p.group_size)
 
 
+def test_sorted_evaluation_chunks_cover_their_rows_and_fit_the_record_region(lib):
+    """Host side of the sorted evaluation of per-channel rows: the segments of all chunks tile the rows of
+    every eligible matrix once, a chunk holds one row length, its records lie back to back inside the
+    region the workspace reserves, and the groups of 4 rows are counted per segment."""
+    import paper_2403_02775_amd as eqg
+    shapes = [(8192, 8192), (22016, 8192), (8192, 22016), (100, 4096), (7, 1024), (0, 4096), (33, 2048), (5, 8192)]
+    rows, cols = [s[0] for s in shapes], [s[1] for s in shapes]
+    caps = [1000] * len(shapes)
+
+    def record_bytes(c):
+        return (32 + 2 * c + 8 * (c // 8 + 1) + 63) // 64 * 64
+
+    for chunk_rows in (0, 1000, 6):
+        eqg.set_override(eqg.OVR_SORT_CHUNK_ROWS, chunk_rows)
+        try:
+            p = eqg.Params(group_size=0, iters=100, bits=4)
+            segs, region = eqg.plan_sort_segments(rows, cols, caps, p)
+            with_region = eqg.eq_workspace_bytes(rows, cols, caps, p)
+            eqg.set_override(eqg.OVR_SORTED_ROWS, 1)
+            without = eqg.eq_workspace_bytes(rows, cols, caps, p)
+            assert eqg.plan_sort_segments(rows, cols, caps, p)[0] == []
+            eqg.set_override(eqg.OVR_SORTED_ROWS, 0)
+        finally:
+            eqg.set_override(eqg.OVR_SORT_CHUNK_ROWS, 0)
+            eqg.set_override(eqg.OVR_SORTED_ROWS, 0)
+        assert with_region > region > 0 and with_region > without      # (the two plans also differ in their work items)
+        covered = {m: np.zeros(r, np.int32) for m, r in enumerate(rows)}
+        by_chunk = {}
+        for chunk, m, r0, nr, g0, first_row, off in segs:
+            assert nr > 0 and 0 <= r0 and r0 + nr <= rows[m]
+            covered[m][r0:r0 + nr] += 1
+            by_chunk.setdefault(chunk, []).append((m, nr, g0, first_row, off))
+        for m, (r, c) in enumerate(shapes):
+            eligible = r > 0 and c % 128 == 0 and 2048 <= c <= 32768
+            assert (covered[m] == (1 if eligible else 0)).all(), (m, r, c)
+        limit = chunk_rows if chunk_rows else (2 << 30) // record_bytes(8192)
+        for chunk, lst in by_chunk.items():
+            assert len({cols[m] for m, *_ in lst}) == 1                 # one row length per chunk
+            rb = record_bytes(cols[lst[0][0]])
+            nrows = ngroups = 0
+            for m, nr, g0, first_row, off in lst:
+                assert first_row == nrows and g0 == ngroups and off == nrows * rb
+                nrows += nr
+                ngroups += (nr + 3) // 4
+            assert nrows * rb <= region
+            assert nrows <= max(4, limit // 4 * 4)
+    # few steps, wide codes or short rows: no sorted evaluation
+    for p in (eqg.Params(group_size=0, iters=10), eqg.Params(group_size=0, iters=100, bits=8), eqg.Params(group_size=128, iters=100)):
+        assert eqg.plan_sort_segments(rows, cols, caps, p)[0] == []
+
+
 def test_benchmark_refuses_more_than_one_gpu():
     # every box has one GPU; the benchmark says so instead of pretending to scale
     import os
