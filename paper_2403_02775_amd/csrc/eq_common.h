@@ -80,18 +80,18 @@ struct SortSeg {
   int64_t first_row;        // index of its first row among the launch's rows
   int64_t ws_off;           // byte offset of its first record
 };
-// A row's record: header, the cols 16-bit values in ascending order (outliers as 0), and the exact
-// binary64 sums of the first 8 j values for j = 0 .. cols / 8.
+// A row's record: a header (SortRecHeader, then the sum of all values at byte 16), then one 32-byte unit
+// per chunk of 8 values in ascending order (outliers as 0): the 8 16-bit values, the exact binary64 sum
+// of all values in front of them, 8 unused bytes.  A probe of a chunk therefore reads one cache line.
 struct SortRecHeader {
   float r0;                 // initial range
   int32_t z;                // zero-point
   uint32_t flags;           // kRecExactSums | kRecSorted
   uint32_t pad;
 };
-constexpr size_t kSortRecHeader = 32;
-__host__ __device__ inline size_t sort_record_bytes(int64_t cols) {
-  return (kSortRecHeader + (size_t)cols * 2 + ((size_t)cols / 8 + 1) * 8 + 63) & ~(size_t)63;
-}
+constexpr size_t kSortRecHeader = 64;
+constexpr size_t kSortUnit = 32;
+__host__ __device__ inline size_t sort_record_bytes(int64_t cols) { return kSortRecHeader + ((size_t)cols / 8) * kSortUnit; }
 
 // Relaxed device-scope atomics on global memory (the HIP wrappers take generic pointers).
 __device__ __forceinline__ unsigned long long global_atomic_add(EQ_GLOBAL unsigned long long* p, unsigned long long v) {

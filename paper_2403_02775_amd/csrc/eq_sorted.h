@@ -16,7 +16,8 @@
 //                    mask, outliers replaced by 0; nothing written to the outlier list here), then
 //                    sorts the 16-bit values in LDS (counting sort into 2048 value-linear buckets,
 //                    ranks inside a bucket by counting) and writes a record per row to the
-//                    workspace: header, sorted values, exact prefix sums at every 8th position.
+//                    workspace: header, then per chunk of 8 sorted values the values and the exact sum of
+//                    everything in front of them.
 //   sorted_iterate : 16 lanes per row, one per boundary, 4 rows per wavefront; Adam on the range
 //                    (Algorithm 1, second step); leaves the chosen range of every row.
 // The codes, scales, zero-points and the outlier list are then written by the kernel without
@@ -100,11 +101,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(sort_waves_p
   unsigned char* pool = smem + sort_header_bytes<NT>();
   const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
+  // (descriptors and segments are read where they are used, through pointers that are the same for
+  // the whole workgroup: copies of them that change from row to row would live in scratch memory)
   int64_t j = blockIdx.x;
   if (j >= total_rows) return;
-  SortSeg sg = segs[find_seg_by_row(segs, nsegs, j)];
-  MatDesc md = mats[sg.mat];
-  const uint32_t cols = (uint32_t)md.cols, nchunks = cols >> 3, upr = cols >> 7;   // the same for every row of the launch
+  const SortSeg* sg = segs + find_seg_by_row(segs, nsegs, j);
+  const MatDesc* md = mats + sg->mat;
+  const uint32_t cols = (uint32_t)md->cols, nchunks = cols >> 3, upr = cols >> 7;   // the same for every row of the launch
   uint16_t* tmp = reinterpret_cast<uint16_t*>(pool + (size_t)upr * kSlotBytes);
   uint32_t* cntw = reinterpret_cast<uint32_t*>(tmp + cols); // 16-bit counts, then the buckets' first positions, in pairs
   const uint16_t* cnt = reinterpret_cast<const uint16_t*>(cntw);
@@ -112,15 +115,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(sort_waves_p
   const size_t rec_bytes = sort_record_bytes(cols);
 
   uint4 v[1][K];
-  int64_t row = sg.row0 + (j - sg.first_row);
-  batch_issue_loads<NT, 1, K, true>(md, row, 1, v);
+  int64_t row = sg->row0 + (j - sg->first_row);
+  batch_issue_loads<NT, 1, K, true>(*md, row, 1, v);
   for (;;) {
     const int64_t jn = j + gridDim.x;
     const bool more = jn < total_rows;
-    SortSeg sgn = sg;
-    if (more && jn >= sg.first_row + sg.nrows) sgn = segs[find_seg_by_row(segs, nsegs, jn)];
-    const MatDesc mdn = (more && sgn.mat != sg.mat) ? mats[sgn.mat] : md;
-    const int64_t rown = more ? sgn.row0 + (jn - sgn.first_row) : row;
+    const SortSeg* sgn = sg;
+    if (more && jn >= sg->first_row + sg->nrows) sgn = segs + find_seg_by_row(segs, nsegs, jn);
+    const MatDesc* mdn = mats + sgn->mat;
+    const int64_t rown = more ? sgn->row0 + (jn - sgn->first_row) : row;
 
     if (tid == 0) {
       sc->rowmax_bits[0] = 0;
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(sort_waves_p
       ss->big_bucket = 0;
     }
     for (uint32_t i = tid; i < (uint32_t)kSortCounters / 2; i += NT) cntw[i] = 0;
-    stage_loaded_rows<DT, NT, 1, K, Padded128Layout, true, false>(md, kp, row, 1, pool, 0u, nullptr, sc, v, [&] {
-      batch_issue_loads<NT, 1, K, true>(mdn, rown, more ? 1 : 0, v);
+    stage_loaded_rows<DT, NT, 1, K, Padded128Layout, true, false>(*md, kp, row, 1, pool, 0u, nullptr, sc, v, [&] {
+      batch_issue_loads<NT, 1, K, true>(*mdn, rown, more ? 1 : 0, v);
     });
     __syncthreads();                                         // wavefront-major staging ends without one
 
@@ -249,10 +252,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(sort_waves_p
     }
     __syncthreads();
 
-    // ---- the record: header, values, exact prefix sums at every 8th position ----
-    EQ_GLOBAL unsigned char* rec = ws + sg.ws_off + (size_t)(j - sg.first_row) * rec_bytes;
+    // ---- the record: header, then per chunk its 8 values and the exact sum of all values in front of them ----
+    EQ_GLOBAL unsigned char* rec = ws + sg->ws_off + (size_t)(j - sg->first_row) * rec_bytes;
     {
-      for (uint32_t c = tid; c < nchunks; c += NT) global_store128(rec + kSortRecHeader + (size_t)c * 16, reinterpret_cast<const uint4*>(out)[c]);
+      for (uint32_t c = tid; c < nchunks; c += NT) global_store128(rec + kSortRecHeader + (size_t)c * kSortUnit, reinterpret_cast<const uint4*>(out)[c]);
       const uint32_t cpt = (nchunks + NT - 1) / NT;
       const uint32_t c0 = min(tid * cpt, nchunks), c1 = min(c0 + cpt, nchunks);
       auto chunk_sum = [&](uint32_t c) {
@@ -276,12 +279,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(sort_waves_p
       double a = inc - s;
 #pragma unroll
       for (int w = 0; w < NW; ++w) a += (uint32_t)w < wave ? ss->wsum[w] : 0.0;
-      EQ_GLOBAL double* P = (EQ_GLOBAL double*)(rec + kSortRecHeader + (size_t)cols * 2);
       for (uint32_t c = c0; c < c1; ++c) {
-        P[c] = a;
+        *(EQ_GLOBAL double*)(rec + kSortRecHeader + (size_t)c * kSortUnit + 16) = a;
         a += chunk_sum(c);
       }
-      if (c1 == nchunks && c0 < c1) P[nchunks] = a;
+      if (c1 == nchunks && c0 < c1) *(EQ_GLOBAL double*)(rec + 16) = a;   // the sum of the whole row
       if (tid == 0) {
         float r0;
         int z;
@@ -359,8 +361,9 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
     const uint4 q = global_load128(rec);
     hd.r0 = __uint_as_float(q.x); hd.z = (int32_t)q.y; hd.flags = q.z; hd.pad = 0;
   }
-  const EQ_GLOBAL unsigned char* srow = rec + kSortRecHeader;
-  const EQ_GLOBAL double* P = (const EQ_GLOBAL double*)(rec + kSortRecHeader + (size_t)N * 2);
+  const EQ_GLOBAL unsigned char* units = rec + kSortRecHeader;   // per chunk: 8 values, then the sum of all values in front of them
+  auto unit_q = [&](int c) { return global_load128(units + (size_t)c * kSortUnit); };
+  auto unit_P = [&](int c) { return *(const EQ_GLOBAL double*)(units + (size_t)c * kSortUnit + 16); };
   unsigned char* win = win_all + lane * kWinStride;          // values at 0, prefix sums at 16 * kWinChunks
   int wj0 = 0;                                               // the window holds chunks [wj0, wj0 + kWinChunks)
   bool wvalid = false;
@@ -379,7 +382,7 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
   const int wA = counts ? 2 * lev + 1 : 0;
   const float thr = kMagic + (float)lev;                     // exact: a small integer next to 1.5 * 2^23
   const bool fast = (hd.flags & (kRecExactSums | kRecSorted)) == (kRecExactSums | kRecSorted);
-  const double PN = P[nblk];
+  const double PN = *(const EQ_GLOBAL double*)(rec + 16);
   const bool act = hd.r0 > 0.0f;
 
   float r32 = act ? hd.r0 : kp.D, r_sel = r32;               // an all-zero row keeps s = 1
@@ -449,8 +452,8 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
           uint4 q;
           double Pj;
           if (first) {
-            q = global_load128(srow + (size_t)j * 16);
-            Pj = P[j];
+            q = unit_q(j);
+            Pj = unit_P(j);
           } else {
             if (!wvalid || j < wj0 || j >= wj0 + kWinChunks) {
               // refill, with j in the middle
@@ -459,8 +462,8 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
 #pragma unroll
               for (int k = 0; k < kWinChunks; ++k) {
                 const int c = wj0 + k;
-                win_q(c) = global_load128(srow + (size_t)c * 16);
-                win_P(c) = P[c];
+                win_q(c) = unit_q(c);
+                win_P(c) = unit_P(c);
               }
             }
             q = win_q(j);
@@ -503,8 +506,8 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
           for (int k = 0; k < kWinFetch; ++k) {
             int c = pf_shift > 0 ? wj0 + kWinChunks + k : wj0 - 1 - k;
             c = max(0, min(c, nblk - 1));                    // (those beyond the shift are not used)
-            pf_q[k] = global_load128(srow + (size_t)c * 16);
-            pf_P[k] = P[c];
+            pf_q[k] = unit_q(c);
+            pf_P[k] = unit_P(c);
           }
         }
       }
@@ -512,7 +515,7 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
       // ---- element by element (binary64 accumulation of exact products, like the general kernel) ----
       const float fclo = (float)clo, fchi = (float)chi;
       for (int ch = b; ch < nblk; ch += 16) {
-        const uint4 q = global_load128(srow + (size_t)ch * 16);
+        const uint4 q = unit_q(ch);
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int k = 0; k < 8; ++k) {

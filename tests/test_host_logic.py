@@ -95,7 +95,7 @@ def test_sorted_evaluation_chunks_cover_their_rows_and_fit_the_record_region(lib
     caps = [1000] * len(shapes)
 
     def record_bytes(c):
-        return (32 + 2 * c + 8 * (c // 8 + 1) + 63) // 64 * 64
+        return 64 + 32 * (c // 8)                        # header, then 32 bytes per chunk of 8 values
 
     for chunk_rows in (0, 1000, 6):
         eqg.set_override(eqg.OVR_SORT_CHUNK_ROWS, chunk_rows)
