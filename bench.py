@@ -260,7 +260,7 @@ def main():
     ap.add_argument("--group-size", type=int, default=128, help="0 = one range per output channel (secondary measurement)")
     ap.add_argument("--channel-evaluation", choices=["auto", "direct", "sorted"], default="auto",
                     help="rows with one range each (--group-size 0): element-by-element kernels, or the evaluation from sorted rows "
-                         "(auto: the library's choice, sorted from 64 steps on)")
+                         "(auto: the library's choice, sorted when steps x columns >= 800 000)")
     ap.add_argument("--stat-scope", choices=["row", "matrix"], default="row",
                     help="scope of mean / sigma in the outlier criterion; matrix = Eq. 3 as printed (secondary measurement)")
     ap.add_argument("--select", choices=["best", "last"], default="best",
@@ -344,11 +344,12 @@ def main():
         eqg.set_override(eqg.OVR_SORTED_ROWS, 1 if args.channel_evaluation == "direct" else 2)
 
     def kernel_name(q):
-        # one range per row, at most 4 bits, 64 steps or more: Adam runs on the sorted rows (sorted_prepare,
-        # sorted_iterate), the kernel without optimisation steps emits
+        # one range per row, at most 4 bits, steps x columns >= 800 000: Adam runs on the sorted rows
+        # (sorted_prepare, sorted_iterate), the kernel without optimisation steps emits
         return ("quantize_rtn128" if q.iters == 0 and q.group_size in (0, 128) else "quantize_units128" if q.group_size == 128
-                else ("sorted_rows" if args.channel_evaluation != "direct" and q.bits <= 4 and
-                      (q.iters >= 64 or args.channel_evaluation == "sorted") else "quantize_channels") if q.group_size == 0
+                else ("sorted_rows" if args.channel_evaluation != "direct" and q.bits <= 4 and q.iters > 0 and
+                      (q.iters * max(w.shape[1] for w in Ws) >= (800000 if dt == "f16" else 1600000) or args.channel_evaluation == "sorted")
+                      else "quantize_channels") if q.group_size == 0
                 else "quantize_rows_generic")
 
     def timed(q, q_outs, steps, warmup, label):

@@ -165,7 +165,7 @@ struct Plan {
 // sorted_iterate to fill the chip several times over).
 constexpr size_t kSortBudgetBytes = (size_t)2 << 30;
 constexpr int64_t kSortMinCols = 2048;
-constexpr int kSortMinIters = 64;
+constexpr int64_t kSortMinWork = 800000;         // steps x columns from which rows are optimised from their sorted values
 
 int64_t clamp_capacity(int64_t c) { return c < 0 ? 0 : (c > 0xFFFFFFFEll ? 0xFFFFFFFEll : c); }
 
@@ -231,11 +231,15 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     const bool chan_keep128 = override_of(EQ_OVR_CHANNEL_KERNEL) == 128;
     // one range per row, at most 4 bits, optimisation steps: Adam runs on the sorted rows (eq_sorted.h)
     // and the kernel without optimisation steps emits at the ranges it leaves
-    // (sorting costs about as much as 60 to 90 direct evaluations of the row, an evaluation from the
-    // sorted row a sixth to a half of a direct one: from 64 steps on)
+    // (sorting costs about as much as 60 to 90 direct evaluations of the row; a step from the sorted row
+    // costs the same whatever the row's length, a sixth to a half of a direct pass over 8192 elements
+    // depending on how far a step moves the range: worth it from steps x columns = 800 000 on, i.e.
+    // 98 steps for rows of 8192, 37 for rows of 22016, 196 for rows of 4096; twice that for bf16, whose
+    // staging, done twice on this route, is the slower one: measured on the 7B-shaped bf16 set)
     const bool chan_sorted = pl.path[(size_t)order[k]] == 2 && p->bits <= 4 && allow_sorted && !chan_keep128 &&
                              c >= kSortMinCols && override_of(EQ_OVR_SORTED_ROWS) != 1 &&
-                             (p->iters >= kSortMinIters || (p->iters > 0 && override_of(EQ_OVR_SORTED_ROWS) == 2));
+                             ((int64_t)p->iters * c >= kSortMinWork * (p->dtype == EQ_BF16 ? 2 : 1) ||
+                              (p->iters > 0 && override_of(EQ_OVR_SORTED_ROWS) == 2));
     const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && (p->iters == 0 || chan_sorted) && !chan_keep128;
     if (pl.path[(size_t)order[k]] == 2 && !chan_rtn) {
       // per-channel: a round is floor(256 / segments) whole rows; items are multiples of that

@@ -100,7 +100,7 @@ def test_sorted_evaluation_chunks_cover_their_rows_and_fit_the_record_region(lib
     for chunk_rows in (0, 1000, 6):
         eqg.set_override(eqg.OVR_SORT_CHUNK_ROWS, chunk_rows)
         try:
-            p = eqg.Params(group_size=0, iters=100, bits=4)
+            p = eqg.Params(group_size=0, iters=400, bits=4)
             segs, region = eqg.plan_sort_segments(rows, cols, caps, p)
             with_region = eqg.eq_workspace_bytes(rows, cols, caps, p)
             eqg.set_override(eqg.OVR_SORTED_ROWS, 1)
@@ -131,6 +131,10 @@ def test_sorted_evaluation_chunks_cover_their_rows_and_fit_the_record_region(lib
                 ngroups += (nr + 3) // 4
             assert nrows * rb <= region
             assert nrows <= max(4, limit // 4 * 4)
+    # rows of 8192 from 98 steps on, rows of 2048 from 391
+    assert {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, iters=98))[0]} == {8192, 22016}
+    assert {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, iters=97))[0]} == {22016}
+    assert {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, iters=391))[0]} == {2048, 4096, 8192, 22016}
     # few steps, wide codes or short rows: no sorted evaluation
     for p in (eqg.Params(group_size=0, iters=10), eqg.Params(group_size=0, iters=100, bits=8), eqg.Params(group_size=128, iters=100)):
         assert eqg.plan_sort_segments(rows, cols, caps, p)[0] == []
