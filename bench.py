@@ -410,6 +410,11 @@ def main():
         roof = {"bound": "hbm", "achieved": m["alg_bytes"] / kern_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": m["kernel_hbm_frac"], "traffic": None}
     roof["traffic"] = measured_traffic(workload_key, args.iters, kernel)
+    if kernel == "sorted_rows":
+        # the lane-operations counted are those of an evaluation that visits every element in every pass; these
+        # kernels take the sums from the sorted row, so the fraction compares with that evaluation at peak
+        roof["note"] = ("frac = work of an element-by-element evaluation / time / ALU peak (can exceed 1: the sums come from "
+                        "sorted rows); issue figures of the kernels: profiles/sorted_rows_*_sq_counters.txt")
     roof.update({"kernel": kernel, "launches_per_step": m["launches_per_step"],
                  "kernel_ms_per_step": m["kernel_ms_per_step"], "avg_launch_ms": m["avg_launch_ms"],
                  "algorithmic_bytes": m["alg_bytes"], "hbm_frac": m["kernel_hbm_frac"],
