@@ -271,6 +271,10 @@ def test_config5_llama65b_per_channel_and_without_optimisation_steps(oracle_pool
     rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=0, iters=100), "c5 per channel", 0.0, 17)
     assert rows >= 9000
     torch.cuda.empty_cache()
+    # the paper's LLaMA setting at its granularity (500 steps, lr = 1e-4): the evaluation from sorted rows
+    rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=0, iters=500, lr=1e-4), "c5 per channel T=500", 0.0, 5)
+    assert rows >= 2500
+    torch.cuda.empty_cache()
     rows = _c5_sample(oracle_pool, Ws, eqo.Params(bits=4, group_size=128, iters=0), "c5 T=0", 0.02, 17)
     assert rows >= 140000
     torch.cuda.empty_cache()
