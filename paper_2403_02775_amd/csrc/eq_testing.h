@@ -3,7 +3,9 @@
  *
  * These symbols are exported by the library but are NOT part of its C ABI (include/easyquant.h):
  * they may change with the kernels.  Nothing here changes a result: the overrides only change
- * which of several equivalent kernels serves a matrix or how the rows are cut into work items.
+ * which of several equivalent kernels serves a matrix or how the rows are cut into work items
+ * (the two that concern the sorted evaluation also change what eq_workspace_bytes() returns: size
+ * the workspace under the setting the call will run with).
  */
 #ifndef EQ_TESTING_H_
 #define EQ_TESTING_H_
