@@ -14,7 +14,7 @@
 //
 //   sorted_prepare : stages a row as every other kernel does (eq_rowbatch.h: statistics, outlier
 //                    mask, outliers replaced by 0; nothing written to the outlier list here), then
-//                    sorts the 16-bit values in LDS (counting sort into 2048 value-linear buckets,
+//                    sorts the 16-bit values in LDS (counting sort into 4096 or 8192 value-linear buckets,
 //                    ranks inside a bucket by counting) and writes a record per row to the
 //                    workspace: header, then per chunk of 8 sorted values the values and the exact sum of
 //                    everything in front of them.
