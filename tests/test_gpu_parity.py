@@ -194,6 +194,51 @@ def test_sorted_rows_in_chunks_and_rows_it_evaluates_directly(chunk_rows, eq_ove
     assert res["excused_elems"] == 0
 
 
+@pytest.mark.parametrize("seed", [21, 22])
+def test_sorted_and_element_by_element_evaluation_give_the_same_bits(seed, eq_override):
+    """Seeded random shapes, parameters and degenerate rows: the two ways of optimising one range per row,
+    compared with each other on every output array (the oracle is too slow for this many long rows)."""
+    import random
+    rng = random.Random(seed)
+    for case in range(80):
+        dtype = rng.choice(["f16", "f16", "bf16"])
+        cols = 128 * rng.choice([16, 17, 24, 32, 33, 40, 48, 64, 65, 86, 100, 108, 128, 129, 140, 172, 200, 256])
+        recipe = eq_inputs.RECIPES[rng.choice(["c2", "c3", "c5"])]
+        if dtype == "bf16":
+            recipe = eq_inputs.with_dtype(recipe, "bf16")
+        Ws = []
+        for m in range(rng.choice([1, 1, 2, 3])):
+            rows = rng.randint(1, 40 if cols <= 8192 else 12)
+            W = eq_inputs.gen_matrix(rows, cols, recipe, seed=rng.randint(0, 10 ** 6), device=DEV)
+            if rng.random() < 0.2:
+                W[rng.randrange(rows)] = 0
+            if rng.random() < 0.2:
+                W[rng.randrange(rows)] *= rng.choice([1e-3, 30.0, 2000.0 if dtype == "f16" else 1e20])
+            if rng.random() < 0.15:
+                W[rng.randrange(rows), ::rng.choice([2, 3, 5])] = rng.choice([0.0, 0.25, -0.01])
+            if rng.random() < 0.1:
+                W[rng.randrange(rows)] = W[rng.randrange(rows)].abs()
+            if rng.random() < 0.1:
+                W[rng.randrange(rows), rng.randrange(cols)] = rng.choice([6e-8, 1e-12 if dtype == "bf16" else 1e-7])
+            Ws.append(W)
+        p = eqo.Params(dtype=eqo.F16 if dtype == "f16" else eqo.BF16, bits=rng.choice([2, 3, 4, 4]), group_size=rng.choice([0, 0, cols]),
+                       mode=rng.choice([eqo.SYMMETRIC, eqo.ASYMMETRIC]), iters=rng.choice([1, 2, 5, 9, 20, 40, 120]),
+                       n_sigma=rng.choice([3.0, 3.0, 2.5, 2.0, 1.0, 4.0, float("inf")]),
+                       stat_scope=rng.choice([eqo.STAT_ROW, eqo.STAT_ROW, eqo.STAT_MATRIX, eqo.STAT_GROUP]),
+                       select=rng.choice([eqo.SELECT_BEST, eqo.SELECT_LAST]), lr=rng.choice([1e-3, 1e-4, 5e-3, 2e-2]))
+        print(f"[case] sorted vs direct {seed}/{case} {dtype} cols={cols} rows={[w.shape[0] for w in Ws]} {p}", flush=True)
+        eq_override(eqg.OVR_SORT_CHUNK_ROWS, rng.choice([0, 0, 4, 7, 33]))
+        eq_override(eqg.OVR_SORTED_ROWS, 2)
+        _, a = run_gpu(Ws, p)
+        eq_override(eqg.OVR_SORTED_ROWS, 1)
+        _, b = run_gpu(Ws, p)
+        for m in range(len(Ws)):
+            assert a[m]["status"] == b[m]["status"]
+            for k in ("codes", "zero_points", "out_row_ptr", "out_col", "out_val"):
+                assert np.array_equal(a[m][k], b[m][k]), (case, m, k)
+            assert np.array_equal(a[m]["scales"].view(np.uint32), b[m]["scales"].view(np.uint32)), (case, m, "scales")
+
+
 @pytest.mark.parametrize("G", [128, 0])
 def test_bf16_wide_exponent_span_takes_the_binary64_evaluation(G):
     # values far below the block fixed-point resolution of their unit (2^-22 of its largest
