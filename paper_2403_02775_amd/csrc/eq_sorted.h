@@ -368,7 +368,7 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
   int wj0 = 0;                                               // the window holds chunks [wj0, wj0 + kWinChunks)
   bool wvalid = false;
   int pf_shift = 0;                                          // chunks on their way: up to +-kWinFetch towards higher / lower positions
-  int j_last = 0;                                            // chunk of the boundary at the last search
+  int j_last = 0, dj_last = 0;                               // chunk of the boundary at the last search, and its last move
   uint4 pf_q[kWinFetch];
   double pf_P[kWinFetch];
   auto win_q = [&](int c) -> uint4& { return *reinterpret_cast<uint4*>(win + (c & (kWinChunks - 1)) * 16); };
@@ -435,15 +435,19 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
           const float x0 = widen16<DT>(*reinterpret_cast<const uint16_t*>(win + k * 16));   // slot k, some chunk of the window
           c += __builtin_fmaf(x0, inv, kMagic) <= thr ? 1 : 0;
         }
+        // a boundary outside the window is looked for where its last move points, in steps of that size
+        const int ahead = max(1, dj_last < 0 ? -dj_last : dj_last);
         if (c > 0) {
           j = wj0 + c - 1;
           nlo = 8 * j;
           have_lo = true;
           if (c < kWinChunks) { nhi = 8 * j + 8; have_hi = true; }
+          else { j = min(max(j, j_last + dj_last), nblk - 1); d = ahead; }
         } else {
           nhi = 8 * wj0;                                     // P[nhi] = 0 if this is the row's start, else found by the probes
           have_hi = true;
-          j = max(wj0 - 1, 0);
+          j = max(min(wj0 - 1, j_last + dj_last), 0);
+          d = ahead;
           if (wj0 == 0) { n = 0; done = true; }
         }
       }
@@ -493,7 +497,8 @@ __global__ __launch_bounds__(kWave) void sorted_iterate(const MatDesc* __restric
       ia = wA * n;
       db = counts ? Pn : 0.0;
       const int j_now = min(n, N - 1) >> 3;
-      const int j_next = j_now + (t > 0 ? j_now - j_last : 0);
+      dj_last = t > 0 ? j_now - j_last : 0;
+      const int j_next = j_now + dj_last;
       j_last = j_now;
       if (wvalid && !last) {
         // the window's middle goes where the boundary is heading: ask for the next chunks on that side
