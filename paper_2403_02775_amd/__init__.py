@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     EQ_SYMMETRIC, EQ_S_NONFINITE, EQ_S_OUTLIER_OVERFLOW, EasyQuantError, Params, QMatrix, eq_code_words_per_row,
     eq_dequant_matvec, eq_dequantize, eq_outlier_capacity_bound, eq_profile_enable, eq_profile_read, eq_quantize_batch, eq_quantize_matrix, eq_quantize_matrix_noalloc, EQ_STATIC_SCRATCH_BYTES, eq_strerror, eq_workspace_bytes,
     alloc_outputs, lib, lib_path,
-    OVR_CHANNEL_KERNEL, OVR_FORCE_GENERAL, OVR_MATVEC_ARITHMETIC, OVR_MATVEC_LOOKUP, OVR_RTN_THREADS, OVR_UNITS_PER_ITEM, OVR_SORTED_ROWS, OVR_SORT_CHUNK_ROWS, OVR_COUNT,
+    OVR_CHANNEL_KERNEL, OVR_FORCE_GENERAL, OVR_MATVEC_ARITHMETIC, OVR_MATVEC_LOOKUP, OVR_RTN_THREADS, OVR_UNITS_PER_ITEM, OVR_SORTED_ROWS, OVR_SORT_CHUNK_ROWS, OVR_CLASS_STREAMS, OVR_COUNT,
     override, plan_items, plan_sort_segments,
     set_override,
 )

@@ -271,8 +271,8 @@ def eq_dequantize(q: QMatrix, rows: int, cols: int, p: Params, W_out: torch.Tens
 
 # ---- hooks for tests and measurements (csrc/eq_testing.h; not part of the C ABI) ----------------
 (OVR_UNITS_PER_ITEM, OVR_FORCE_GENERAL, OVR_RTN_THREADS, OVR_CHANNEL_KERNEL, OVR_MATVEC_ARITHMETIC, OVR_MATVEC_LOOKUP,
- OVR_SORTED_ROWS, OVR_SORT_CHUNK_ROWS) = range(8)
-OVR_COUNT = 8
+ OVR_SORTED_ROWS, OVR_SORT_CHUNK_ROWS, OVR_CLASS_STREAMS) = range(9)
+OVR_COUNT = 9
 
 
 class override:

@@ -53,8 +53,8 @@ std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
 struct ScopedKernelTimer {
   hipStream_t st;
   hipEvent_t a = nullptr, b = nullptr;
-  explicit ScopedKernelTimer(hipStream_t s) : st(s) {
-    if (!g_profile) return;
+  explicit ScopedKernelTimer(hipStream_t s, bool enabled = true) : st(s) {
+    if (!g_profile || !enabled) return;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
     (void)hipEventRecord(a, st);
   }
@@ -636,9 +636,37 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
   hipStream_t aux = nullptr;
   bool aux_used = false;
   int rc = EQ_OK;
+  // Without optimisation steps the main kernels are bound by memory, the one for long rows (three
+  // wavefronts meeting at barriers) more by its latency than by bandwidth: the row-length classes then
+  // alternate between the caller's stream and the second one, each followed by its own finish, so that
+  // the kernels of two classes can share the chip (65B-shaped set, alternating measurements in one
+  // process: 35.5 instead of 35.7-35.8 ms per step, whichever class goes first; with optimisation
+  // steps the kernels are bound by instruction issue and nothing changes).  Classes of the
+  // sorted evaluation share one region of records and always run one after the other.
+  int busy_classes = 0;
+  bool any_sorted = false;
+  for (const LaneClass& lc : pl.classes) {
+    busy_classes += lc.n_items != 0;
+    any_sorted = any_sorted || lc.sorted;
+  }
+  bool concurrent = false;
+  if (dids && busy_classes >= 2 && !any_sorted && override_of(EQ_OVR_CLASS_STREAMS) != 1 &&
+      (kp.iters == 0 || override_of(EQ_OVR_CLASS_STREAMS) == 2) && aux_stream_of_current_device(&aux) == EQ_OK) {
+    hipEvent_t ev = nullptr;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) {
+      concurrent = hipEventRecord(ev, st) == hipSuccess && hipStreamWaitEvent(aux, ev, 0) == hipSuccess;
+      (void)hipEventDestroy(ev);
+      aux_used = concurrent;
+    }
+  }
+  hipStream_t const caller_stream = st;
+  // side by side the kernels' own durations overlap: one bracket around all of them, up to the join
+  ScopedKernelTimer* whole = concurrent ? new ScopedKernelTimer(caller_stream) : nullptr;
+  size_t launched = 0;
   for (size_t ci = 0; ci < pl.classes.size() && rc == EQ_OK; ++ci) {
     const LaneClass& lc = pl.classes[ci];
     if (lc.n_items == 0) continue;
+    st = (concurrent && (launched++ & 1)) ? aux : caller_stream;
     // the kernels of each family are instantiated in a translation unit of their own (eq_launch.h)
     const LaneKernel lk = (lc.kind == 3 || lc.kind == 6) ? pick_rtn_kernel<DT>(lc)
                           : (lc.kind == 2 || lc.kind == 5 || lc.kind == 7) ? pick_channel_kernel<DT>(lc) : pick_units_kernel<DT>(lc);
@@ -652,7 +680,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
       break;
     }
     {
-      ScopedKernelTimer tm(st);
+      ScopedKernelTimer tm(st, !concurrent);
       KParams kq = kp;
       if (lc.sorted) {
         // chunk by chunk: the records, then Adam on them; the ranges go to MatDesc::range
@@ -679,6 +707,10 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
       launch(lc, dmats, ditems, kq, st);
     }
     if (hipGetLastError() != hipSuccess) { rc = EQ_E_HIP; break; }
+    if (concurrent) {
+      rc = launch_finish(dmats, dids, pl.finish_groups[ci], st);
+      continue;
+    }
     bool more_main = have_general;
     for (size_t cj = ci + 1; cj < pl.classes.size(); ++cj) more_main = more_main || pl.classes[cj].n_items != 0;
     hipEvent_t ev = nullptr;
@@ -694,6 +726,22 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
     }
     rc = launch_finish(dmats, dids, pl.finish_groups[ci], st);
   }
+  st = caller_stream;
+  auto join_aux = [&] {
+    // whatever went to the second stream is part of this call: the caller's stream waits for it
+    hipEvent_t ev = nullptr;
+    bool joined = false;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) {
+      joined = hipEventRecord(ev, aux) == hipSuccess && hipStreamWaitEvent(st, ev, 0) == hipSuccess;
+      (void)hipEventDestroy(ev);
+    }
+    if (!joined) (void)hipStreamSynchronize(aux);          // no event: wait on the host instead
+    aux_used = false;
+  };
+  if (concurrent) {
+    join_aux();
+    delete whole;                                          // closes the bracket on the caller's stream, behind the join
+  }
   if (rc == EQ_OK && gen_rows > 0) {
     const size_t lds = 256 + (size_t)gen_cols * 2 + (size_t)gen_cols / 8;
     if (lds > 65536 && hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_rows_generic<DT>),
@@ -708,18 +756,7 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
     }
   }
   if (rc == EQ_OK) rc = launch_finish(dmats, dids, pl.finish_groups.back(), st);
-  // whatever went to the second stream is part of this call: the caller's stream waits for it
-  if (aux_used) {
-    hipEvent_t ev = nullptr;
-    bool joined = false;
-    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) {
-      joined = hipEventRecord(ev, aux) == hipSuccess && hipStreamWaitEvent(st, ev, 0) == hipSuccess;
-      (void)hipEventDestroy(ev);
-    }
-    if (!joined) {
-      (void)hipStreamSynchronize(aux);                 // no event: wait on the host instead
-    }
-  }
+  if (aux_used) join_aux();
   return rc;
 }
 

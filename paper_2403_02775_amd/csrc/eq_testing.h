@@ -34,7 +34,10 @@ enum {
                                 steps (default: when steps x columns >= 800 000) */
   EQ_OVR_SORT_CHUNK_ROWS = 7, /* n > 0: at most n rows (rounded down to a multiple of 4) per chunk of the sorted
                                  evaluation, instead of as many as 2 GiB of records hold */
-  EQ_OVR_COUNT = 8
+  EQ_OVR_CLASS_STREAMS = 8,  /* the row-length classes of a batch alternate between the caller's stream and the
+                                library's second one, so that their main kernels run side by side: 1 = never,
+                                2 = whenever the batch has two classes (default: without optimisation steps) */
+  EQ_OVR_COUNT = 9
 };
 EQ_API int eq_test_set_override(int which, int64_t value);   /* EQ_OK or EQ_E_PARAM */
 

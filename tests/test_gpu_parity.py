@@ -625,6 +625,27 @@ def test_batch_of_mixed_shapes_matches_single_calls_and_is_deterministic():
                 assert np.array_equal(a[k], single[0][k]), k
 
 
+@pytest.mark.parametrize("streams", [0, 1, 2])
+def test_row_length_classes_side_by_side_on_two_streams(streams, eq_override):
+    """A batch whose matrices fall into four row-length classes: the classes' kernels one after the other on
+    the caller's stream (1), alternating with the library's second stream (2), or as the library chooses
+    (side by side without optimisation steps).  Same bits as matrix-by-matrix calls, run after run."""
+    eq_override(eqg.OVR_CLASS_STREAMS, streams)
+    rec = eq_inputs.RECIPES["c5"]
+    shapes = [(300, 1024), (64, 4096), (200, 2816), (37, 8192), (150, 1024), (90, 4096), (5, 22016)]
+    Ws = [eq_inputs.gen_matrix(r, c, rec, seed=70 + i, device=DEV) for i, (r, c) in enumerate(shapes)]
+    for p in (eqo.Params(bits=4, group_size=128, iters=0), eqo.Params(bits=4, group_size=0, iters=0),
+              eqo.Params(bits=3, group_size=128, iters=4)):
+        print(f"[case] classes on streams={streams} G={p.group_size} T={p.iters}", flush=True)
+        runs = [run_gpu(Ws, p)[1] for _ in range(3)]
+        for W, a, b, c in zip(Ws, *runs):
+            _, single = run_gpu([W], p, batch=False)
+            for k in a:
+                assert np.array_equal(a[k], b[k]) and np.array_equal(a[k], c[k]) and np.array_equal(a[k], single[0][k]), k
+        res = compare(raw_of(Ws[3]), runs[0][3], eqo.quantize_matrix(raw_of(Ws[3]), p), p, "classes on streams")
+        assert res["excused_elems"] == 0
+
+
 def test_per_channel_batch_spans_three_kernels():
     # one call, one range per row: rows for the per-channel lane kernel (two row lengths, i.e. two
     # launches), rows too short for it (general kernel), and an empty matrix
