@@ -164,6 +164,7 @@ struct Plan {
 // chunks of at most this many bytes (some 87 000 rows of 8192 elements: enough wavefronts of
 // sorted_iterate to fill the chip several times over).
 constexpr size_t kSortBudgetBytes = (size_t)2 << 30;
+constexpr int64_t kSideItems = 160;               // work items of the long-row class when it runs beside the others (T = 0)
 constexpr int64_t kSortMinCols = 2048;
 constexpr int64_t kSortMinWork = 800000;         // steps x columns from which rows are optimised from their sorted values
 
@@ -219,6 +220,23 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     }
   }
   std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return cols[a] < cols[b]; });
+  // Without optimisation steps the row-length classes of a batch run side by side on two streams
+  // (launch_all).  The kernel for the longest rows, when it is the multi-wavefront one and holds a minor
+  // share of the elements, is then started first with FEW, LONG work items (kSideItems workgroups in all),
+  // so that it keeps about one workgroup on every other compute unit for the whole step instead of taking
+  // the chip for itself at the end, where it runs at 48 % of the memory bandwidth: on the 65B-shaped set
+  // 34.35 instead of 35.55 ms per step (alternating measurements in one process; 160 to 420 items: 34.35 to
+  // 34.55 ms, 1000 and more: no gain).
+  int64_t all_elems = 0, longest_cols = 0, longest_elems = 0;
+  size_t distinct = 0;
+  for (size_t k = 0; k < order.size(); ++k) {
+    const int64_t c = cols[order[k]];
+    if (k == 0 || c != cols[order[k - 1]]) { ++distinct; longest_cols = c; longest_elems = 0; }
+    all_elems += rows[order[k]] * c;
+    longest_elems += rows[order[k]] * c;
+  }
+  const bool side_by_side = p->iters == 0 && distinct >= 2 && override_of(EQ_OVR_CLASS_STREAMS) != 1;
+  const bool few_long_items = side_by_side && longest_cols > 8192 && longest_elems * 20 <= all_elems * 7;   // at most 35 %
   for (size_t k = 0; k < order.size();) {
     size_t e = k;
     int64_t total_units = 0;
@@ -341,6 +359,7 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
       // sets against items 2, 4 and 8 times as large: 4 % and 8 % faster)
       int64_t target = std::min<int64_t>(8192, std::max<int64_t>(2048, total_units / 32768));
       if (override_of(EQ_OVR_UNITS_PER_ITEM) > 0) target = override_of(EQ_OVR_UNITS_PER_ITEM);
+      if (few_long_items && c == longest_cols && override_of(EQ_OVR_UNITS_PER_ITEM) <= 0) target = std::max<int64_t>(target, total_units / kSideItems);
       int64_t rpi = std::max<int64_t>(rpb, target / upr);
       rpi -= rpi % rpb;
       lc.first_item = pl.work.size();
@@ -639,9 +658,9 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
   // Without optimisation steps the main kernels are bound by memory, the one for long rows (three
   // wavefronts meeting at barriers) more by its latency than by bandwidth: the row-length classes then
   // alternate between the caller's stream and the second one, each followed by its own finish, so that
-  // the kernels of two classes can share the chip (65B-shaped set, alternating measurements in one
-  // process: 35.5 instead of 35.7-35.8 ms per step, whichever class goes first; with optimisation
-  // steps the kernels are bound by instruction issue and nothing changes).  Classes of the
+  // the kernels of two classes share the chip, the longest rows first and in few, long work items
+  // (make_plan; with optimisation steps the kernels are bound by instruction issue and nothing
+  // changes).  Classes of the
   // sorted evaluation share one region of records and always run one after the other.
   int busy_classes = 0;
   bool any_sorted = false;
@@ -663,7 +682,9 @@ int launch_all(int32_t n, const MatDesc* dmats, const WorkItem* ditems, const in
   // side by side the kernels' own durations overlap: one bracket around all of them, up to the join
   ScopedKernelTimer* whole = concurrent ? new ScopedKernelTimer(caller_stream) : nullptr;
   size_t launched = 0;
-  for (size_t ci = 0; ci < pl.classes.size() && rc == EQ_OK; ++ci) {
+  // side by side: the longest rows first (see make_plan)
+  for (size_t cii = 0; cii < pl.classes.size() && rc == EQ_OK; ++cii) {
+    const size_t ci = concurrent ? pl.classes.size() - 1 - cii : cii;
     const LaneClass& lc = pl.classes[ci];
     if (lc.n_items == 0) continue;
     st = (concurrent && (launched++ & 1)) ? aux : caller_stream;
