@@ -261,6 +261,9 @@ def main():
     ap.add_argument("--channel-evaluation", choices=["auto", "direct", "sorted"], default="auto",
                     help="rows with one range each (--group-size 0): element-by-element kernels, or the evaluation from sorted rows "
                          "(auto: the library's choice, sorted when steps x columns >= 800 000)")
+    ap.add_argument("--class-streams", choices=["auto", "sequential"], default="auto",
+                    help="sequential: the row-length classes of a batch one after the other also without optimisation steps "
+                         "(auto: side by side then), so that per-kernel counters and durations do not overlap")
     ap.add_argument("--stat-scope", choices=["row", "matrix"], default="row",
                     help="scope of mean / sigma in the outlier criterion; matrix = Eq. 3 as printed (secondary measurement)")
     ap.add_argument("--select", choices=["best", "last"], default="best",
@@ -322,6 +325,11 @@ def main():
                       ("T=500, lr=1e-4 (the paper's LLaMA setting)", 500, 128, 1e-4),
                       ("per channel, T=100 (the paper's granularity)", 100, 0, args.lr),
                       ("per channel, T=500, lr=1e-4 (the paper's LLaMA setting at its granularity)", 500, 0, 1e-4)]
+    # test hooks of the library: same results, other kernels (set before the workspace is sized: it depends on them)
+    if args.class_streams == "sequential":
+        eqg.set_override(eqg.OVR_CLASS_STREAMS, 1)
+    if args.channel_evaluation != "auto":
+        eqg.set_override(eqg.OVR_SORTED_ROWS, 1 if args.channel_evaluation == "direct" else 2)
     caps = [int(w.numel() * args.capacity_frac) for w in Ws]
     outs = [eqg.alloc_outputs(w.shape[0], w.shape[1], gp, c, dev) for w, c in zip(Ws, caps)]
     shape_r, shape_c = [w.shape[0] for w in Ws], [w.shape[1] for w in Ws]
@@ -339,9 +347,6 @@ def main():
         torch.cuda.synchronize()
         log("[calibration] copied 4 GiB (reads 4 GiB, writes 4 GiB)")
         del src, dst
-
-    if args.channel_evaluation != "auto":            # a test hook of the library: same results, other kernels
-        eqg.set_override(eqg.OVR_SORTED_ROWS, 1 if args.channel_evaluation == "direct" else 2)
 
     def kernel_name(q):
         # one range per row, at most 4 bits, steps x columns >= 800 000: Adam runs on the sorted rows
