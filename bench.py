@@ -363,7 +363,8 @@ def main():
         for i in range(warmup):
             eqg.eq_quantize_batch(Ws, q, q_outs, ws)
             torch.cuda.synchronize()
-            log(f"[warmup] {label} {i + 1}/{warmup}")
+            if warmup <= 5 or (i + 1) % 10 == 0:
+                log(f"[warmup] {label} {i + 1}/{warmup}")
         eqg.eq_profile_enable(True)
         eqg.eq_profile_read()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -461,9 +462,9 @@ def main():
                                              out_row_ptr=o.out_row_ptr, out_col=o.out_col, out_val=o.out_val, status=o.status)
                                  for o, w in zip(outs, Ws)]
                 q_outs = chan_outs
-            # short steps need more of them: the first few calls of a configuration run a few percent
+            # short steps need more of them: the first second or so of a configuration runs a few percent
             # slower than the steady state (clocks, address translation of 180 GB of buffers)
-            n_steps, n_warm = (10 * args.sweep_steps, 5) if iters <= 10 else (args.sweep_steps, 1)
+            n_steps, n_warm = (10 * args.sweep_steps, 30 if iters == 0 else 10) if iters <= 10 else (args.sweep_steps, 1)
             r = timed(q, q_outs, n_steps, n_warm, label)
             sweep.append({"config": label, "iters": iters, "group_size": group, "lr": lr, "steps": n_steps, "warmup": n_warm,
                           "ms_per_step": r["ms_per_step"], "seconds_per_model": r["ms_per_step"] * 1e-3,

@@ -637,7 +637,16 @@ def test_row_length_classes_side_by_side_on_two_streams(streams, eq_override):
     for p in (eqo.Params(bits=4, group_size=128, iters=0), eqo.Params(bits=4, group_size=0, iters=0),
               eqo.Params(bits=3, group_size=128, iters=4)):
         print(f"[case] classes on streams={streams} G={p.group_size} T={p.iters}", flush=True)
-        runs = [run_gpu(Ws, p)[1] for _ in range(3)]
+        runs = [run_gpu(Ws, p)[1] for _ in range(2)]
+        eqg.eq_profile_enable(True)                     # the event brackets around the main kernels change nothing
+        try:
+            eqg.eq_profile_read()
+            runs.append(run_gpu(Ws, p)[1])
+            ms, brackets = eqg.eq_profile_read()
+        finally:
+            eqg.eq_profile_enable(False)
+        side_by_side = streams == 2 or (streams == 0 and p.iters == 0)
+        assert ms > 0.0 and (brackets == 1 + (p.group_size == 0) if side_by_side else brackets >= 4)
         for W, a, b, c in zip(Ws, *runs):
             _, single = run_gpu([W], p, batch=False)
             for k in a:
