@@ -43,11 +43,12 @@ constexpr int kQueue = 128;          // candidate chunks a wavefront can queue p
 template <int RB, int NW>
 struct BatchScratch {
   float part[RB][NW][2];             // per wavefront: sum x, sum x^2 of each row
-  double dred[kMaxWaves];
+  static constexpr int kW = NW > kMaxWaves ? NW : kMaxWaves;   // (kMaxWaves entries for every workgroup of up to 512 threads)
+  double dred[kW];
   double mu[RB], thr[RB];            // exact mean and n*sigma of the rows that were redone
   float4 fast[RB];                   // fast mean, lower and upper end of the band around n*sigma
   unsigned long long base;           // start of the batch's run of the staging list
-  uint32_t wtot[kMaxWaves];          // outliers found by each wavefront's units
+  uint32_t wtot[kW];                 // outliers found by each wavefront's units
   uint32_t slow[RB];                 // row takes the exact path
   uint32_t rowmax_bits[RB];          // for kernels with one range per row: bit patterns of max(x, 0) and
   uint32_t rownegmin_bits[RB];       // max(-x, 0) over the row's normal values

@@ -18,7 +18,7 @@ template <int DT>
 SortKernels pick_sorted_kernels(const LaneClass& lc) {
   SortKernels k;
   const int64_t nchunks = (int64_t)lc.cols / 8;
-  const int nt = lc.cols <= 8192 ? 256 : 512;
+  const int nt = lc.cols <= 8192 ? 256 : 1024;
   const int64_t per_thread = (nchunks + nt - 1) / nt;
 #define EQ_SORT_VARIANT(NT_, K_, NB_)                                                                                  \
   {                                                                                                                  \
@@ -35,8 +35,8 @@ SortKernels pick_sorted_kernels(const LaneClass& lc) {
     else if (per_thread <= 2) EQ_SORT_VARIANT(256, 2, 4096)
     else EQ_SORT_VARIANT(256, 4, 4096)
   } else {
-    if (per_thread <= 4) EQ_SORT_VARIANT(512, 4, 8192)
-    else if (per_thread <= 8) EQ_SORT_VARIANT(512, 8, 8192)
+    if (per_thread <= 2) EQ_SORT_VARIANT(1024, 2, 8192)
+    else EQ_SORT_VARIANT(1024, 4, 8192)
   }
 #undef EQ_SORT_VARIANT
   k.iterate = [](const LaneClass&, const SortLaunchArgs& a, const KParams& kp, hipStream_t s) {
