@@ -132,8 +132,9 @@ typedef struct eq_qmatrix {
  * one unit per lane (without optimisation steps, iters == 0, a load-pipelined variant of it);
  * one range per row with cols a multiple of 128 in 2048..32768 spreads the row over
  * cols / 128 lanes (rows of 11008, 13824, 17920 or 22016 columns with 4-bit codes: in
- * equal pieces over 128 or 256 lanes; with at most 4 bits and iters * cols >= 800 000 (bf16:
- * 1 600 000) the rows are sorted first and every step takes its two sums from the sorted row and its exact prefix
+ * equal pieces over 128 or 256 lanes; with at most 4 bits and iters * (cols - 960) >= 57 * cols
+ * (60 to 65 steps for rows of 8192 and longer, 108 for rows of 2048; bf16: 80 in place of 57) the rows
+ * are sorted first and every step takes its two sums from the sorted row and its exact prefix
  * sums, which needs up to 2 GiB more workspace, counted by eq_workspace_bytes()); everything
  * else goes to a general kernel (one workgroup per row, one wavefront per unit). */
 EQ_API int eq_quantize_matrix(const void* W, int64_t rows, int64_t cols, int64_t ld,

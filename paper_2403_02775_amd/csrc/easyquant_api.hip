@@ -173,7 +173,12 @@ struct Plan {
 constexpr size_t kSortBudgetBytes = (size_t)2 << 30;
 constexpr int64_t kSideItems = 160;               // work items of the long-row class when it runs beside the others (T = 0)
 constexpr int64_t kSortMinCols = 2048;
-constexpr int64_t kSortMinWork = 800000;         // steps x columns from which rows are optimised from their sorted values
+// Rows are optimised from their sorted values when steps x (columns - kSortStepCols) >= kSortPasses x columns:
+// sorting a row costs as much as kSortPasses direct evaluations of it, a step from the sorted row as much as
+// a direct evaluation of kSortStepCols elements whatever the row's length.
+constexpr int64_t kSortPasses = 57;               // (bf16: kSortPassesBf16; its staging, done twice on this route, is the slower one)
+constexpr int64_t kSortPassesBf16 = 80;
+constexpr int64_t kSortStepCols = 960;
 
 int64_t clamp_capacity(int64_t c) { return c < 0 ? 0 : (c > 0xFFFFFFFEll ? 0xFFFFFFFEll : c); }
 
@@ -256,14 +261,13 @@ Plan make_plan(int32_t n, const int64_t* rows, const int64_t* cols, const int64_
     const bool chan_keep128 = override_of(EQ_OVR_CHANNEL_KERNEL) == 128;
     // one range per row, at most 4 bits, optimisation steps: Adam runs on the sorted rows (eq_sorted.h)
     // and the kernel without optimisation steps emits at the ranges it leaves
-    // (sorting costs about as much as 60 to 90 direct evaluations of the row; a step from the sorted row
-    // costs the same whatever the row's length, a sixth to a half of a direct pass over 8192 elements
-    // depending on how far a step moves the range: worth it from steps x columns = 800 000 on, i.e.
-    // 98 steps for rows of 8192, 37 for rows of 22016, 196 for rows of 4096; twice that for bf16, whose
-    // staging, done twice on this route, is the slower one: measured on the 7B-shaped bf16 set)
+    // (measured on the 65B-shaped set at lr = 1e-3, each row length by itself: the two evaluations take the
+    // same time at 55 steps for rows of 22016 and at 60 for rows of 8192; the rule adds 8 % to that: 60 and 65
+    // steps, 75 for rows of 4096, 108 for rows of 2048; for bf16 1.4 times as many: on the 7B-shaped bf16 set
+    // the two take the same time at 80 steps for rows of 4096 and at 89 for rows of 11008)
     const bool chan_sorted = pl.path[(size_t)order[k]] == 2 && p->bits <= 4 && allow_sorted && !chan_keep128 &&
                              c >= kSortMinCols && override_of(EQ_OVR_SORTED_ROWS) != 1 &&
-                             ((int64_t)p->iters * c >= kSortMinWork * (p->dtype == EQ_BF16 ? 2 : 1) ||
+                             ((int64_t)p->iters * (c - kSortStepCols) >= (p->dtype == EQ_BF16 ? kSortPassesBf16 : kSortPasses) * c ||
                               (p->iters > 0 && override_of(EQ_OVR_SORTED_ROWS) == 2));
     const bool chan_rtn = pl.path[(size_t)order[k]] == 2 && (p->iters == 0 || chan_sorted) && !chan_keep128;
     if (pl.path[(size_t)order[k]] == 2 && !chan_rtn) {

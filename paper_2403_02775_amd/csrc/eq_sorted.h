@@ -32,7 +32,7 @@
 
 namespace eq {
 
-constexpr int kSortThreads = 256;              // workgroup of sorted_prepare for rows of up to 8192 elements (1024 beyond)
+constexpr int kSortThreads = 256;              // workgroup of sorted_prepare for rows of up to 8192 elements (512 or 1024 beyond)
 // NB value-linear buckets (+2: zero has a bucket of its own): 4096 for rows of up to 8192 elements,
 // 8192 beyond.  16-bit counters, two to a word (a row has at most 32768 elements).
 constexpr int sort_counters(int nb) { return nb + 16; }
@@ -80,11 +80,12 @@ __device__ __forceinline__ int find_seg_by_row(const SortSeg* __restrict__ segs,
   return lo;
 }
 
-// NT threads (256 for rows of up to 8192 elements, three workgroups per compute unit; 1024 beyond, one),
+// NT threads (256 for rows of up to 8192 elements, three workgroups per compute unit; 512 or 1024 beyond),
 // K 16-byte chunks of the row per thread.  A workgroup walks through rows j, j + G, j + 2 G, ... of the
 // launch, the loads of its next row in flight while it sorts this one.
 // Wavefronts per SIMD the kernel is compiled for: what its LDS lets a compute unit hold (three
-// 256-thread workgroups; one 1024-thread workgroup for longer rows: every phase of the sort waits on
+// 256-thread workgroups; two 512-thread ones for rows of up to some 14 000 elements; one 1024-thread
+// workgroup for longer rows: every phase of the sort waits on
 // LDS round trips, and four wavefronts per SIMD hide them better than the two of a 512-thread
 // workgroup with twice the registers, 18 % less time on rows of 22016).
 template <int NT, int K>

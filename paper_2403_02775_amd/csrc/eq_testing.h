@@ -31,7 +31,7 @@ enum {
                                 2 = all from the table of single values (default: all from the table of pairs) */
   EQ_OVR_SORTED_ROWS = 6,    /* rows with one range each and at most 4 bits: 1 = always optimised element by element
                                 (the per-channel lane kernels), 2 = from their sorted values whatever the number of
-                                steps (default: when steps x columns >= 800 000) */
+                                steps (default: when steps x (columns - 960) >= 57 x columns) */
   EQ_OVR_SORT_CHUNK_ROWS = 7, /* n > 0: at most n rows (rounded down to a multiple of 4) per chunk of the sorted
                                  evaluation, instead of as many as 2 GiB of records hold */
   EQ_OVR_CLASS_STREAMS = 8,  /* the row-length classes of a batch alternate between the caller's stream and the

@@ -18,7 +18,10 @@ template <int DT>
 SortKernels pick_sorted_kernels(const LaneClass& lc) {
   SortKernels k;
   const int64_t nchunks = (int64_t)lc.cols / 8;
-  const int nt = lc.cols <= 8192 ? 256 : 1024;
+  // rows of which two fit the LDS of a compute unit (up to some 14 000 elements): 512 threads, two
+  // workgroups; longer ones: 1024 threads, one workgroup; four wavefronts per SIMD either way
+  const bool two_fit = lc.cols <= 16384 && 2 * sort_prepare_lds(sort_header_bytes<512>(), lc.cols, 8192) <= 160u * 1024u - 128u;
+  const int nt = lc.cols <= 8192 ? 256 : two_fit ? 512 : 1024;
   const int64_t per_thread = (nchunks + nt - 1) / nt;
 #define EQ_SORT_VARIANT(NT_, K_, NB_)                                                                                  \
   {                                                                                                                  \
@@ -34,6 +37,8 @@ SortKernels pick_sorted_kernels(const LaneClass& lc) {
     if (per_thread <= 1) EQ_SORT_VARIANT(256, 1, 4096)
     else if (per_thread <= 2) EQ_SORT_VARIANT(256, 2, 4096)
     else EQ_SORT_VARIANT(256, 4, 4096)
+  } else if (nt == 512) {
+    EQ_SORT_VARIANT(512, 4, 8192)
   } else {
     if (per_thread <= 2) EQ_SORT_VARIANT(1024, 2, 8192)
     else EQ_SORT_VARIANT(1024, 4, 8192)

@@ -131,10 +131,14 @@ def test_sorted_evaluation_chunks_cover_their_rows_and_fit_the_record_region(lib
                 ngroups += (nr + 3) // 4
             assert nrows * rb <= region
             assert nrows <= max(4, limit // 4 * 4)
-    # rows of 8192 from 98 steps on, rows of 2048 from 391
-    assert {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, iters=98))[0]} == {8192, 22016}
-    assert {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, iters=97))[0]} == {22016}
-    assert {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, iters=391))[0]} == {2048, 4096, 8192, 22016}
+    # rows of 22016 from 60 steps on, rows of 8192 from 65, rows of 4096 from 75, rows of 2048 from 108; bf16 1.4 times as many
+    def sorted_cols(**kw):
+        return {cols[m] for _, m, *_ in eqg.plan_sort_segments(rows, cols, caps, eqg.Params(group_size=0, **kw))[0]}
+    assert sorted_cols(iters=59) == set() and sorted_cols(iters=60) == {22016} and sorted_cols(iters=64) == {22016}
+    assert sorted_cols(iters=65) == {8192, 22016} and sorted_cols(iters=74) == {8192, 22016}
+    assert sorted_cols(iters=75) == {4096, 8192, 22016} and sorted_cols(iters=107) == {4096, 8192, 22016}
+    assert sorted_cols(iters=108) == {2048, 4096, 8192, 22016}
+    assert sorted_cols(iters=83, dtype=eqg.EQ_BF16) == set() and sorted_cols(iters=91, dtype=eqg.EQ_BF16) == {8192, 22016}
     # few steps, wide codes or short rows: no sorted evaluation
     for p in (eqg.Params(group_size=0, iters=10), eqg.Params(group_size=0, iters=100, bits=8), eqg.Params(group_size=128, iters=100)):
         assert eqg.plan_sort_segments(rows, cols, caps, p)[0] == []
