@@ -182,7 +182,8 @@ def test_sorted_rows_in_chunks_and_rows_it_evaluates_directly(chunk_rows, eq_ove
             assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
     if chunk_rows == 0:
         # statistics of the whole matrix (every row decided by the exact path) at each number of chunks per thread
-        for rows, cols in ((4, 2048), (5, 4096), (3, 8192), (3, 11008), (2, 22016)):
+        # (rows of up to 8192: 256 threads; while two rows fit the LDS: 512; beyond: 1024, up to the longest rows)
+        for rows, cols in ((4, 2048), (5, 4096), (3, 8192), (3, 11008), (2, 13824), (2, 16384), (2, 22016), (2, 32768)):
             Wm = eq_inputs.gen_matrix(rows, cols, eq_inputs.RECIPES["c5"], seed=cols, device=DEV)
             res = _check(Wm, eqo.Params(bits=4, group_size=0, iters=3, stat_scope=eqo.STAT_MATRIX), f"sorted rows matrix scope {cols}", deq=False)
             assert res["excused_elems"] == 0 and res["scale_exact"] == res["units"]
